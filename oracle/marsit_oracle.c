@@ -1,0 +1,356 @@
+/*
+ * marsit_oracle.c -- plain CPU oracle for the one-bit synchronisation pass of Marsit
+ * ("Sign Bit is Enough", arXiv 2204.06787).
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  It is the slow, by-eye-checkable statement of what the
+ * hot path computes.  Only the tests, the smoke check and the benchmark's cpu_baseline leg may
+ * call it.  It shares no code, header, table or constant generator with the HIP library; the
+ * product never routes through it.
+ *
+ * What it follows
+ *   - Algorithm 1, lines 1-2 and 4-10 (the branch mod(t,K) != 0): compensated gradient,
+ *     split into M parts, per-part chain of "sign, merge, send", decode, global compensation.
+ *   - Eq. 2 of Section 4.1.1: the transient Bernoulli vector v.
+ *   - The operator  v_i (.) v_i* = (v_i AND v_i*) OR ((v_i XOR v_i*) AND v)  of Section 4.1.1.
+ *   - Algorithm 1, lines 11-13 (the branch mod(t,K) == 0): full-precision mean, c <- 0.
+ *   - Algorithm 2, line 6: x <- x - g_t.
+ *
+ * Readings taken where the paper is silent (each is listed in the design notes of the build):
+ *   - "m" in Eq. 2 is the fold count: how many workers' signs the outgoing vector will stand
+ *     for, the local one included.  Hop h of a chain (h = 1..M-1) has m = h + 1.
+ *   - bit 1 means +1.  sgn() is the complement of the IEEE-754 sign bit (+0 -> +1, -0 -> -1).
+ *   - Bernoulli draws: one 32-bit word u per (seed, hop, packed word, bit);
+ *       keep-local indicator t = (u < floor(2^32 / m)),  v = XNOR(v*, t)   (that is Eq. 2).
+ *     u is the j-th 32-bit output of the Philox4x32-10 stream with key = the 64-bit seed and
+ *     counter = (j / 4, hop id, word index low, word index high); j = bit position 0..63.
+ *   - Packing: element e sits in 64-bit word e / 64 at bit e % 64 (least significant first);
+ *     bits at positions >= d are zero.
+ *   - Split into parts: word-aligned, part i = words [floor(i*W/P), floor((i+1)*W/P)).
+ *   - Ring: part i starts at worker i; hop h folds in worker (i + h) mod M.
+ *   - 2D torus, X columns by Y rows, worker (y, x) = y*X + x: rows first (ring over the X
+ *     columns inside every row, parts = X row-parts of the W words), then columns (ring over
+ *     the Y row results, every row-part split again in Y sub-parts).
+ *   - Arithmetic type: the gradients and the compensation are fp32 vectors (Section 1 speaks
+ *     of 32-bit single precision), so line 1 and line 10 are one fp32 round-to-nearest-even
+ *     operation each.  Build with -ffp-contract=off and without fast-math.
+ *
+ * Parity status: the building blocks are pinned by tests (exact enumeration of the
+ * unbiasedness property, binomial frequency tests, identity cases, an independently written
+ * second formulation, numpy reductions, Philox known answers).  The specific merged bitmaps
+ * for a given seed have no published worked example: "parity unpinned" beyond those pins.
+ */
+
+#include <stdint.h>
+#include <stddef.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORACLE_MAX_WORKERS 64
+
+/* ------------------------------------------------------------------------------------------
+ * Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3",
+ * SC'11).  Four 32-bit counter words, two 32-bit key words, ten rounds.  The key is bumped by
+ * the two Weyl constants before every round but the first.
+ * ---------------------------------------------------------------------------------------- */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    const uint32_t mult_a = 0xD2511F53u;   /* multiplies counter word 0 */
+    const uint32_t mult_b = 0xCD9E8D57u;   /* multiplies counter word 2 */
+    const uint32_t weyl_a = 0x9E3779B9u;   /* golden ratio               */
+    const uint32_t weyl_b = 0xBB67AE85u;   /* sqrt(3) - 1                */
+
+    uint32_t x0 = ctr[0], x1 = ctr[1], x2 = ctr[2], x3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) {
+            k0 += weyl_a;
+            k1 += weyl_b;
+        }
+        uint64_t prod_a = (uint64_t)mult_a * (uint64_t)x0;
+        uint64_t prod_b = (uint64_t)mult_b * (uint64_t)x2;
+        uint32_t hi_a = (uint32_t)(prod_a >> 32), lo_a = (uint32_t)prod_a;
+        uint32_t hi_b = (uint32_t)(prod_b >> 32), lo_b = (uint32_t)prod_b;
+        uint32_t y0 = hi_b ^ x1 ^ k0;
+        uint32_t y1 = lo_b;
+        uint32_t y2 = hi_a ^ x3 ^ k1;
+        uint32_t y3 = lo_a;
+        x0 = y0; x1 = y1; x2 = y2; x3 = y3;
+    }
+    out[0] = x0; out[1] = x1; out[2] = x2; out[3] = x3;
+}
+
+/* The j-th 32-bit word (j = 0..63) of the stream that belongs to (seed, hop id, word index). */
+uint32_t oracle_stream_u32(uint64_t seed, uint32_t hop_id, uint64_t word_index, uint32_t j)
+{
+    uint32_t ctr[4], key[2], out[4];
+    ctr[0] = j / 4u;
+    ctr[1] = hop_id;
+    ctr[2] = (uint32_t)(word_index & 0xFFFFFFFFu);
+    ctr[3] = (uint32_t)(word_index >> 32);
+    key[0] = (uint32_t)(seed & 0xFFFFFFFFu);
+    key[1] = (uint32_t)(seed >> 32);
+    oracle_philox4x32_10(ctr, key, out);
+    return out[j % 4u];
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Algorithm 1, line 1:  g <- g + c   (elementwise, fp32).
+ * ---------------------------------------------------------------------------------------- */
+void oracle_add_compensation(const float *g, const float *c, float *s, uint64_t d)
+{
+    for (uint64_t e = 0; e < d; ++e) {
+        float ce = (c != NULL) ? c[e] : 0.0f;
+        s[e] = g[e] + ce;                        /* one rounding to fp32 */
+    }
+}
+
+/* sgn() of one fp32 value as a bit: 1 for +, 0 for -, decided by the IEEE-754 sign bit. */
+static unsigned sign_bit_plus(float x)
+{
+    uint32_t raw;
+    memcpy(&raw, &x, sizeof raw);
+    return (raw >> 31) ? 0u : 1u;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Algorithm 1, line 5:  v* <- sgn(g_part), stored one bit per element.
+ * bits has ceil(d/64) words; positions >= d stay 0.
+ * ---------------------------------------------------------------------------------------- */
+void oracle_sign_pack(const float *s, uint64_t *bits, uint64_t d)
+{
+    uint64_t n_words = (d + 63u) / 64u;
+    for (uint64_t w = 0; w < n_words; ++w)
+        bits[w] = 0;
+    for (uint64_t e = 0; e < d; ++e) {
+        if (sign_bit_plus(s[e]))
+            bits[e / 64u] |= (uint64_t)1 << (e % 64u);
+    }
+}
+
+/* Inverse of the packing: out[e] = +1.0f or -1.0f. */
+void oracle_sign_unpack(const uint64_t *bits, float *out, uint64_t d)
+{
+    for (uint64_t e = 0; e < d; ++e)
+        out[e] = ((bits[e / 64u] >> (e % 64u)) & 1u) ? 1.0f : -1.0f;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Eq. 2: the transient vector for one packed word, given the local sign word v*, the fold
+ * count m and the 64 "keep local" outcomes t (bit j of keep: the Bernoulli(1/m) draw of bit j
+ * came up).   b_j = (m-1)/m if v*_j = 0,  1/m if v*_j = 1   <=>   v_j = NOT (v*_j XOR t_j).
+ * ---------------------------------------------------------------------------------------- */
+uint64_t oracle_transient_from_keep(uint64_t local, uint64_t keep)
+{
+    uint64_t v = 0;
+    for (unsigned j = 0; j < 64; ++j) {
+        unsigned l = (unsigned)((local >> j) & 1u);
+        unsigned t = (unsigned)((keep >> j) & 1u);
+        unsigned vj = (l == 1u) ? t : (1u - t);     /* P(v=1) = 1/m when v*=1, (m-1)/m when v*=0 */
+        v |= (uint64_t)vj << j;
+    }
+    return v;
+}
+
+/* The 64 Bernoulli(1/m) outcomes of (seed, hop id, word): t_j = (u_j < floor(2^32/m)). */
+uint64_t oracle_keep_mask(uint32_t fold, uint32_t hop_id, uint64_t seed, uint64_t word_index)
+{
+    uint64_t threshold = ((uint64_t)1 << 32) / (uint64_t)fold;   /* 2^32 when fold == 1 */
+    uint64_t keep = 0;
+    for (unsigned j = 0; j < 64; ++j) {
+        uint64_t u = oracle_stream_u32(seed, hop_id, word_index, j);
+        if (u < threshold)
+            keep |= (uint64_t)1 << j;
+    }
+    return keep;
+}
+
+/* The operator of Section 4.1.1:  (recv AND local) OR ((recv XOR local) AND v). */
+uint64_t oracle_odot(uint64_t recv, uint64_t local, uint64_t v)
+{
+    return (recv & local) | ((recv ^ local) & v);
+}
+
+/* One hop for one packed word: draw v by Eq. 2, then apply the operator. */
+uint64_t oracle_merge_word(uint64_t recv, uint64_t local, uint32_t fold, uint32_t hop_id,
+                           uint64_t seed, uint64_t word_index)
+{
+    uint64_t keep = oracle_keep_mask(fold, hop_id, seed, word_index);
+    uint64_t v = oracle_transient_from_keep(local, keep);
+    return oracle_odot(recv, local, v);
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Algorithm 1, line 6 for a run of words: out = recv (.) local.
+ * word_begin is the global index of the first word (it keys the random stream).
+ * Returns 0, or -1 on a bad argument.
+ * ---------------------------------------------------------------------------------------- */
+int oracle_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                     uint64_t word_begin, uint64_t n_words, uint32_t fold, uint32_t hop_id,
+                     uint64_t seed)
+{
+    if (fold == 0)
+        return -1;
+    for (uint64_t i = 0; i < n_words; ++i)
+        out[i] = oracle_merge_word(recv[i], local[i], fold, hop_id, seed, word_begin + i);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Algorithm 1, line 9:  g_t <- eta_s * (union of the final sign parts): +scale or -scale.
+ * ---------------------------------------------------------------------------------------- */
+void oracle_decode(const uint64_t *bits, float scale, float *update, uint64_t d)
+{
+    for (uint64_t e = 0; e < d; ++e) {
+        unsigned bit = (unsigned)((bits[e / 64u] >> (e % 64u)) & 1u);
+        update[e] = bit ? scale : -scale;
+    }
+}
+
+/* Algorithm 1, line 10:  c_{t+1} <- g (the compensated one of line 1) - g_t. */
+void oracle_compensate(const float *s, const float *update, float *c_next, uint64_t d)
+{
+    for (uint64_t e = 0; e < d; ++e) {
+        c_next[e] = s[e] - update[e];            /* one rounding to fp32 */
+    }
+}
+
+/* Algorithm 1, line 2: bounds[i] = floor(i * n / parts) + begin, i = 0..parts. */
+void oracle_split_bounds(uint64_t begin, uint64_t n, uint32_t parts, uint64_t *bounds)
+{
+    for (uint32_t i = 0; i <= parts; ++i)
+        bounds[i] = begin + (uint64_t)(((unsigned __int128)i * n) / parts);
+}
+
+static uint32_t part_of(uint64_t w, const uint64_t *bounds, uint32_t parts)
+{
+    for (uint32_t i = 0; i < parts; ++i)
+        if (bounds[i] <= w && w < bounds[i + 1])
+            return i;
+    return parts - 1;   /* not reached for w inside [bounds[0], bounds[parts]) */
+}
+
+/* hop ids: row phase (phase 0) carries the row y and the hop h; column phase (phase 1) the hop. */
+uint32_t oracle_hop_id(uint32_t phase, uint32_t row, uint32_t hop)
+{
+    return (phase << 16) | (row << 8) | hop;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * The whole one-bit pass for M simulated workers (Algorithm 1, lines 1-2, 4-10).
+ *
+ *   g          [M][ld]  gradients (already scaled by the local step, Algorithm 2 line 5)
+ *   c          [M][ld]  compensation, read as c_t and overwritten with c_{t+1}
+ *   update     [d]      g_t
+ *   bits_final [W]      the final merged bitmap every worker ends up with (may be NULL)
+ *   sign_maps  [M][W]   every worker's own v* (may be NULL)
+ *   grid_x     0 or M: ring.  Otherwise X columns, Y = M / X rows, rows first.
+ *   threads    > 1: the loop over packed words is run by that many OpenMP threads (the words
+ *              are independent because the stream is counter based); results do not change.
+ * Returns 0, -1 for bad arguments, -2 if memory ran out.
+ * ---------------------------------------------------------------------------------------- */
+int oracle_sync_step(const float *g, float *c, float *update, uint64_t *bits_final,
+                     uint64_t *sign_maps, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                     uint64_t seed, uint32_t grid_x, int threads)
+{
+    if (M == 0 || M > ORACLE_MAX_WORKERS || ld < d || g == NULL || c == NULL || update == NULL)
+        return -1;
+    uint32_t X = (grid_x == 0) ? M : grid_x;
+    if (X == 0 || M % X != 0)
+        return -1;
+    uint32_t Y = M / X;
+    if (d == 0)
+        return 0;
+    if (threads < 1)
+        threads = 1;
+
+    uint64_t W = (d + 63u) / 64u;
+    float *s = (float *)malloc((size_t)M * d * sizeof(float));
+    uint64_t *L = (uint64_t *)malloc((size_t)M * W * sizeof(uint64_t));
+    uint64_t *B = (uint64_t *)malloc((size_t)W * sizeof(uint64_t));
+    if (s == NULL || L == NULL || B == NULL) {
+        free(s); free(L); free(B);
+        return -2;
+    }
+
+    /* line 1 and line 5 for every worker */
+    for (uint32_t m = 0; m < M; ++m) {
+        oracle_add_compensation(g + (size_t)m * ld, c + (size_t)m * ld, s + (size_t)m * d, d);
+        oracle_sign_pack(s + (size_t)m * d, L + (size_t)m * W, d);
+    }
+
+    /* line 2: the W packed words are split in X row-parts */
+    uint64_t row_bounds[ORACLE_MAX_WORKERS + 1];
+    oracle_split_bounds(0, W, X, row_bounds);
+
+    /* lines 4-8, one packed word at a time */
+    #pragma omp parallel for schedule(static) num_threads(threads) if (threads > 1)
+    for (uint64_t w = 0; w < W; ++w) {
+        uint32_t a = part_of(w, row_bounds, X);
+
+        /* row phase: in every row y the chain of part a starts at column a */
+        uint64_t R[ORACLE_MAX_WORKERS];
+        for (uint32_t y = 0; y < Y; ++y) {
+            uint64_t r = L[(size_t)(y * X + a) * W + w];          /* first holder sends its own signs */
+            for (uint32_t h = 1; h < X; ++h) {
+                uint32_t col = (a + h) % X;
+                uint64_t local = L[(size_t)(y * X + col) * W + w];
+                r = oracle_merge_word(r, local, h + 1u, oracle_hop_id(0, y, h), seed, w);
+            }
+            R[y] = r;
+        }
+
+        /* column phase: row-part a is split again in Y sub-parts; chain of sub-part b starts at row b */
+        uint64_t col_bounds[ORACLE_MAX_WORKERS + 1];
+        oracle_split_bounds(row_bounds[a], row_bounds[a + 1] - row_bounds[a], Y, col_bounds);
+        uint32_t b = part_of(w, col_bounds, Y);
+        uint64_t r = R[b];
+        for (uint32_t k = 1; k < Y; ++k) {
+            uint64_t local = R[(b + k) % Y];
+            r = oracle_merge_word(r, local, k + 1u, oracle_hop_id(1, 0, k), seed, w);
+        }
+        B[w] = r;
+    }
+
+    /* line 9 and line 10 */
+    oracle_decode(B, scale, update, d);
+    for (uint32_t m = 0; m < M; ++m)
+        oracle_compensate(s + (size_t)m * d, update, c + (size_t)m * ld, d);
+
+    if (bits_final != NULL)
+        memcpy(bits_final, B, (size_t)W * sizeof(uint64_t));
+    if (sign_maps != NULL)
+        memcpy(sign_maps, L, (size_t)M * W * sizeof(uint64_t));
+    free(s); free(L); free(B);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Algorithm 1, lines 11-13 (full-precision round):  g_t <- (1/M) sum_m (g^(m) + c^(m)),  c <- 0.
+ * The sum is taken in double and rounded once to fp32.
+ * ---------------------------------------------------------------------------------------- */
+int oracle_full_sync(const float *g, float *c, float *update, uint32_t M, uint64_t d, uint64_t ld)
+{
+    if (M == 0 || ld < d || g == NULL || c == NULL || update == NULL)
+        return -1;
+    for (uint64_t e = 0; e < d; ++e) {
+        double acc = 0.0;
+        for (uint32_t m = 0; m < M; ++m) {
+            float sm = g[(size_t)m * ld + e] + c[(size_t)m * ld + e];   /* line 1, fp32 */
+            acc += (double)sm;
+        }
+        update[e] = (float)(acc / (double)M);
+    }
+    for (uint32_t m = 0; m < M; ++m)
+        for (uint64_t e = 0; e < d; ++e)
+            c[(size_t)m * ld + e] = 0.0f;
+    return 0;
+}
+
+/* Algorithm 2, line 6:  x <- x - g_t. */
+void oracle_apply_update(float *x, const float *update, uint64_t d)
+{
+    for (uint64_t e = 0; e < d; ++e) {
+        x[e] = x[e] - update[e];
+    }
+}

@@ -1,0 +1,502 @@
+"""Pins for the CPU oracle: every check here compares the oracle with something that is NOT the
+oracle -- the paper's stated properties, exact enumeration, closed forms, numpy routines, an
+independently written second formulation, other people's Philox."""
+
+import ctypes
+import itertools
+import os
+import subprocess
+import sys
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import marsit_oracle as orc
+import philox_ref
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+MASK64 = (1 << 64) - 1
+
+
+# ---------------------------------------------------------------------------------------------
+# Philox: known answers, Python big-int transcription, PyTorch's host engine
+# ---------------------------------------------------------------------------------------------
+
+def _kat_rows():
+    rows = []
+    with open(os.path.join(HERE, "golden", "philox4x32_10_kat.txt")) as fh:
+        for line in fh:
+            if line.startswith("#") or not line.strip():
+                continue
+            v = [int(x, 16) for x in line.split()]
+            rows.append((v[0:4], v[4:6], v[6:10]))
+    return rows
+
+
+def test_philox_known_answers():
+    rows = _kat_rows()
+    assert len(rows) == 3
+    for ctr, key, want in rows:
+        assert list(orc.philox4x32_10(ctr, key)) == want
+        assert philox_ref.philox4x32_10(ctr, key) == want
+
+
+def test_philox_matches_python_transcription():
+    rng = np.random.default_rng(7)
+    for _ in range(500):
+        ctr = rng.integers(0, 2**32, size=4, dtype=np.uint64)
+        key = rng.integers(0, 2**32, size=2, dtype=np.uint64)
+        assert list(orc.philox4x32_10(ctr, key)) == philox_ref.philox4x32_10(ctr, key)
+
+
+@pytest.fixture(scope="module")
+def aten_philox(tmp_path_factory):
+    import torch
+    inc = os.path.join(os.path.dirname(torch.__file__), "include")
+    src = os.path.join(HERE, "helpers", "aten_philox_probe.cpp")
+    so = str(tmp_path_factory.mktemp("aten") / "aten_philox_probe.so")
+    try:
+        subprocess.run(["g++", "-O1", "-std=c++17", "-fPIC", "-shared", "-I" + inc, "-o", so, src],
+                       check=True, capture_output=True)
+    except (subprocess.CalledProcessError, FileNotFoundError) as exc:   # pragma: no cover
+        pytest.skip(f"cannot compile the ATen Philox probe: {exc}")
+    lib = ctypes.CDLL(so)
+    lib.aten_philox4x32_10.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_uint64,
+                                       ctypes.c_void_p]
+
+    def call(seed, subsequence, offset):
+        out = np.zeros(4, dtype=np.uint32)
+        lib.aten_philox4x32_10(seed, subsequence, offset, out.ctypes.data_as(ctypes.c_void_p))
+        return [int(x) for x in out]
+    return call
+
+
+def test_stream_matches_pytorch_engine(aten_philox):
+    """stream (seed, hop, word)[j] == PyTorch's engine with subsequence = word index and
+    offset = block | hop << 32 (its counter is (offset lo, offset hi, subseq lo, subseq hi))."""
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        seed = int(rng.integers(0, 2**63)) * 2 + int(rng.integers(0, 2))
+        hop = int(rng.integers(0, 2**20))
+        word = int(rng.integers(0, 2**40))
+        block = int(rng.integers(0, 16))
+        want = aten_philox(seed, word, block | (hop << 32))
+        got = [orc.stream_u32(seed, hop, word, 4 * block + k) for k in range(4)]
+        assert got == want
+        assert [philox_ref.stream_u32(seed, hop, word, 4 * block + k) for k in range(4)] == want
+
+
+# ---------------------------------------------------------------------------------------------
+# Eq. 2 and the operator: exact enumeration of the unbiasedness property (Section 4.1.1)
+# ---------------------------------------------------------------------------------------------
+
+def test_eq2_probabilities():
+    """P(v=1) = 1/m where v*=1 and (m-1)/m where v*=0, when the keep-local draw has P = 1/m."""
+    for m in range(1, 9):
+        p_keep = Fraction(1, m)
+        for l in (0, 1):
+            p_v1 = Fraction(0)
+            for t in (0, 1):
+                w = p_keep if t else 1 - p_keep
+                p_v1 += w * (orc.transient_from_keep(l, t) & 1)
+            assert p_v1 == (Fraction(1, m) if l else Fraction(m - 1, m))
+
+
+def test_odot_truth_table():
+    """Same bit in both vectors: unchanged.  Different: the transient bit decides (Section 1)."""
+    for r, l, v in itertools.product((0, 1), repeat=3):
+        out = orc.odot(r, l, v) & 1
+        assert out == (r if r == l else v)
+    # word-wide: every bit position acts on its own
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        r, l, v = (int(x) for x in rng.integers(0, 2**63, size=3, dtype=np.uint64) * 2 + 1)
+        got = orc.odot(r, l, v)
+        for j in range(64):
+            rb, lb, vb = (r >> j) & 1, (l >> j) & 1, (v >> j) & 1
+            assert (got >> j) & 1 == (rb if rb == lb else vb)
+
+
+def _chain_prob_one(bits):
+    """Exact P(final = 1) for a chain over workers with sign bits `bits`, fold count h+1 at hop h,
+    enumerating every outcome of the keep-local draws with its rational weight."""
+    M = len(bits)
+    total = Fraction(0)
+    for draws in itertools.product((0, 1), repeat=M - 1):
+        weight = Fraction(1)
+        r = bits[0]
+        for h in range(1, M):
+            m = h + 1
+            t = draws[h - 1]
+            weight *= Fraction(1, m) if t else Fraction(m - 1, m)
+            v = orc.transient_from_keep(bits[h], t)
+            r = orc.odot(r, bits[h], v) & 1
+        total += weight * r
+    return total
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 6])
+def test_exact_unbiasedness_ring(M):
+    """Expected merged sign bit == mean of the workers' sign bits, for every sign pattern."""
+    for bits in itertools.product((0, 1), repeat=M):
+        assert _chain_prob_one(bits) == Fraction(sum(bits), M)
+
+
+@pytest.mark.parametrize("X,Y", [(2, 2), (3, 2), (2, 3)])
+def test_exact_unbiasedness_torus(X, Y):
+    """Rows first (fold counts 2..X), then columns over the row results (fold counts 2..Y)."""
+    M = X * Y
+    n_draws = Y * (X - 1) + (Y - 1)
+    for bits in itertools.product((0, 1), repeat=M):
+        total = Fraction(0)
+        for draws in itertools.product((0, 1), repeat=n_draws):
+            it = iter(draws)
+            weight = Fraction(1)
+            rows = []
+            for y in range(Y):
+                r = bits[y * X]
+                for h in range(1, X):
+                    t = next(it)
+                    weight *= Fraction(1, h + 1) if t else Fraction(h, h + 1)
+                    l = bits[y * X + h]
+                    r = orc.odot(r, l, orc.transient_from_keep(l, t)) & 1
+                rows.append(r)
+            r = rows[0]
+            for k in range(1, Y):
+                t = next(it)
+                weight *= Fraction(1, k + 1) if t else Fraction(k, k + 1)
+                r = orc.odot(r, rows[k], orc.transient_from_keep(rows[k], t)) & 1
+            total += weight * r
+        assert total == Fraction(sum(bits), M)
+
+
+# ---------------------------------------------------------------------------------------------
+# Empirical unbiasedness through the whole pass with the Philox stream (binomial bound)
+# ---------------------------------------------------------------------------------------------
+
+def _pattern_inputs(patterns, M, n_rep):
+    """g[m, p*n_rep + r] has the sign given by bit m of patterns[p]."""
+    d = len(patterns) * n_rep
+    g = np.empty((M, d), dtype=np.float32)
+    for p, pat in enumerate(patterns):
+        for m in range(M):
+            g[m, p * n_rep:(p + 1) * n_rep] = 1.0 if (pat >> m) & 1 else -1.0
+    return g
+
+
+@pytest.mark.parametrize("M,grid_x,patterns", [
+    (2, 0, list(range(4))),
+    (3, 0, list(range(8))),
+    (5, 0, list(range(32))),
+    (8, 0, [0x00, 0x01, 0x80, 0x03, 0x18, 0x0F, 0xF0, 0xAA, 0x55, 0x7F, 0xFE, 0xFF, 0x35]),
+    (6, 3, [0, 1, 2, 4, 8, 16, 32, 7, 56, 21, 42, 63, 27]),
+    (16, 4, [0x0001, 0x8000, 0x00FF, 0xFF00, 0x0F0F, 0x5555, 0x7FFF, 0x1248]),
+])
+def test_empirical_unbiasedness(M, grid_x, patterns):
+    n_rep = 1 << 18
+    g = _pattern_inputs(patterns, M, n_rep)
+    c = np.zeros_like(g)
+    update, bits, _ = orc.sync_step(g, c, scale=1.0, seed=0x1234_5678_9ABC_DEF0 + M, grid_x=grid_x,
+                                    threads=8)
+    plus = (update > 0).reshape(len(patterns), n_rep)
+    for p, pat in enumerate(patterns):
+        mean = bin(pat).count("1") / M
+        bound = 5.0 * np.sqrt(max(mean * (1 - mean), 1e-12) / n_rep)
+        assert abs(plus[p].mean() - mean) <= bound, (M, grid_x, hex(pat))
+
+
+@pytest.mark.parametrize("fold", [1, 2, 3, 4, 5, 7, 8, 16])
+def test_keep_mask_frequency_and_independence(fold):
+    """P(t=1) = 1/m per bit position; neighbouring bits and neighbouring hops uncorrelated."""
+    n_words = 4096
+    seed = 99
+    masks = np.array([orc.keep_mask(fold, 5, seed, w) for w in range(n_words)], dtype=np.uint64)
+    bits = ((masks[:, None] >> np.arange(64, dtype=np.uint64)[None, :]) & np.uint64(1)).astype(np.float64)
+    p = 1.0 / fold
+    n = bits.size
+    sigma = np.sqrt(p * (1 - p) / n) if fold > 1 else 0.0
+    assert abs(bits.mean() - p) <= 5 * sigma + 1e-9
+    if fold == 1:
+        assert np.all(masks == np.uint64(MASK64))      # fold 1: always keep local
+        return
+    # per bit position
+    per_pos = bits.mean(axis=0)
+    assert np.all(np.abs(per_pos - p) <= 5 * np.sqrt(p * (1 - p) / n_words))
+    # lag-1 correlation along the bit axis
+    a, b = bits[:, :-1].ravel() - p, bits[:, 1:].ravel() - p
+    corr = (a * b).mean() / (p * (1 - p))
+    assert abs(corr) <= 5 / np.sqrt(a.size)
+    # a different hop id gives an unrelated mask
+    other = np.array([orc.keep_mask(fold, 6, seed, w) for w in range(n_words)], dtype=np.uint64)
+    ob = ((other[:, None] >> np.arange(64, dtype=np.uint64)[None, :]) & np.uint64(1)).astype(np.float64)
+    corr2 = ((bits - p) * (ob - p)).mean() / (p * (1 - p))
+    assert abs(corr2) <= 5 / np.sqrt(n)
+
+
+def test_keep_mask_threshold_definition():
+    """t_j = (u_j < floor(2^32 / m)) with u_j from the independent Python Philox."""
+    for fold, hop, seed, word in [(2, 1, 5, 0), (3, 2, 2**40 + 17, 123456789), (7, 0x10003, 1, 2**33 + 5)]:
+        thr = (1 << 32) // fold
+        want = 0
+        for j in range(64):
+            if philox_ref.stream_u32(seed, hop, word, j) < thr:
+                want |= 1 << j
+        assert orc.keep_mask(fold, hop, seed, word) == want
+
+
+# ---------------------------------------------------------------------------------------------
+# Identity / agreement cases
+# ---------------------------------------------------------------------------------------------
+
+def test_all_workers_equal_is_identity():
+    rng = np.random.default_rng(5)
+    d = 64 * 37 + 13
+    row = rng.standard_normal(d).astype(np.float32)
+    for M, gx in [(1, 0), (2, 0), (5, 0), (8, 0), (6, 2)]:
+        g = np.tile(row, (M, 1))
+        c = np.zeros_like(g)
+        for seed in (0, 1, 2**63 + 5):
+            update, bits, maps = orc.sync_step(g.copy(), c.copy(), 0.5, seed, grid_x=gx,
+                                               want_sign_maps=True)
+            assert np.array_equal(bits, maps[0])
+            assert np.array_equal(update, np.where(np.signbit(row), np.float32(-0.5), np.float32(0.5)))
+
+
+def test_fold_one_returns_local():
+    rng = np.random.default_rng(6)
+    recv = rng.integers(0, 2**63, size=33, dtype=np.uint64)
+    local = rng.integers(0, 2**63, size=33, dtype=np.uint64)
+    assert np.array_equal(orc.hop_merge(recv, local, 7, 1, 3, 42), local)
+
+
+def test_two_workers_take_local_iff_top_bit_clear():
+    """m = 2: threshold 2^31, so a differing bit takes the local sign iff u < 2^31."""
+    seed, hop, word = 77, 1, 900
+    recv, local = 0xAAAA_AAAA_5555_5555, 0x0F0F_0F0F_F0F0_F0F0
+    got = orc.merge_word(recv, local, 2, hop, seed, word)
+    for j in range(64):
+        rb, lb = (recv >> j) & 1, (local >> j) & 1
+        u = philox_ref.stream_u32(seed, hop, word, j)
+        want = lb if (u >> 31) == 0 else rb
+        assert (got >> j) & 1 == want
+
+
+# ---------------------------------------------------------------------------------------------
+# Second formulation (written independently): the final bit is the sign bit of the worker picked
+# by the last successful keep-local draw of its chain ("reservoir" form)
+# ---------------------------------------------------------------------------------------------
+
+def _floor_bounds(begin, n, parts):
+    return [begin + (i * n) // parts for i in range(parts + 1)]
+
+
+def _part(w, bounds):
+    for i in range(len(bounds) - 1):
+        if bounds[i] <= w < bounds[i + 1]:
+            return i
+    raise AssertionError
+
+
+def _reservoir_final_bits(signs, d, M, X, seed):
+    """signs[m][e] in {0,1}.  Returns the final bit of every element, in pure Python."""
+    Y = M // X
+    W = (d + 63) // 64
+    row_bounds = _floor_bounds(0, W, X)
+    final = np.zeros(d, dtype=np.uint8)
+    for e in range(d):
+        w, j = divmod(e, 64)
+        a = _part(w, row_bounds)
+        picked_rows = []
+        for y in range(Y):
+            pick = 0
+            for h in range(1, X):
+                if philox_ref.stream_u32(seed, (0 << 16) | (y << 8) | h, w, j) < (1 << 32) // (h + 1):
+                    pick = h
+            picked_rows.append(signs[y * X + (a + pick) % X][e])
+        col_bounds = _floor_bounds(row_bounds[a], row_bounds[a + 1] - row_bounds[a], Y)
+        b = _part(w, col_bounds)
+        pick = 0
+        for k in range(1, Y):
+            if philox_ref.stream_u32(seed, (1 << 16) | k, w, j) < (1 << 32) // (k + 1):
+                pick = k
+        final[e] = picked_rows[(b + pick) % Y]
+    return final
+
+
+@pytest.mark.parametrize("M,grid_x,d", [(3, 0, 64 * 10 + 5), (5, 0, 64 * 7), (8, 0, 64 * 9 + 63),
+                                        (6, 3, 64 * 11 + 1), (4, 2, 64 * 5 + 17)])
+def test_second_formulation(M, grid_x, d):
+    rng = np.random.default_rng(100 + M)
+    g = rng.standard_normal((M, d)).astype(np.float32)
+    c = (0.3 * rng.standard_normal((M, d))).astype(np.float32)
+    seed = 0xDEADBEEF00 + M
+    s = g + c
+    signs = (~np.signbit(s)).astype(np.uint8)
+    want = _reservoir_final_bits(signs, d, M, grid_x or M, seed)
+    update, bits, _ = orc.sync_step(g, c.copy(), 1.0, seed, grid_x=grid_x)
+    got = ((bits[np.arange(d) // 64] >> (np.arange(d) % 64).astype(np.uint64)) & np.uint64(1)).astype(np.uint8)
+    assert np.array_equal(got, want)
+    assert np.array_equal(update > 0, want.astype(bool))
+
+
+# ---------------------------------------------------------------------------------------------
+# Packing, decode, compensation: numpy routines and closed forms
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("d", [1, 63, 64, 65, 64 * 20 + 7])
+def test_sign_pack_matches_numpy_packbits(d):
+    rng = np.random.default_rng(d)
+    s = rng.standard_normal(d).astype(np.float32)
+    s[rng.integers(0, d, size=max(1, d // 10))] = 0.0
+    s[rng.integers(0, d, size=max(1, d // 10))] = -0.0
+    bits = orc.sign_pack(s)
+    padded = np.zeros(orc.n_words(d) * 64, dtype=np.uint8)
+    padded[:d] = ~np.signbit(s)
+    want = np.packbits(padded, bitorder="little").view("<u8")
+    assert np.array_equal(bits, want)
+    # round trip
+    assert np.array_equal(orc.sign_unpack(bits, d), np.where(np.signbit(s), -1.0, 1.0).astype(np.float32))
+
+
+def test_sign_special_values():
+    s = np.array([0.0, -0.0, np.inf, -np.inf, 1e-45, -1e-45, 3.0, -3.0], dtype=np.float32)
+    assert int(orc.sign_pack(s)[0]) == 0b01010101
+    all_pos = np.full(130, 2.0, dtype=np.float32)
+    b = orc.sign_pack(all_pos)
+    assert [int(x) for x in b] == [MASK64, MASK64, 0b11]     # tail bits beyond d stay zero
+
+
+def test_add_compensation_matches_numpy_float32():
+    rng = np.random.default_rng(1)
+    g = (rng.standard_normal(10_000) * 10.0 ** rng.integers(-30, 30, 10_000)).astype(np.float32)
+    c = (rng.standard_normal(10_000) * 10.0 ** rng.integers(-30, 30, 10_000)).astype(np.float32)
+    g[:4] = [1e-40, -1e-40, 1.0, -1.0]
+    c[:4] = [1e-41, 1e-40, -1.0, 1.0]
+    s = orc.add_compensation(g, c)
+    assert np.array_equal(s.view(np.uint32), (g + c).view(np.uint32))     # bit for bit, denormals kept
+    assert np.array_equal(orc.add_compensation(g, None).view(np.uint32), g.view(np.uint32))
+
+
+def test_decode_closed_form():
+    rng = np.random.default_rng(2)
+    d = 64 * 13 + 29
+    bits = rng.integers(0, 2**63, size=orc.n_words(d), dtype=np.uint64)
+    scale = np.float32(3.25e-3)
+    upd = orc.decode(bits, float(scale), d)
+    assert set(np.unique(upd)) <= {scale, -scale}              # only {+eta_s, -eta_s}
+    assert np.isclose(np.sum((upd / scale).astype(np.float64) ** 2), d)   # ||g_t / eta_s||^2 = D
+    e = np.arange(d)
+    bit = (bits[e // 64] >> (e % 64).astype(np.uint64)) & np.uint64(1)
+    assert np.array_equal(upd > 0, bit.astype(bool))
+
+
+def test_compensation_invariants_single_step():
+    rng = np.random.default_rng(8)
+    M, d = 5, 64 * 40 + 3
+    g = rng.standard_normal((M, d)).astype(np.float32)
+    c0 = (0.1 * rng.standard_normal((M, d))).astype(np.float32)
+    c = c0.copy()
+    update, _, _ = orc.sync_step(g, c, 1e-3, 4242)
+    s = g + c0
+    # line 10: c_next = s - update, one fp32 rounding
+    assert np.array_equal(c.view(np.uint32), (s - update[None, :]).view(np.uint32))
+    # every worker subtracts the same global update
+    assert np.allclose((c[0] - c[1]).astype(np.float64), (s[0].astype(np.float64) - s[1]), atol=2e-7 * 8)
+
+
+def test_compensation_telescopes_over_steps():
+    """Appendix B: mean_m c_T = sum_t (mean_m g_t - update_t) while no full-precision round occurs."""
+    rng = np.random.default_rng(9)
+    M, d, T = 4, 64 * 16, 12
+    c = np.zeros((M, d), dtype=np.float32)
+    acc = np.zeros(d, dtype=np.float64)
+    for t in range(T):
+        g = (0.01 * rng.standard_normal((M, d))).astype(np.float32)
+        update, _, _ = orc.sync_step(g, c, 1e-3, 1000 + t)
+        acc += g.astype(np.float64).mean(axis=0) - update.astype(np.float64)
+    assert np.allclose(c.astype(np.float64).mean(axis=0), acc, atol=T * 4 * 2.0 ** -24 * 0.1)
+
+
+def test_split_bounds_floor_rule():
+    assert [int(x) for x in orc.split_bounds(0, 1024, 3)] == [0, 341, 682, 1024]
+    assert [int(x) for x in orc.split_bounds(10, 7, 4)] == [10, 11, 13, 15, 17]
+    b = orc.split_bounds(0, 2_156_250, 8)
+    assert int(b[0]) == 0 and int(b[-1]) == 2_156_250
+    assert all(int(b[i]) == (i * 2_156_250) // 8 for i in range(9))
+    # fewer words than parts: some parts are empty, none is negative
+    b = orc.split_bounds(0, 3, 8)
+    assert int(b[-1]) == 3 and np.all(np.diff(b.astype(np.int64)) >= 0)
+
+
+def test_padding_and_ld_are_ignored():
+    rng = np.random.default_rng(10)
+    M, d, ld = 3, 64 * 6 + 9, 64 * 7 + 4
+    g = rng.standard_normal((M, ld)).astype(np.float32)
+    c = rng.standard_normal((M, ld)).astype(np.float32)
+    g2, c2 = np.ascontiguousarray(g[:, :d]), np.ascontiguousarray(c[:, :d])
+    cpad = c.copy()
+    u1, b1, _ = orc.sync_step(g, cpad, 0.01, 5, d=d)
+    u2, b2, _ = orc.sync_step(g2, c2, 0.01, 5)
+    assert np.array_equal(u1, u2) and np.array_equal(b1, b2)
+    assert np.array_equal(cpad[:, :d], c2)
+    assert np.array_equal(cpad[:, d:], c[:, d:])              # padding untouched
+    assert int(b1[-1]) >> (d % 64) == 0                        # tail bits zero
+
+
+def test_threads_do_not_change_results():
+    rng = np.random.default_rng(12)
+    g = rng.standard_normal((8, 64 * 50 + 1)).astype(np.float32)
+    c1 = np.zeros_like(g)
+    c2 = np.zeros_like(g)
+    u1, b1, _ = orc.sync_step(g, c1, 1e-3, 31337, threads=1)
+    u2, b2, _ = orc.sync_step(g, c2, 1e-3, 31337, threads=4)
+    assert np.array_equal(u1, u2) and np.array_equal(b1, b2) and np.array_equal(c1, c2)
+
+
+def test_hop_merge_composes_to_sync_step():
+    """Chaining the single-hop routine along the ring schedule reproduces the whole pass."""
+    rng = np.random.default_rng(13)
+    M, d = 4, 64 * 23 + 40
+    g = rng.standard_normal((M, d)).astype(np.float32)
+    c = np.zeros_like(g)
+    seed = 2024
+    update, bits, maps = orc.sync_step(g, c, 1.0, seed, want_sign_maps=True)
+    W = orc.n_words(d)
+    bounds = [int(x) for x in orc.split_bounds(0, W, M)]
+    final = np.zeros(W, dtype=np.uint64)
+    for i in range(M):
+        lo, hi = bounds[i], bounds[i + 1]
+        r = maps[i, lo:hi].copy()
+        for h in range(1, M):
+            r = orc.hop_merge(r, np.ascontiguousarray(maps[(i + h) % M, lo:hi]), lo, h + 1, h, seed)
+        final[lo:hi] = r
+    assert np.array_equal(final, bits)
+
+
+# ---------------------------------------------------------------------------------------------
+# Full-precision round and model update (Algorithm 1 lines 11-13, Algorithm 2 line 6)
+# ---------------------------------------------------------------------------------------------
+
+def test_full_sync_is_the_mean_and_resets_compensation():
+    rng = np.random.default_rng(14)
+    M, d = 8, 1000
+    g = rng.standard_normal((M, d)).astype(np.float32)
+    c = rng.standard_normal((M, d)).astype(np.float32)
+    want = ((g + c).astype(np.float64).mean(axis=0)).astype(np.float32)
+    upd = orc.full_sync(g, c)
+    assert np.array_equal(upd, want)
+    assert not c.any()
+
+
+def test_average_bits_per_element_table():
+    """Fig. 4(b): one full-precision round (32 bits) every K rounds, one bit otherwise."""
+    printed = {50: 1.62, 100: 1.31, 200: 1.16}
+    for K, bits in printed.items():
+        assert round((K - 1 + 32) / K, 2) == bits
+
+
+def test_apply_update():
+    x = np.array([1.0, 2.0, -3.0], dtype=np.float32)
+    u = np.array([0.5, -0.5, 0.25], dtype=np.float32)
+    assert np.array_equal(orc.apply_update(x, u), np.array([0.5, 2.5, -3.25], dtype=np.float32))
