@@ -1,0 +1,153 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused Marsit one-bit synchronisation pass on one MI355X.
+
+A step = one pass of the whole hot path (compensate, sign, the M-1 merges of every part's chain,
+decode, global compensation) over one batch of synthetic gradients of all M simulated workers; it
+is one launch of the fused kernel through the C ABI.  Inputs are resident in HBM before the timed
+region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet50]
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, vendor figure
+
+# HBM traffic of one launch of the fused kernel in bytes, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs scaled by a copy kernel of known size (figures and commands: profiles/).
+# None where no counter run has been made for that workload.
+MEASURED_TRAFFIC_BYTES = {
+}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--seed", type=int, default=2022)
+    ap.add_argument("--pool", type=int, default=0, help="gradient sets kept in HBM (0: one per step)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-threads", type=int, default=0)
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, g_host, seed, threads):
+    """The oracle, as it stands, on the host cores: one full step of the same workload."""
+    import numpy as np
+    from oracle import marsit_oracle as orc
+    c_host = np.zeros_like(g_host)
+    t0 = time.perf_counter()
+    orc.sync_step(g_host, c_host, wl.scale, seed, grid_x=wl.grid_x, threads=threads)
+    dt = time.perf_counter() - t0
+    gbps = wl.algorithmic_bytes() / dt / 1e9
+    # the same on one thread, on the first 1/8 of the columns
+    d8 = max(64, (wl.d // 8) // 64 * 64)
+    g8 = np.ascontiguousarray(g_host[:, :d8])
+    c8 = np.zeros_like(g8)
+    t0 = time.perf_counter()
+    orc.sync_step(g8, c8, wl.scale, seed, grid_x=wl.grid_x, threads=1)
+    dt1 = time.perf_counter() - t0
+    bytes8 = 12 * wl.M * d8 + 4 * d8 + d8 // 8
+    return {
+        "value": gbps, "unit": "GB/s", "cores": threads, "kind": "oracle",
+        "sample": f"1 full step of {wl.name} (M={wl.M}, d={wl.d}) on {threads} OpenMP threads",
+        "seconds": dt, "worker_elements_per_s": wl.M * wl.d / dt,
+        "single_thread": {"value": bytes8 / dt1 / 1e9, "unit": "GB/s", "seconds": dt1,
+                          "sample": f"1 step on the first {d8} columns"},
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build simulates the M workers inside ONE GPU; there is no multi-GPU "
+              "path to time (--gpus must be 1).", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2204_06787_amd import marsit, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    marsit.load_library()          # raises if the HIP library has not been built
+    torch.cuda.set_device(0)
+    wl = workloads.WORKLOADS[args.workload]
+    K, Wm = args.steps, args.warmup
+    total = K + Wm
+    pool = args.pool if args.pool > 0 else total
+    pool = max(1, min(pool, total, int(64e9 // (4 * wl.M * wl.d))))
+
+    # inputs: resident in HBM before anything is timed
+    grads = [workloads.make_gradients(wl, t, args.seed, device="cuda") for t in range(pool)]
+    c = workloads.zero_compensation(wl, device="cuda")
+    update = torch.empty(wl.d, dtype=torch.float32, device="cuda")
+    bits = marsit.new_bitmap(wl.d)
+    stream = torch.cuda.current_stream()
+
+    def step(t):
+        marsit.marsit_ring_step_sim(grads[t % pool], c, update, bits, wl.scale,
+                                    workloads.step_seed(args.seed, t), grid_x=wl.grid_x,
+                                    stream=stream)
+
+    for t in range(Wm):
+        step(t)
+    torch.cuda.synchronize()
+
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    t0 = time.perf_counter()
+    events[0].record(stream)
+    for i in range(K):
+        step(Wm + i)
+        events[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    per_launch_ms = [events[i].elapsed_time(events[i + 1]) for i in range(K)]
+    avg_kernel_ms = sum(per_launch_ms) / K
+    ms_per_step = wall * 1e3 / K
+    nbytes = wl.algorithmic_bytes()
+    value = nbytes / (ms_per_step * 1e-3) / 1e9
+    achieved = nbytes / (avg_kernel_ms * 1e-3) / 1e9
+
+    out = {
+        "metric": "fused Marsit sync pass GB/s (algorithmic bytes / time)",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: M={wl.M} simulated workers, d={wl.d} fp32, "
+                               f"{'ring' if not wl.grid_x else f'torus {wl.grid_x}x{wl.M // wl.grid_x}'}, "
+                               f"{wl.dist} gradients, compensation carried over steps, one seed per step",
+                   "M": wl.M, "d": wl.d, "grid_x": wl.grid_x, "scale": wl.scale,
+                   "gradient_sets_in_hbm": pool},
+        "worker_elements_per_s": wl.M * wl.d / (ms_per_step * 1e-3),
+        "elements_per_s": wl.d / (ms_per_step * 1e-3),
+        "algorithmic_bytes_per_step": nbytes,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+                     "kernel": "sync_step_kernel", "avg_launch_ms": avg_kernel_ms,
+                     "min_launch_ms": min(per_launch_ms), "max_launch_ms": max(per_launch_ms)},
+    }
+
+    if not args.no_cpu_baseline:
+        threads = args.cpu_threads or min(16, os.cpu_count() or 1)
+        g_host = grads[0].cpu().numpy()
+        out["cpu_baseline"] = cpu_baseline(wl, g_host, workloads.step_seed(args.seed, 0), threads)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,151 @@
+/*
+ * marsit.h -- C ABI of the MI355X (gfx950) library for the one-bit synchronisation pass of
+ * Marsit ("Sign Bit is Enough: A Learning Synchronization Framework for Multi-hop All-reduce with
+ * Ultimate Compression", arXiv 2204.06787).
+ *
+ * Conventions shared by every entry point
+ *   - Return value: MARSIT_OK (0) or a negative marsit_status.  Nothing throws.
+ *   - Pointers named g, c, x, update*, bits*, recv, local, out are DEVICE pointers owned by the
+ *     caller.  The library never allocates, frees or synchronises; work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL is the default stream) and the call returns at once.
+ *   - fp32 vectors are plain arrays of IEEE-754 binary32.  Arithmetic is fp32 with one
+ *     round-to-nearest-even operation per step of Algorithm 1; denormals are kept.
+ *   - Sign bitmaps: 64-bit words; element e sits in word e/64 at bit e%64 (least significant
+ *     first); bit 1 means +1, i.e. the IEEE sign bit is clear (+0 -> +1, -0 -> -1); bits at
+ *     positions >= d of the last word are written as 0.  Bitmap pointers must be 8-byte aligned,
+ *     fp32 pointers 4-byte aligned (MARSIT_EALIGN otherwise).  16-byte aligned fp32 pointers and a
+ *     row stride that is a multiple of 4 select the 128-bit path; anything else is still correct,
+ *     only slower.
+ *   - Random merge masks: counter-based Philox4x32-10.  The 32-bit word that decides bit j of
+ *     packed word w at hop id h is output (j mod 4) of Philox with key = (seed low, seed high) and
+ *     counter = (j / 4, h, w low, w high).  With fold count m the local sign is taken where that
+ *     word is < floor(2^32 / m)  (probability 1/m; m = 1: always).
+ *   - d == 0 or n_words == 0: success, nothing is launched.
+ *   - NaN inputs: the sign bit of whatever the fp32 add produces is used; bit-for-bit agreement
+ *     with another machine is not promised for NaN.
+ */
+#ifndef MARSIT_H
+#define MARSIT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MARSIT_MAX_WORKERS 64u
+
+typedef enum marsit_status {
+    MARSIT_OK = 0,
+    MARSIT_EINVAL = -1,   /* NULL required pointer, M == 0, M > MARSIT_MAX_WORKERS, fold == 0, ld < d,
+                             grid_x does not divide M, non-finite scale, K == 0, size too large */
+    MARSIT_EALIGN = -2,   /* a pointer is not aligned to its element size */
+    MARSIT_EHIP = -3      /* a HIP call failed; marsit_last_hip_error() has the raw hipError_t */
+} marsit_status;
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int marsit_version(void);
+
+/* Raw hipError_t of the last failed HIP call made by this library on the calling thread (0: none). */
+int marsit_last_hip_error(void);
+
+/* Static, NUL-terminated description of a status code. */
+const char *marsit_status_string(int status);
+
+/*
+ * Host-side Philox4x32-10 (Salmon et al., SC'11), the generator behind the merge masks.
+ * All three arrays are HOST memory.  For tests and for callers that want to replay a mask.
+ */
+void marsit_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
+
+/*
+ * Host-side.  "Split into M parts" (Algorithm 1, line 2) on packed words, as the schedules use it.
+ * Writes M + 1 non-decreasing word indices to bounds_out (HOST memory); part f covers words
+ * [bounds_out[f], bounds_out[f+1]).
+ *   ring (grid_x == 0 or grid_x == M): part i = [floor(i*W/M), floor((i+1)*W/M)); its chain
+ *     starts at worker i.
+ *   torus (X = grid_x columns, Y = M / X rows): the W words are split in X row-parts by the same
+ *     rule and every row-part again in Y sub-parts; part f = a*Y + b is sub-part b of row-part a.
+ * Returns MARSIT_EINVAL for M == 0, M > MARSIT_MAX_WORKERS, grid_x not dividing M, NULL bounds_out.
+ */
+int marsit_split_bounds(uint64_t n_words, uint32_t M, uint32_t grid_x, uint64_t *bounds_out);
+
+/*
+ * Algorithm 1, line 1 and line 5 for one worker:  bit e of bits_out = sgn(g[e] + c[e]).
+ *   g, c     [d] fp32; c may be NULL (taken as 0).
+ *   bits_out [ceil(d/64)] 64-bit words.
+ */
+int marsit_compress(const float *g, const float *c, uint64_t *bits_out, uint64_t d, void *stream);
+
+/*
+ * Algorithm 1, line 6 for one hop and a run of packed words:
+ *     out = (recv AND local) OR ((recv XOR local) AND v),  v drawn by Eq. 2 of Section 4.1.1
+ * which is the same as: take the local bit where the Bernoulli(1/fold) draw succeeds, else keep
+ * the received bit.
+ *   recv       [n_words] bitmap received from the previous worker of the chain.
+ *   local      [n_words] this worker's own sign bitmap (torus column phase: its row's result).
+ *   out        [n_words]; may be the same buffer as recv or as local.
+ *   word_begin global index of word 0 of these arrays in the whole bitmap (it keys the stream).
+ *   fold       how many workers `out` stands for, this one included (>= 1); hop h of a ring: h+1.
+ *   hop_id     Philox counter word 1.  Ring: h.  Torus: row phase (y << 8) | h for row y,
+ *              column phase (1 << 16) | k.
+ */
+int marsit_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                     uint64_t word_begin, uint64_t n_words, uint32_t fold, uint32_t hop_id,
+                     uint64_t seed, void *stream);
+
+/*
+ * Algorithm 1, lines 9-10 for one worker, from the final bitmap every worker holds after the
+ * gather period:   update_out[e] = bit ? +scale : -scale;   c_out[e] = (g[e] + c[e]) - update_out[e].
+ *   bits       [ceil(d/64)].
+ *   g, c       [d]; c may be NULL (taken as 0).
+ *   scale      global step size eta_s; finite.
+ *   update_out [d] or NULL (not written).
+ *   c_out      [d]; may be the same buffer as c.
+ */
+int marsit_decode_compensate(const uint64_t *bits, const float *g, const float *c, float scale,
+                             float *update_out, float *c_out, uint64_t d, void *stream);
+
+/*
+ * The whole one-bit pass (Algorithm 1, lines 1-2 and 4-10) for M workers simulated inside one
+ * device, fused in one kernel: compensate, sign, the M-1 merges of every part's chain, decode,
+ * global compensation.  Results are bit-identical to chaining marsit_compress, marsit_hop_merge
+ * and marsit_decode_compensate along the same schedule.
+ *   g          [M][ld] gradients, already multiplied by the local step size (Algorithm 2, line 5).
+ *   c          [M][ld] compensation; read as c_t, overwritten with c_{t+1}.  Columns >= d untouched.
+ *   update_out [d] global update g_t (the same for every worker).
+ *   bits_out   [ceil(d/64)] final merged bitmap, or NULL.
+ *   M          1..MARSIT_MAX_WORKERS.   ld >= d.
+ *   grid_x     0 or M: ring; part i starts at worker i and hop h folds worker (i+h) mod M.
+ *              Otherwise a torus with X = grid_x columns and Y = M/X rows, worker (y,x) = y*X + x:
+ *              rows first (in every row the chain of row-part a starts at column a), then columns
+ *              over the Y row results (the chain of sub-part b starts at row b).
+ */
+int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                         uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed,
+                         uint32_t grid_x, void *stream);
+
+/*
+ * Algorithm 1, lines 11-13 (the full-precision round) for M simulated workers:
+ *     update_out[e] = (1/M) * sum_m (g[m][e] + c[m][e]);   c[m][e] = 0.
+ * The sum runs over m = 0..M-1 in fp32, then one division by M.
+ */
+int marsit_full_sync(const float *g, float *c, float *update_out, uint32_t M, uint64_t d,
+                     uint64_t ld, void *stream);
+
+/*
+ * Algorithm 1 as a whole: the one-bit pass when t mod K != 0, the full-precision round when
+ * t mod K == 0 (line 3).  K == 0 is MARSIT_EINVAL; pass K > t_max for "never".  bits_out is left
+ * untouched by a full-precision round.  Other arguments as in marsit_ring_step_sim.
+ */
+int marsit_step(uint64_t t, uint64_t K, const float *g, float *c, float *update_out,
+                uint64_t *bits_out, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                uint64_t seed, uint32_t grid_x, void *stream);
+
+/* Algorithm 2, line 6:  x[e] <- x[e] - update[e]. */
+int marsit_apply_update(float *x, const float *update, uint64_t d, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MARSIT_H */

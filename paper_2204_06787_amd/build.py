@@ -1,0 +1,48 @@
+"""Builds ``libmarsit.so`` (HIP, gfx950) in-tree with hipcc.  ``python -m paper_2204_06787_amd.build``."""
+
+from __future__ import annotations
+
+import os
+import shutil
+import subprocess
+import sys
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(PKG)
+SOURCES = [os.path.join(PKG, "csrc", "marsit_kernels.hip")]
+HEADERS = [os.path.join(PKG, "csrc", "marsit_device.hpp"), os.path.join(ROOT, "include", "marsit.h")]
+LIB = os.path.join(PKG, "libmarsit.so")
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "-ffp-contract=off",                      # every fp32 step is a single rounding
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 instructions
+    "-Wall", "-Wextra",
+]
+
+
+def hipcc() -> str:
+    exe = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(exe):
+        raise RuntimeError("hipcc not found: the HIP library cannot be built on this machine")
+    return exe
+
+
+def build_library(force: bool = True, extra_flags=(), out: str | None = None) -> str:
+    """Compile the HIP library.  With ``force=False`` an up-to-date library is kept."""
+    out = out or LIB
+    if not force and os.path.exists(out):
+        newest = max(os.path.getmtime(p) for p in SOURCES + HEADERS)
+        if os.path.getmtime(out) >= newest:
+            return out
+    cmd = [hipcc(), *HIPCC_FLAGS, *extra_flags, "-I", os.path.join(ROOT, "include"),
+           "-I", os.path.join(PKG, "csrc"), "-o", out, *SOURCES]
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    if proc.returncode != 0:
+        sys.stderr.write(proc.stdout + proc.stderr)
+        raise RuntimeError("hipcc failed: " + " ".join(cmd))
+    return out
+
+
+if __name__ == "__main__":
+    print(build_library(force=True))

@@ -1,0 +1,661 @@
+// HIP kernels (gfx950) and the C ABI of the Marsit one-bit synchronisation pass.
+//
+// The operation is the one-bit branch of Algorithm 1 of the paper (lines 1-2, 4-10) with the
+// transient vector of Eq. 2 and the merge operator of Section 4.1.1.  The merge
+//     (r AND l) OR ((r XOR l) AND v),  v = XNOR(l, t),  t ~ Bernoulli(1/m)
+// reduces, bit by bit, to "t ? l : r" (check the eight cases), so a chain of merges is carried
+// here as a running selection: after the chain, every bit is the sign bit of the worker picked by
+// the last successful draw.  The selection is done on the fp32 words themselves; only bit 31 of
+// the result is ever looked at.
+//
+// Everything is bandwidth-bound elementwise and bit work: 128-bit coalesced accesses, the random
+// draws generated in registers, no LDS, no matrix cores.
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+
+#include "marsit.h"
+#include "marsit_device.hpp"
+
+#ifndef MARSIT_STREAMING_STORES
+#define MARSIT_STREAMING_STORES 1
+#endif
+
+namespace marsit {
+
+constexpr int kBlock = 256;
+constexpr uint64_t kMaxElements = static_cast<uint64_t>(1) << 37;   // word index stays below 2^31
+
+// Bounds of the M parts of the packed words (word indices), passed by value in the kernel
+// arguments so that a compile-time index becomes a scalar load.
+struct PartTable {
+    uint32_t bound[MARSIT_MAX_WORKERS + 1];
+};
+
+// Keep thresholds floor(2^32 / fold) for the kernels whose fold counts are run-time values.
+struct ThresholdTable {
+    uint32_t thr[MARSIT_MAX_WORKERS + 1];
+};
+
+// -------------------------------------------------------------------------------------------------
+// Fused pass, schedule known at compile time: X columns, Y rows (ring: Y = 1).
+// One lane = one column of 4 elements of all M workers.  Workers are loaded in chain order
+// (row (b+ky) mod Y, column (a+kx) mod X for part a*Y+b), so register indices are static and only
+// the addresses depend on the part.
+// -------------------------------------------------------------------------------------------------
+template <int X, int Y>
+__global__ void __launch_bounds__(kBlock)
+sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
+                 uint32_t *__restrict__ bits32, uint64_t d, uint64_t ld, uint32_t scale_bits,
+                 uint32_t key0, uint32_t key1, PartTable parts)
+{
+    constexpr int M = X * Y;
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint32_t w = static_cast<uint32_t>(col >> 4);
+    const uint32_t q = static_cast<uint32_t>(col) & 15u;
+    uint32_t nib = 0;
+
+    if (col < n_cols) {
+        const uint64_t e = col << 2;
+        const bool full = e + 4 <= d;
+        const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+
+        // Algorithm 1, line 2: which part does this packed word belong to
+        uint32_t f = 0;
+#pragma unroll
+        for (int k = 1; k < M; ++k)
+            f += (w >= parts.bound[k]) ? 1u : 0u;
+        const uint32_t a = f / Y;
+        const uint32_t b = f % Y;
+
+        // line 1: s = g + c for every worker, in chain order
+        size_t off[Y][X];
+        f32x4 s[Y][X];
+#pragma unroll
+        for (int ky = 0; ky < Y; ++ky) {
+            uint32_t y = b + ky;
+            y = (y >= Y) ? y - Y : y;
+#pragma unroll
+            for (int kx = 0; kx < X; ++kx) {
+                uint32_t x = a + kx;
+                x = (x >= X) ? x - X : x;
+                off[ky][kx] = static_cast<size_t>(y * X + x) * ld + e;
+                const f32x4 gv = load4(g + off[ky][kx], full, n_valid);
+                const f32x4 cv = load4(c + off[ky][kx], full, n_valid);
+                s[ky][kx] = gv + cv;
+            }
+        }
+
+        // Eq. 2 draws: which hop's local sign survives, for each of the lane's four bits
+        uint32_t pick_row[Y][4];
+#pragma unroll
+        for (int ky = 0; ky < Y; ++ky) {
+            uint32_t y = b + ky;
+            y = (y >= Y) ? y - Y : y;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                pick_row[ky][j] = 0;
+#pragma unroll
+            for (int h = 1; h < X; ++h) {
+                uint32_t u[4];
+                philox4x32_10(q, row_hop_id(y, h), w, 0u, key0, key1, u);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    pick_row[ky][j] = (u[j] < keep_threshold(h + 1)) ? h : pick_row[ky][j];
+            }
+        }
+        uint32_t pick_col[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int k = 1; k < Y; ++k) {
+            uint32_t u[4];
+            philox4x32_10(q, col_hop_id(k), w, 0u, key0, key1, u);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                pick_col[j] = (u[j] < keep_threshold(k + 1)) ? k : pick_col[j];
+        }
+
+        // lines 4-8: the chains, as selections on the raw fp32 words
+        uint32_t fin[4];
+        {
+            uint32_t row_res[Y][4];
+#pragma unroll
+            for (int ky = 0; ky < Y; ++ky) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    uint32_t r = f32_bits(s[ky][0][j]);
+#pragma unroll
+                    for (int h = 1; h < X; ++h)
+                        r = (pick_row[ky][j] == static_cast<uint32_t>(h)) ? f32_bits(s[ky][h][j]) : r;
+                    row_res[ky][j] = r;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t r = row_res[0][j];
+#pragma unroll
+                for (int k = 1; k < Y; ++k)
+                    r = (pick_col[j] == static_cast<uint32_t>(k)) ? row_res[k][j] : r;
+                fin[j] = r;
+            }
+        }
+
+        // line 9: update = +scale where the final sign bit is clear, -scale where it is set
+        f32x4 upd;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t sign = fin[j] & 0x80000000u;
+            upd[j] = __uint_as_float(scale_bits ^ sign);
+            nib |= ((static_cast<uint32_t>(j) < n_valid) && sign == 0u) ? (1u << j) : 0u;
+        }
+        store4<MARSIT_STREAMING_STORES>(update + e, upd, full, n_valid);
+
+        // line 10: c <- s - update for every worker
+#pragma unroll
+        for (int ky = 0; ky < Y; ++ky)
+#pragma unroll
+            for (int kx = 0; kx < X; ++kx)
+                store4<MARSIT_STREAMING_STORES>(c + off[ky][kx], s[ky][kx] - upd, full, n_valid);
+    }
+
+    // final bitmap: all lanes of the wavefront take part in the cross-lane OR
+    const uint32_t half = gather_half_word(nib, q);
+    if (bits32 != nullptr && (q & 7u) == 0u && static_cast<uint64_t>(w) * 64u < d)
+        bits32[2u * static_cast<size_t>(w) + (q >> 3)] = half;
+}
+
+// -------------------------------------------------------------------------------------------------
+// Fused pass, any schedule (X, Y at run time) and any alignment.  Two sweeps over the workers: the
+// first carries the chains, the second re-reads g and c to write the compensation.
+// -------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
+                         float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
+                         uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1, uint32_t X,
+                         uint32_t Y, bool aligned, PartTable parts, ThresholdTable thresholds)
+{
+    const uint32_t M = X * Y;
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint32_t w = static_cast<uint32_t>(col >> 4);
+    const uint32_t q = static_cast<uint32_t>(col) & 15u;
+    uint32_t nib = 0;
+
+    if (col < n_cols) {
+        const uint64_t e = col << 2;
+        const bool full = e + 4 <= d;
+        const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+        const bool vec = full && aligned;
+
+        uint32_t f = 0;
+        for (uint32_t k = 1; k < M; ++k)
+            f += (w >= parts.bound[k]) ? 1u : 0u;
+        const uint32_t a = f / Y;
+        const uint32_t b = f % Y;
+
+        uint32_t fin[4] = {0, 0, 0, 0};
+        for (uint32_t ky = 0; ky < Y; ++ky) {
+            uint32_t y = b + ky;
+            y = (y >= Y) ? y - Y : y;
+            uint32_t row_res[4] = {0, 0, 0, 0};
+            for (uint32_t kx = 0; kx < X; ++kx) {
+                uint32_t x = a + kx;
+                x = (x >= X) ? x - X : x;
+                const size_t off = static_cast<size_t>(y * X + x) * ld + e;
+                const f32x4 sv = load4(g + off, vec, n_valid) + load4(c + off, vec, n_valid);
+                if (kx == 0) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        row_res[j] = f32_bits(sv[j]);
+                } else {
+                    uint32_t u[4];
+                    philox4x32_10(q, row_hop_id(y, kx), w, 0u, key0, key1, u);
+                    const uint32_t thr = thresholds.thr[kx + 1];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        row_res[j] = (u[j] < thr) ? f32_bits(sv[j]) : row_res[j];
+                }
+            }
+            if (ky == 0) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    fin[j] = row_res[j];
+            } else {
+                uint32_t u[4];
+                philox4x32_10(q, col_hop_id(ky), w, 0u, key0, key1, u);
+                const uint32_t thr = thresholds.thr[ky + 1];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    fin[j] = (u[j] < thr) ? row_res[j] : fin[j];
+            }
+        }
+
+        f32x4 upd;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t sign = fin[j] & 0x80000000u;
+            upd[j] = __uint_as_float(scale_bits ^ sign);
+            nib |= ((static_cast<uint32_t>(j) < n_valid) && sign == 0u) ? (1u << j) : 0u;
+        }
+        store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
+
+        for (uint32_t m = 0; m < M; ++m) {
+            const size_t off = static_cast<size_t>(m) * ld + e;
+            const f32x4 sv = load4(g + off, vec, n_valid) + load4(c + off, vec, n_valid);
+            store4<MARSIT_STREAMING_STORES>(c + off, sv - upd, vec, n_valid);
+        }
+    }
+
+    const uint32_t half = gather_half_word(nib, q);
+    if (bits32 != nullptr && (q & 7u) == 0u && static_cast<uint64_t>(w) * 64u < d)
+        bits32[2u * static_cast<size_t>(w) + (q >> 3)] = half;
+}
+
+// -------------------------------------------------------------------------------------------------
+// marsit_compress: a wavefront takes 64 consecutive elements per packed word, one per lane, and
+// the 64-lane ballot of "sign bit clear" IS the word.  Four words per wavefront per trip keep
+// eight independent 256-byte loads in flight.
+// -------------------------------------------------------------------------------------------------
+constexpr int kWordsPerWave = 4;
+
+__global__ void __launch_bounds__(kBlock)
+compress_kernel(const float *__restrict__ g, const float *__restrict__ c,
+                uint64_t *__restrict__ bits, uint64_t d, uint64_t n_words)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t wave = (static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x) >> 6;
+    const uint64_t w0 = wave * kWordsPerWave;
+    if (w0 >= n_words)
+        return;   // uniform over the wavefront
+
+    float s[kWordsPerWave];
+    bool valid[kWordsPerWave];
+#pragma unroll
+    for (int i = 0; i < kWordsPerWave; ++i) {
+        const uint64_t e = (w0 + i) * 64u + lane;
+        valid[i] = e < d;
+        const float gv = valid[i] ? g[e] : 0.0f;
+        const float cv = (valid[i] && c != nullptr) ? c[e] : 0.0f;
+        s[i] = gv + cv;
+    }
+#pragma unroll
+    for (int i = 0; i < kWordsPerWave; ++i) {
+        const uint64_t word = __ballot(valid[i] && (f32_bits(s[i]) >> 31) == 0u);
+        if (lane == 0 && w0 + i < n_words)
+            bits[w0 + i] = word;
+    }
+}
+
+// -------------------------------------------------------------------------------------------------
+// marsit_hop_merge: lane = (packed word i, nibble q); one Philox call per lane.
+// -------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+hop_merge_kernel(const uint32_t *recv32, const uint32_t *local32, uint32_t *out32,
+                 uint64_t word_begin, uint64_t n_words, uint32_t threshold, bool always_local,
+                 uint32_t hop_id, uint32_t key0, uint32_t key1)
+{
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint64_t i = col >> 4;
+    const uint32_t q = static_cast<uint32_t>(col) & 15u;
+    const size_t half_index = 2u * static_cast<size_t>(i) + (q >> 3);
+    const uint32_t shift = (q & 7u) * 4u;
+    uint32_t nib = 0;
+
+    if (i < n_words) {
+        const uint32_t r = (recv32[half_index] >> shift) & 0xFu;
+        const uint32_t l = (local32[half_index] >> shift) & 0xFu;
+        const uint64_t w = word_begin + i;
+        uint32_t u[4];
+        philox4x32_10(q, hop_id, static_cast<uint32_t>(w), static_cast<uint32_t>(w >> 32), key0,
+                      key1, u);
+        uint32_t t = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            t |= (always_local || u[j] < threshold) ? (1u << j) : 0u;
+        nib = r ^ ((r ^ l) & t);   // t ? l : r
+    }
+
+    const uint32_t half = half_row_or(nib << shift);
+    if (i < n_words && (q & 7u) == 0u)
+        out32[half_index] = half;
+}
+
+// -------------------------------------------------------------------------------------------------
+// marsit_decode_compensate: lane = one column of 4 elements.
+// -------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+decode_compensate_kernel(const uint32_t *__restrict__ bits32, const float *__restrict__ g,
+                         const float *c, float *__restrict__ update, float *c_out, uint64_t d,
+                         uint32_t scale_bits, bool aligned)
+{
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (col >= n_cols)
+        return;
+    const uint64_t e = col << 2;
+    const bool full = e + 4 <= d;
+    const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+    const bool vec = full && aligned;
+
+    const uint32_t nib = (bits32[col >> 3] >> ((static_cast<uint32_t>(col) & 7u) * 4u)) & 0xFu;
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    const f32x4 sv = load4(g + e, vec, n_valid) + ((c != nullptr) ? load4(c + e, vec, n_valid) : zero);
+    f32x4 upd;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        upd[j] = __uint_as_float(scale_bits ^ (((nib >> j) & 1u) ? 0u : 0x80000000u));
+    if (update != nullptr)
+        store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
+    store4<MARSIT_STREAMING_STORES>(c_out + e, sv - upd, vec, n_valid);
+}
+
+// -------------------------------------------------------------------------------------------------
+// Full-precision round (Algorithm 1, lines 11-13) and the model update (Algorithm 2, line 6).
+// -------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
+                 uint32_t M, uint64_t d, uint64_t ld, bool aligned)
+{
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (col >= n_cols)
+        return;
+    const uint64_t e = col << 2;
+    const bool full = e + 4 <= d;
+    const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+    const bool vec = full && aligned;
+
+    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 4
+    for (uint32_t m = 0; m < M; ++m) {
+        const size_t off = static_cast<size_t>(m) * ld + e;
+        const f32x4 sv = load4(g + off, vec, n_valid) + load4(c + off, vec, n_valid);
+        acc = (m == 0) ? sv : acc + sv;
+        store4<MARSIT_STREAMING_STORES>(c + off, zero, vec, n_valid);
+    }
+    const float fm = static_cast<float>(M);
+    f32x4 mean;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        mean[j] = acc[j] / fm;
+    store4<MARSIT_STREAMING_STORES>(update + e, mean, vec, n_valid);
+}
+
+__global__ void __launch_bounds__(kBlock)
+apply_update_kernel(float *__restrict__ x, const float *__restrict__ update, uint64_t d, bool aligned)
+{
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (col >= n_cols)
+        return;
+    const uint64_t e = col << 2;
+    const bool full = e + 4 <= d;
+    const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+    const bool vec = full && aligned;
+    const f32x4 xv = load4(x + e, vec, n_valid);
+    const f32x4 uv = load4(update + e, vec, n_valid);
+    store4<false>(x + e, xv - uv, vec, n_valid);
+}
+
+// -------------------------------------------------------------------------------------------------
+// Host side
+// -------------------------------------------------------------------------------------------------
+thread_local int tls_last_hip_error = 0;
+
+inline int finish_launch()
+{
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess) {
+        tls_last_hip_error = static_cast<int>(err);
+        return MARSIT_EHIP;
+    }
+    return MARSIT_OK;
+}
+
+inline bool aligned_to(const void *p, uintptr_t n) { return (reinterpret_cast<uintptr_t>(p) % n) == 0; }
+
+inline uint32_t blocks_for(uint64_t n_threads)
+{
+    return static_cast<uint32_t>((n_threads + kBlock - 1) / kBlock);
+}
+
+inline uint32_t float_bits_host(float x)
+{
+    uint32_t u;
+    std::memcpy(&u, &x, sizeof u);
+    return u;
+}
+
+// Fine part bounds of the schedule (see marsit_split_bounds in marsit.h).
+int split_bounds_host(uint64_t n_words, uint32_t M, uint32_t grid_x, uint64_t *bounds)
+{
+    if (bounds == nullptr || M == 0 || M > MARSIT_MAX_WORKERS)
+        return MARSIT_EINVAL;
+    const uint32_t X = (grid_x == 0) ? M : grid_x;
+    if (X == 0 || M % X != 0)
+        return MARSIT_EINVAL;
+    const uint32_t Y = M / X;
+    for (uint32_t a = 0; a < X; ++a) {
+        const uint64_t lo = static_cast<uint64_t>((static_cast<unsigned __int128>(a) * n_words) / X);
+        const uint64_t hi = static_cast<uint64_t>((static_cast<unsigned __int128>(a + 1) * n_words) / X);
+        const uint64_t n = hi - lo;
+        for (uint32_t b = 0; b < Y; ++b)
+            bounds[a * Y + b] = lo + static_cast<uint64_t>((static_cast<unsigned __int128>(b) * n) / Y);
+    }
+    bounds[M] = n_words;
+    return MARSIT_OK;
+}
+
+template <int X, int Y>
+void launch_sync_step(const float *g, float *c, float *update, uint32_t *bits32, uint64_t d,
+                      uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1,
+                      const PartTable &parts, hipStream_t stream)
+{
+    const uint64_t n_cols = (d + 3) >> 2;
+    hipLaunchKernelGGL((sync_step_kernel<X, Y>), dim3(blocks_for(n_cols)), dim3(kBlock), 0, stream,
+                       g, c, update, bits32, d, ld, scale_bits, key0, key1, parts);
+}
+
+using SyncLauncher = void (*)(const float *, float *, float *, uint32_t *, uint64_t, uint64_t,
+                              uint32_t, uint32_t, uint32_t, const PartTable &, hipStream_t);
+
+// Schedules with a compiled specialisation; every other shape runs the generic kernel.
+SyncLauncher find_specialisation(uint32_t X, uint32_t Y)
+{
+#define MARSIT_CASE(XX, YY) \
+    if (X == XX && Y == YY) return &launch_sync_step<XX, YY>;
+    MARSIT_CASE(1, 1) MARSIT_CASE(2, 1) MARSIT_CASE(3, 1) MARSIT_CASE(4, 1) MARSIT_CASE(5, 1)
+    MARSIT_CASE(6, 1) MARSIT_CASE(7, 1) MARSIT_CASE(8, 1) MARSIT_CASE(12, 1) MARSIT_CASE(16, 1)
+    MARSIT_CASE(2, 2) MARSIT_CASE(3, 2) MARSIT_CASE(2, 3) MARSIT_CASE(4, 2) MARSIT_CASE(2, 4)
+    MARSIT_CASE(3, 3) MARSIT_CASE(4, 4)
+#undef MARSIT_CASE
+    return nullptr;
+}
+
+}   // namespace marsit
+
+using namespace marsit;
+
+extern "C" {
+
+int marsit_version(void) { return 100; }
+
+int marsit_last_hip_error(void) { return tls_last_hip_error; }
+
+const char *marsit_status_string(int status)
+{
+    switch (status) {
+    case MARSIT_OK: return "ok";
+    case MARSIT_EINVAL: return "invalid argument";
+    case MARSIT_EALIGN: return "pointer not aligned to its element size";
+    case MARSIT_EHIP: return "HIP call failed (see marsit_last_hip_error)";
+    default: return "unknown status";
+    }
+}
+
+void marsit_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    philox4x32_10(ctr[0], ctr[1], ctr[2], ctr[3], key[0], key[1], out);
+}
+
+int marsit_split_bounds(uint64_t n_words, uint32_t M, uint32_t grid_x, uint64_t *bounds_out)
+{
+    return split_bounds_host(n_words, M, grid_x, bounds_out);
+}
+
+int marsit_compress(const float *g, const float *c, uint64_t *bits_out, uint64_t d, void *stream)
+{
+    if (g == nullptr || bits_out == nullptr || d > kMaxElements)
+        return MARSIT_EINVAL;
+    if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(bits_out, 8))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+    const uint64_t n_words = (d + 63) / 64;
+    const uint64_t n_waves = (n_words + kWordsPerWave - 1) / kWordsPerWave;
+    hipLaunchKernelGGL(compress_kernel, dim3(blocks_for(n_waves * 64)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), g, c, bits_out, d, n_words);
+    return finish_launch();
+}
+
+int marsit_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                     uint64_t word_begin, uint64_t n_words, uint32_t fold, uint32_t hop_id,
+                     uint64_t seed, void *stream)
+{
+    if (recv == nullptr || local == nullptr || out == nullptr || fold == 0 ||
+        n_words > kMaxElements / 64)
+        return MARSIT_EINVAL;
+    if (!aligned_to(recv, 8) || !aligned_to(local, 8) || !aligned_to(out, 8))
+        return MARSIT_EALIGN;
+    if (n_words == 0)
+        return MARSIT_OK;
+    const bool always_local = (fold == 1);
+    const uint32_t threshold = always_local ? 0xFFFFFFFFu : keep_threshold(fold);
+    hipLaunchKernelGGL(hop_merge_kernel, dim3(blocks_for(n_words * 16)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(recv),
+                       reinterpret_cast<const uint32_t *>(local), reinterpret_cast<uint32_t *>(out),
+                       word_begin, n_words, threshold, always_local, hop_id,
+                       static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32));
+    return finish_launch();
+}
+
+int marsit_decode_compensate(const uint64_t *bits, const float *g, const float *c, float scale,
+                             float *update_out, float *c_out, uint64_t d, void *stream)
+{
+    if (bits == nullptr || g == nullptr || c_out == nullptr || !std::isfinite(scale) ||
+        d > kMaxElements)
+        return MARSIT_EINVAL;
+    if (!aligned_to(bits, 8) || !aligned_to(g, 4) || !aligned_to(c, 4) ||
+        !aligned_to(update_out, 4) || !aligned_to(c_out, 4))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
+                         aligned_to(c_out, 16);
+    hipLaunchKernelGGL(decode_compensate_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(bits), g,
+                       c, update_out, c_out, d, float_bits_host(scale), aligned);
+    return finish_launch();
+}
+
+int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                         uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed,
+                         uint32_t grid_x, void *stream)
+{
+    if (g == nullptr || c == nullptr || update_out == nullptr || M == 0 ||
+        M > MARSIT_MAX_WORKERS || ld < d || !std::isfinite(scale) || d > kMaxElements)
+        return MARSIT_EINVAL;
+    const uint32_t X = (grid_x == 0) ? M : grid_x;
+    if (M % X != 0)
+        return MARSIT_EINVAL;
+    const uint32_t Y = M / X;
+    if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(update_out, 4) ||
+        !aligned_to(bits_out, 8))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+
+    const uint64_t n_words = (d + 63) / 64;
+    uint64_t bounds[MARSIT_MAX_WORKERS + 1];
+    split_bounds_host(n_words, M, grid_x, bounds);
+    PartTable parts;
+    for (uint32_t k = 0; k <= MARSIT_MAX_WORKERS; ++k)
+        parts.bound[k] = static_cast<uint32_t>(k <= M ? bounds[k] : n_words);
+
+    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
+                         (ld % 4 == 0);
+    const uint32_t scale_bits = float_bits_host(scale);
+    const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
+    uint32_t *bits32 = reinterpret_cast<uint32_t *>(bits_out);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    // Y == 1 is a ring whatever X was asked as; a single column is a ring over the rows.
+    uint32_t sx = X, sy = Y;
+    const SyncLauncher fast = aligned ? find_specialisation(sx, sy) : nullptr;
+    if (fast != nullptr) {
+        fast(g, c, update_out, bits32, d, ld, scale_bits, key0, key1, parts, s);
+    } else {
+        ThresholdTable thresholds;
+        thresholds.thr[0] = 0;
+        thresholds.thr[1] = 0xFFFFFFFFu;
+        for (uint32_t m = 2; m <= MARSIT_MAX_WORKERS; ++m)
+            thresholds.thr[m] = keep_threshold(m);
+        hipLaunchKernelGGL(sync_step_generic_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock),
+                           0, s, g, c, update_out, bits32, d, ld, scale_bits, key0, key1, X, Y,
+                           aligned, parts, thresholds);
+    }
+    return finish_launch();
+}
+
+int marsit_full_sync(const float *g, float *c, float *update_out, uint32_t M, uint64_t d,
+                     uint64_t ld, void *stream)
+{
+    if (g == nullptr || c == nullptr || update_out == nullptr || M == 0 ||
+        M > MARSIT_MAX_WORKERS || ld < d || d > kMaxElements)
+        return MARSIT_EINVAL;
+    if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(update_out, 4))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
+                         (ld % 4 == 0);
+    hipLaunchKernelGGL(full_sync_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), g, c, update_out, M, d, ld, aligned);
+    return finish_launch();
+}
+
+int marsit_step(uint64_t t, uint64_t K, const float *g, float *c, float *update_out,
+                uint64_t *bits_out, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                uint64_t seed, uint32_t grid_x, void *stream)
+{
+    if (K == 0)
+        return MARSIT_EINVAL;
+    if (t % K != 0)
+        return marsit_ring_step_sim(g, c, update_out, bits_out, M, d, ld, scale, seed, grid_x, stream);
+    // the full-precision round takes the same arguments; check the ones it does not use itself
+    if (!std::isfinite(scale) || (grid_x != 0 && (M == 0 || M % grid_x != 0)))
+        return MARSIT_EINVAL;
+    if (!aligned_to(bits_out, 8))
+        return MARSIT_EALIGN;
+    return marsit_full_sync(g, c, update_out, M, d, ld, stream);
+}
+
+int marsit_apply_update(float *x, const float *update, uint64_t d, void *stream)
+{
+    if (x == nullptr || update == nullptr || d > kMaxElements)
+        return MARSIT_EINVAL;
+    if (!aligned_to(x, 4) || !aligned_to(update, 4))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+    const bool aligned = aligned_to(x, 16) && aligned_to(update, 16);
+    hipLaunchKernelGGL(apply_update_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), x, update, d, aligned);
+    return finish_launch();
+}
+
+}   // extern "C"

@@ -1,0 +1,220 @@
+"""Python binding over the C ABI of ``libmarsit.so`` (see ``include/marsit.h``).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.  PyTorch supplies device
+memory (``tensor.data_ptr()``) and the current stream, nothing else.  There is no fallback: if the
+library is missing, loading raises.
+"""
+
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmarsit.so")
+
+MAX_WORKERS = 64
+OK, EINVAL, EALIGN, EHIP = 0, -1, -2, -3
+
+# every symbol include/marsit.h declares
+EXPORTS = (
+    "marsit_version", "marsit_last_hip_error", "marsit_status_string", "marsit_philox4x32_10",
+    "marsit_split_bounds", "marsit_compress", "marsit_hop_merge", "marsit_decode_compensate",
+    "marsit_ring_step_sim", "marsit_full_sync", "marsit_step", "marsit_apply_update",
+)
+
+_lib = None
+
+
+class MarsitError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        lib = _lib
+        text = lib.marsit_status_string(status).decode() if lib is not None else "?"
+        extra = f", hipError_t={lib.marsit_last_hip_error()}" if (lib is not None and status == EHIP) else ""
+        super().__init__(f"{fn} failed: {text} (status {status}{extra})")
+
+
+def load_library(path: str | None = None):
+    """Load the HIP library; raises if it has not been built (``python -m paper_2204_06787_amd.build``)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    path = path or LIB_PATH
+    if not os.path.exists(path):
+        raise RuntimeError(
+            f"{path} is missing: build the HIP library first (python -m paper_2204_06787_amd.build). "
+            "There is no CPU fallback.")
+    lib = ctypes.CDLL(path)
+    u32, u64, f32, vp, ci = ctypes.c_uint32, ctypes.c_uint64, ctypes.c_float, ctypes.c_void_p, ctypes.c_int
+    lib.marsit_version.argtypes = []
+    lib.marsit_version.restype = ci
+    lib.marsit_last_hip_error.argtypes = []
+    lib.marsit_last_hip_error.restype = ci
+    lib.marsit_status_string.argtypes = [ci]
+    lib.marsit_status_string.restype = ctypes.c_char_p
+    lib.marsit_philox4x32_10.argtypes = [vp, vp, vp]
+    lib.marsit_philox4x32_10.restype = None
+    lib.marsit_split_bounds.argtypes = [u64, u32, u32, vp]
+    lib.marsit_split_bounds.restype = ci
+    lib.marsit_compress.argtypes = [vp, vp, vp, u64, vp]
+    lib.marsit_compress.restype = ci
+    lib.marsit_hop_merge.argtypes = [vp, vp, vp, u64, u64, u32, u32, u64, vp]
+    lib.marsit_hop_merge.restype = ci
+    lib.marsit_decode_compensate.argtypes = [vp, vp, vp, f32, vp, vp, u64, vp]
+    lib.marsit_decode_compensate.restype = ci
+    lib.marsit_ring_step_sim.argtypes = [vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
+    lib.marsit_ring_step_sim.restype = ci
+    lib.marsit_full_sync.argtypes = [vp, vp, vp, u32, u64, u64, vp]
+    lib.marsit_full_sync.restype = ci
+    lib.marsit_step.argtypes = [u64, u64, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
+    lib.marsit_step.restype = ci
+    lib.marsit_apply_update.argtypes = [vp, vp, u64, vp]
+    lib.marsit_apply_update.restype = ci
+    if path == LIB_PATH:
+        _lib = lib
+    return lib
+
+
+def n_words(d: int) -> int:
+    return (int(d) + 63) // 64
+
+
+def _check(fn: str, status: int):
+    if status != OK:
+        raise MarsitError(fn, status)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def _f32_ptr(t, name, allow_none=False):
+    if t is None:
+        if allow_none:
+            return None
+        raise TypeError(f"{name} is required")
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32):
+        raise TypeError(f"{name}: need a float32 tensor in device memory")
+    return t.data_ptr()
+
+
+def _bits_ptr(t, name, allow_none=False):
+    if t is None:
+        if allow_none:
+            return None
+        raise TypeError(f"{name} is required")
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype in (torch.int64, torch.uint64)
+            and t.is_contiguous()):
+        raise TypeError(f"{name}: need a contiguous 64-bit integer tensor in device memory")
+    return t.data_ptr()
+
+
+def _rows(t, name):
+    """[M, >=d] tensor with unit inner stride -> (M, row stride in elements)."""
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise TypeError(f"{name}: need a 2-D tensor whose rows are contiguous")
+    return t.shape[0], (t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1]))
+
+
+def new_bitmap(d: int, device="cuda") -> torch.Tensor:
+    """Device buffer for a packed sign bitmap of d elements (int64 storage, 64 signs per word)."""
+    return torch.empty(n_words(d), dtype=torch.int64, device=device)
+
+
+# --- host-side helpers -------------------------------------------------------------------------
+
+def marsit_version() -> int:
+    return load_library().marsit_version()
+
+
+def marsit_philox4x32_10(ctr, key):
+    c = (ctypes.c_uint32 * 4)(*[int(x) & 0xFFFFFFFF for x in ctr])
+    k = (ctypes.c_uint32 * 2)(*[int(x) & 0xFFFFFFFF for x in key])
+    out = (ctypes.c_uint32 * 4)()
+    load_library().marsit_philox4x32_10(c, k, out)
+    return [int(x) for x in out]
+
+
+def marsit_split_bounds(n_words_: int, M: int, grid_x: int = 0):
+    out = (ctypes.c_uint64 * (MAX_WORKERS + 1))()
+    _check("marsit_split_bounds", load_library().marsit_split_bounds(n_words_, M, grid_x, out))
+    return [int(out[i]) for i in range(M + 1)]
+
+
+# --- device entry points -----------------------------------------------------------------------
+
+def marsit_compress(g, c, bits_out, d: int | None = None, stream=None):
+    d = g.numel() if d is None else int(d)
+    _check("marsit_compress", load_library().marsit_compress(
+        _f32_ptr(g, "g"), _f32_ptr(c, "c", True), _bits_ptr(bits_out, "bits_out"), d, _stream(stream)))
+    return bits_out
+
+
+def marsit_hop_merge(recv, local, out, word_begin: int, n_words_: int, fold: int, hop_id: int,
+                     seed: int, stream=None):
+    _check("marsit_hop_merge", load_library().marsit_hop_merge(
+        _bits_ptr(recv, "recv"), _bits_ptr(local, "local"), _bits_ptr(out, "out"), word_begin,
+        n_words_, fold, hop_id, seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
+    return out
+
+
+def marsit_decode_compensate(bits, g, c, scale: float, update_out, c_out, d: int | None = None,
+                             stream=None):
+    d = g.numel() if d is None else int(d)
+    _check("marsit_decode_compensate", load_library().marsit_decode_compensate(
+        _bits_ptr(bits, "bits"), _f32_ptr(g, "g"), _f32_ptr(c, "c", True), scale,
+        _f32_ptr(update_out, "update_out", True), _f32_ptr(c_out, "c_out"), d, _stream(stream)))
+    return update_out, c_out
+
+
+def marsit_ring_step_sim(g, c, update_out, bits_out, scale: float, seed: int, grid_x: int = 0,
+                         d: int | None = None, stream=None):
+    """``g``, ``c``: ``[M, ld]`` float32 (rows contiguous); ``c`` is updated in place."""
+    M, ld = _rows(g, "g")
+    Mc, ldc = _rows(c, "c")
+    if (M, ld) != (Mc, ldc):
+        raise TypeError("g and c must have the same shape and row stride")
+    d = g.shape[1] if d is None else int(d)
+    _check("marsit_ring_step_sim", load_library().marsit_ring_step_sim(
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
+        _bits_ptr(bits_out, "bits_out", True), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF, grid_x,
+        _stream(stream)))
+    return update_out, bits_out
+
+
+def marsit_full_sync(g, c, update_out, d: int | None = None, stream=None):
+    M, ld = _rows(g, "g")
+    if _rows(c, "c") != (M, ld):
+        raise TypeError("g and c must have the same shape and row stride")
+    d = g.shape[1] if d is None else int(d)
+    _check("marsit_full_sync", load_library().marsit_full_sync(
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"), M, d, ld,
+        _stream(stream)))
+    return update_out
+
+
+def marsit_step(t: int, K: int, g, c, update_out, bits_out, scale: float, seed: int,
+                grid_x: int = 0, d: int | None = None, stream=None):
+    M, ld = _rows(g, "g")
+    if _rows(c, "c") != (M, ld):
+        raise TypeError("g and c must have the same shape and row stride")
+    d = g.shape[1] if d is None else int(d)
+    _check("marsit_step", load_library().marsit_step(
+        t, K, _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
+        _bits_ptr(bits_out, "bits_out", True), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF, grid_x,
+        _stream(stream)))
+    return update_out, bits_out
+
+
+def marsit_apply_update(x, update, d: int | None = None, stream=None):
+    d = x.numel() if d is None else int(d)
+    _check("marsit_apply_update", load_library().marsit_apply_update(
+        _f32_ptr(x, "x"), _f32_ptr(update, "update"), d, _stream(stream)))
+    return x

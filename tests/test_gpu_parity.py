@@ -1,0 +1,277 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI, on the same seeded inputs.
+
+Bar: packed bitmaps, merged signs and decoded updates bit-exact; compensation within 1e-6 relative
+(checked, and additionally bit for bit because each value is one fp32 rounding of the same
+operands on both sides).
+"""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import marsit_oracle as orc
+from paper_2204_06787_amd import marsit, workloads
+from gpu_util import (assert_f32_parity, dev, fused_step, host_bits, host_f32, oracle_step,
+                      unaligned_rows, unfused_step)
+
+pytestmark = pytest.mark.gpu
+
+SPECIALS = np.array([0.0, -0.0, np.inf, -np.inf, 1e-45, -1e-45, 1e-40, -1e-40, 3.4e38, -3.4e38,
+                     1.17549435e-38, -1.17549435e-38], dtype=np.float32)
+
+
+def _inputs(M, d, ld=None, seed=0, c_scale=0.3):
+    ld = d if ld is None else ld
+    rng = np.random.default_rng(seed * 7919 + M * 131 + d)
+    g = rng.standard_normal((M, ld)).astype(np.float32)
+    c = (c_scale * rng.standard_normal((M, ld))).astype(np.float32)
+    return g, c
+
+
+# ------------------------------------------------------------------------------------------------
+# marsit_compress
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("d", [1, 2, 63, 64, 65, 255, 256, 257, 1023, 4097, 65536 + 5, 1_000_003])
+@pytest.mark.parametrize("with_c", [True, False])
+def test_compress(d, with_c):
+    g, c = _inputs(1, d, seed=1)
+    g, c = g[0], c[0]
+    n = min(d, SPECIALS.size)
+    g[:n] = SPECIALS[:n]
+    c[:n] = 0.0
+    if d > 40:
+        g[20:30] = 1.5
+        c[20:30] = -1.5          # exact cancellation -> +0 -> bit 1
+    want = orc.sign_pack(orc.add_compensation(g, c if with_c else None))
+    bits = marsit.new_bitmap(d)
+    bits.fill_(-1)
+    marsit.marsit_compress(dev(g), dev(c) if with_c else None, bits, d=d)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_bits(bits), want)
+
+
+def test_compress_unaligned_pointer():
+    d = 5000
+    g, c = _inputs(1, d + 3, seed=2)
+    gd, cd = dev(g[0]), dev(c[0])
+    for off in (1, 2, 3):
+        want = orc.sign_pack(orc.add_compensation(np.ascontiguousarray(g[0, off:off + d]),
+                                                  np.ascontiguousarray(c[0, off:off + d])))
+        bits = marsit.new_bitmap(d)
+        marsit.marsit_compress(gd[off:off + d], cd[off:off + d], bits, d=d)
+        torch.cuda.synchronize()
+        assert np.array_equal(host_bits(bits), want)
+
+
+# ------------------------------------------------------------------------------------------------
+# marsit_hop_merge
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("n_words", [1, 2, 15, 16, 17, 63, 1000, 50_000])
+@pytest.mark.parametrize("fold,hop", [(1, 0), (2, 1), (3, 2), (5, 4), (8, 7), (16, (1 << 16) | 3),
+                                      (4, (3 << 8) | 3), (64, 63)])
+def test_hop_merge(n_words, fold, hop):
+    rng = np.random.default_rng(n_words * 100 + fold)
+    recv = rng.integers(0, 2**64, size=n_words, dtype=np.uint64)
+    local = rng.integers(0, 2**64, size=n_words, dtype=np.uint64)
+    seed = 0xABCDEF0123456789
+    for word_begin in (0, 341, (1 << 33) + 7):
+        want = orc.hop_merge(recv, local, word_begin, fold, hop, seed)
+        out = torch.zeros(n_words, dtype=torch.int64, device="cuda")
+        marsit.marsit_hop_merge(dev(recv), dev(local), out, word_begin, n_words, fold, hop, seed)
+        torch.cuda.synchronize()
+        assert np.array_equal(host_bits(out), want), (word_begin,)
+
+
+def test_hop_merge_in_place():
+    rng = np.random.default_rng(3)
+    n = 777
+    recv = rng.integers(0, 2**64, size=n, dtype=np.uint64)
+    local = rng.integers(0, 2**64, size=n, dtype=np.uint64)
+    want = orc.hop_merge(recv, local, 12, 3, 2, 99)
+    r, l = dev(recv), dev(local)
+    marsit.marsit_hop_merge(r, l, r, 12, n, 3, 2, 99)           # out aliases recv
+    torch.cuda.synchronize()
+    assert np.array_equal(host_bits(r), want)
+    assert np.array_equal(host_bits(l), local)
+    r2 = dev(recv)
+    marsit.marsit_hop_merge(r2, l, l, 12, n, 3, 2, 99)          # out aliases local
+    torch.cuda.synchronize()
+    assert np.array_equal(host_bits(l), want)
+
+
+# ------------------------------------------------------------------------------------------------
+# marsit_decode_compensate
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("d", [1, 3, 4, 5, 63, 64, 65, 1023, 4100, 100_003])
+@pytest.mark.parametrize("offset", [0, 1])
+def test_decode_compensate(d, offset):
+    rng = np.random.default_rng(d)
+    g, c = _inputs(1, d + 1, seed=4)
+    g1 = np.ascontiguousarray(g[0, offset:offset + d])
+    c1 = np.ascontiguousarray(c[0, offset:offset + d])
+    n = min(d, SPECIALS.size)
+    g1[:n] = SPECIALS[:n]
+    c1[:n] = 0.0
+    bits = rng.integers(0, 2**64, size=orc.n_words(d), dtype=np.uint64)
+    scale = 2.5e-3
+    want_u = orc.decode(bits, scale, d)
+    want_c = orc.compensate(orc.add_compensation(g1, c1), want_u)
+
+    gd = torch.zeros(d + 1, dtype=torch.float32, device="cuda")
+    cd = torch.zeros(d + 1, dtype=torch.float32, device="cuda")
+    gd[offset:offset + d] = dev(g1)
+    cd[offset:offset + d] = dev(c1)
+    ud = torch.zeros(d + 1, dtype=torch.float32, device="cuda")
+    gv, cv, uv = gd[offset:offset + d], cd[offset:offset + d], ud[offset:offset + d]
+    marsit.marsit_decode_compensate(dev(bits), gv, cv, scale, uv, cv, d=d)      # in place on c
+    torch.cuda.synchronize()
+    assert np.array_equal(host_f32(uv).view(np.uint32), want_u.view(np.uint32))
+    assert_f32_parity(host_f32(cv), want_c, "c_out")
+
+    # c = NULL and update_out = NULL
+    want_c0 = orc.compensate(orc.add_compensation(g1, None), want_u)
+    out = torch.zeros(d, dtype=torch.float32, device="cuda")
+    marsit.marsit_decode_compensate(dev(bits), gv, None, scale, None, out, d=d)
+    torch.cuda.synchronize()
+    assert_f32_parity(host_f32(out), want_c0, "c_out (c = NULL)")
+
+
+# ------------------------------------------------------------------------------------------------
+# fused pass vs oracle
+# ------------------------------------------------------------------------------------------------
+
+def _check_fused(M, d, grid_x, ld=None, aligned=True, scale=1e-3, seed=0x5EED, steps=1, specials=False):
+    ld = d if ld is None else ld
+    g_h, c_h = _inputs(M, d, ld=ld, seed=seed & 0xFFFF)
+    if specials and d >= SPECIALS.size:
+        for m in range(M):
+            g_h[m, :SPECIALS.size] = np.roll(SPECIALS, m)
+            c_h[m, :SPECIALS.size] = 0.0
+    if aligned:
+        g_d, c_d = dev(g_h), dev(c_h)
+    else:
+        g_d, c_d = unaligned_rows(M, ld), unaligned_rows(M, ld)
+        g_d.copy_(dev(g_h))
+        c_d.copy_(dev(c_h))
+    c_before_pad = c_h[:, d:].copy()
+    for t in range(steps):
+        sd = workloads.step_seed(seed, t)
+        want_u, want_b, _ = oracle_step(g_h, c_h, scale, sd, grid_x=grid_x, d=d)
+        got_u, got_b = fused_step(g_d, c_d, scale, sd, grid_x=grid_x, d=d)
+        assert np.array_equal(host_bits(got_b), want_b), f"bitmap, step {t}"
+        assert np.array_equal(host_f32(got_u).view(np.uint32), want_u.view(np.uint32)), f"update, step {t}"
+        assert_f32_parity(host_f32(c_d)[:, :d], c_h[:, :d], f"compensation, step {t}")
+    if ld > d:
+        assert np.array_equal(host_f32(c_d)[:, d:], c_before_pad), "padding columns were touched"
+
+
+def test_tiny_ring_config():
+    """M=3, d=65,536, N(0,1), c=0, scale 1e-3, one step."""
+    wl = workloads.WORKLOADS["tiny_ring"]
+    g = workloads.make_gradients(wl, 0, seed=1, device="cuda")
+    c = workloads.zero_compensation(wl, device="cuda")
+    g_h, c_h = host_f32(g).copy(), host_f32(c).copy()
+    sd = workloads.step_seed(2022, 0)
+    want_u, want_b, want_maps = orc.sync_step(g_h, c_h, wl.scale, sd, want_sign_maps=True)
+    got_u, got_b = fused_step(g, c, wl.scale, sd)
+    assert np.array_equal(host_bits(got_b), want_b)
+    assert np.array_equal(host_f32(got_u).view(np.uint32), want_u.view(np.uint32))
+    assert_f32_parity(host_f32(c), c_h, "compensation")
+    # the un-fused chain gives the same, and its per-worker bitmaps are the oracle's
+    c2 = workloads.zero_compensation(wl, device="cuda")
+    u2, b2, maps = unfused_step(g, c2, wl.scale, sd)
+    for m in range(wl.M):
+        assert np.array_equal(host_bits(maps[m]), want_maps[m])
+    assert np.array_equal(host_bits(b2), want_b)
+    assert torch.equal(u2, got_u) and torch.equal(c2, c)
+
+
+@pytest.mark.parametrize("d", [1, 3, 4, 5, 63, 64, 65, 255, 1023, 1024, 4100, 16384 + 1, 100_003])
+@pytest.mark.parametrize("M", [1, 2, 3, 5, 8, 16])
+def test_fused_ring_shapes(M, d):
+    _check_fused(M, d, grid_x=0, seed=0x1000 + M)
+
+
+@pytest.mark.parametrize("X,Y", [(2, 2), (3, 2), (2, 3), (4, 2), (2, 4), (3, 3), (4, 4)])
+@pytest.mark.parametrize("d", [5, 64, 1000, 64 * 4 * 16 + 3, 50_001])
+def test_fused_torus_shapes(X, Y, d):
+    _check_fused(X * Y, d, grid_x=X, seed=0x2000 + X * 10 + Y)
+
+
+@pytest.mark.parametrize("M,grid_x", [(9, 0), (10, 5), (10, 2), (24, 6), (64, 0), (64, 8), (11, 0), (7, 1)])
+@pytest.mark.parametrize("d", [7, 640, 33_333])
+def test_fused_generic_schedule(M, grid_x, d):
+    """Schedules without a compiled specialisation run the generic kernel."""
+    _check_fused(M, d, grid_x=grid_x, seed=0x3000 + M)
+
+
+@pytest.mark.parametrize("M,grid_x", [(3, 0), (8, 0), (16, 4), (9, 3)])
+@pytest.mark.parametrize("d,ld", [(1000, 1001), (4099, 4102), (64, 67), (20_000, 20_004)])
+def test_fused_row_stride_and_misaligned_base(M, grid_x, d, ld):
+    _check_fused(M, d, grid_x=grid_x, ld=ld, seed=0x4000 + M)
+    _check_fused(M, d, grid_x=grid_x, ld=ld, aligned=False, seed=0x4100 + M)
+
+
+@pytest.mark.parametrize("M,grid_x", [(3, 0), (8, 0), (16, 4)])
+def test_fused_special_values_and_scales(M, grid_x):
+    for scale in (1e-3, -2.0, 0.0, 1e-42, 3.0e38):
+        _check_fused(M, 4096 + 17, grid_x=grid_x, scale=scale, specials=True, seed=0x5000 + M)
+
+
+@pytest.mark.parametrize("M,grid_x", [(3, 0), (8, 0), (16, 4), (12, 0)])
+def test_fused_compensation_carried_over_steps(M, grid_x):
+    _check_fused(M, 70_000 + 9, grid_x=grid_x, steps=4, seed=0x6000 + M)
+
+
+def test_fused_without_bitmap_output():
+    M, d = 8, 10_000
+    g_h, c_h = _inputs(M, d, seed=7)
+    g_d, c_d = dev(g_h), dev(c_h)
+    want_u, _, _ = oracle_step(g_h, c_h, 1e-3, 5)
+    got_u, _ = fused_step(g_d, c_d, 1e-3, 5, want_bits=False)
+    assert np.array_equal(host_f32(got_u), want_u)
+    assert_f32_parity(host_f32(c_d), c_h, "compensation")
+
+
+def test_empty_input_is_a_no_op():
+    lib = marsit.load_library()
+    g = torch.ones(4, 8, device="cuda")
+    c = torch.ones(4, 8, device="cuda")
+    u = torch.ones(8, device="cuda")
+    rc = lib.marsit_ring_step_sim(g.data_ptr(), c.data_ptr(), u.data_ptr(), None, 4, 0, 8, 1.0, 1, 0,
+                                  torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert rc == 0 and bool((c == 1).all()) and bool((u == 1).all())
+
+
+def test_runs_on_a_side_stream():
+    M, d = 8, 200_000
+    g_h, c_h = _inputs(M, d, seed=8)
+    g_d, c_d = dev(g_h), dev(c_h)
+    u = torch.empty(d, device="cuda")
+    b = marsit.new_bitmap(d)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        marsit.marsit_ring_step_sim(g_d, c_d, u, b, 1e-3, 77)
+    side.synchronize()
+    want_u, want_b, _ = oracle_step(g_h, c_h, 1e-3, 77)
+    assert np.array_equal(host_bits(b), want_b) and np.array_equal(host_f32(u), want_u)
+
+
+# ------------------------------------------------------------------------------------------------
+# fused pass == chain of the un-fused entry points (bit for bit), moderate sizes
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,grid_x,d", [(8, 0, 1_000_000 + 37), (16, 4, 500_000 + 1), (5, 0, 300_001),
+                                        (6, 3, 250_000), (10, 5, 99_999)])
+def test_fused_equals_unfused_chain(M, grid_x, d):
+    g_h, c_h = _inputs(M, d, seed=9)
+    g1, c1 = dev(g_h), dev(c_h)
+    g2, c2 = dev(g_h), dev(c_h)
+    u1, b1 = fused_step(g1, c1, 1e-3, 4242, grid_x=grid_x)
+    u2, b2, _ = unfused_step(g2, c2, 1e-3, 4242, grid_x=grid_x)
+    assert torch.equal(b1, b2) and torch.equal(u1, u2) and torch.equal(c1, c2)
