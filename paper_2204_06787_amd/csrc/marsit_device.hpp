@@ -96,6 +96,19 @@ __device__ __forceinline__ void store4(float *p, f32x4 v, bool vec, uint32_t n_v
     if (n_valid > 3) p[3] = v.w;
 }
 
+// Aligned, streaming (read-once / write-once) 128-bit accesses: the non-temporal hint keeps
+// the lines from displacing each other in L2 and the memory-side cache; with 2M+ concurrent
+// streams it is worth about 10 % of bandwidth on MI355X.
+__device__ __forceinline__ f32x4 load4_stream(const float *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+}
+
+__device__ __forceinline__ void store4_stream(float *p, f32x4 v)
+{
+    __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(p));
+}
+
 // ---- DPP: OR over the 8 lanes of a half row ------------------------------------------------------
 
 template <int CTRL>

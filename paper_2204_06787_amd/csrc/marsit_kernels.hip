@@ -44,16 +44,22 @@ struct ThresholdTable {
 // Fused pass, schedule known at compile time: X columns, Y rows (ring: Y = 1).
 // One lane = one column of 4 elements of all M workers.  Workers are loaded in chain order
 // (row (b+ky) mod Y, column (a+kx) mod X for part a*Y+b), so register indices are static and only
-// the addresses depend on the part.
+// the addresses depend on the part.  Handles whole packed words only (n_cols is a multiple of 16,
+// every column has its 4 elements, every pointer is 16-byte aligned); a ragged tail goes to the
+// generic kernel.
+//
+// Order inside a lane: issue all 2M 128-bit loads, then generate the M-1 Philox draws while the
+// loads are in flight (they do not depend on the data), then consume.  The two scheduling
+// barriers keep the compiler from sinking the loads next to their uses, which would leave only
+// two loads in flight per wavefront.
 // -------------------------------------------------------------------------------------------------
 template <int X, int Y>
 __global__ void __launch_bounds__(kBlock)
 sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
-                 uint32_t *__restrict__ bits32, uint64_t d, uint64_t ld, uint32_t scale_bits,
+                 uint32_t *__restrict__ bits32, uint64_t n_cols, uint64_t ld, uint32_t scale_bits,
                  uint32_t key0, uint32_t key1, PartTable parts)
 {
     constexpr int M = X * Y;
-    const uint64_t n_cols = (d + 3) >> 2;
     const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
     const uint32_t w = static_cast<uint32_t>(col >> 4);
     const uint32_t q = static_cast<uint32_t>(col) & 15u;
@@ -61,8 +67,6 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
 
     if (col < n_cols) {
         const uint64_t e = col << 2;
-        const bool full = e + 4 <= d;
-        const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
 
         // Algorithm 1, line 2: which part does this packed word belong to
         uint32_t f = 0;
@@ -72,9 +76,9 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
         const uint32_t a = f / Y;
         const uint32_t b = f % Y;
 
-        // line 1: s = g + c for every worker, in chain order
+        // line 1, first half: fetch g and c of every worker, in chain order
         size_t off[Y][X];
-        f32x4 s[Y][X];
+        f32x4 gv[Y][X], cv[Y][X];
 #pragma unroll
         for (int ky = 0; ky < Y; ++ky) {
             uint32_t y = b + ky;
@@ -84,11 +88,11 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
                 uint32_t x = a + kx;
                 x = (x >= X) ? x - X : x;
                 off[ky][kx] = static_cast<size_t>(y * X + x) * ld + e;
-                const f32x4 gv = load4(g + off[ky][kx], full, n_valid);
-                const f32x4 cv = load4(c + off[ky][kx], full, n_valid);
-                s[ky][kx] = gv + cv;
+                gv[ky][kx] = load4_stream(g + off[ky][kx]);
+                cv[ky][kx] = load4_stream(c + off[ky][kx]);
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
 
         // Eq. 2 draws: which hop's local sign survives, for each of the lane's four bits
         uint32_t pick_row[Y][4];
@@ -117,6 +121,15 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
             for (int j = 0; j < 4; ++j)
                 pick_col[j] = (u[j] < keep_threshold(k + 1)) ? k : pick_col[j];
         }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // line 1, second half: s = g + c
+        f32x4 s[Y][X];
+#pragma unroll
+        for (int ky = 0; ky < Y; ++ky)
+#pragma unroll
+            for (int kx = 0; kx < X; ++kx)
+                s[ky][kx] = gv[ky][kx] + cv[ky][kx];
 
         // lines 4-8: the chains, as selections on the raw fp32 words
         uint32_t fin[4];
@@ -149,37 +162,39 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
         for (int j = 0; j < 4; ++j) {
             const uint32_t sign = fin[j] & 0x80000000u;
             upd[j] = __uint_as_float(scale_bits ^ sign);
-            nib |= ((static_cast<uint32_t>(j) < n_valid) && sign == 0u) ? (1u << j) : 0u;
+            nib |= (sign == 0u) ? (1u << j) : 0u;
         }
-        store4<MARSIT_STREAMING_STORES>(update + e, upd, full, n_valid);
+        store4_stream(update + e, upd);
 
         // line 10: c <- s - update for every worker
 #pragma unroll
         for (int ky = 0; ky < Y; ++ky)
 #pragma unroll
             for (int kx = 0; kx < X; ++kx)
-                store4<MARSIT_STREAMING_STORES>(c + off[ky][kx], s[ky][kx] - upd, full, n_valid);
+                store4_stream(c + off[ky][kx], s[ky][kx] - upd);
     }
 
     // final bitmap: all lanes of the wavefront take part in the cross-lane OR
     const uint32_t half = gather_half_word(nib, q);
-    if (bits32 != nullptr && (q & 7u) == 0u && static_cast<uint64_t>(w) * 64u < d)
+    if (bits32 != nullptr && (q & 7u) == 0u && col < n_cols)
         bits32[2u * static_cast<size_t>(w) + (q >> 3)] = half;
 }
 
 // -------------------------------------------------------------------------------------------------
-// Fused pass, any schedule (X, Y at run time) and any alignment.  Two sweeps over the workers: the
-// first carries the chains, the second re-reads g and c to write the compensation.
+// Fused pass, any schedule (X, Y at run time), any alignment, ragged tails.  Covers columns
+// col_begin .. ceil(d/4)-1 (col_begin is a multiple of 16).  Two sweeps over the workers: the first
+// carries the chains, the second re-reads g and c to write the compensation.
 // -------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kBlock)
 sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
                          float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
-                         uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1, uint32_t X,
-                         uint32_t Y, bool aligned, PartTable parts, ThresholdTable thresholds)
+                         uint64_t ld, uint64_t col_begin, uint32_t scale_bits, uint32_t key0,
+                         uint32_t key1, uint32_t X, uint32_t Y, bool aligned, PartTable parts,
+                         ThresholdTable thresholds)
 {
     const uint32_t M = X * Y;
     const uint64_t n_cols = (d + 3) >> 2;
-    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
     const uint32_t w = static_cast<uint32_t>(col >> 4);
     const uint32_t q = static_cast<uint32_t>(col) & 15u;
     uint32_t nib = 0;
@@ -451,13 +466,12 @@ int split_bounds_host(uint64_t n_words, uint32_t M, uint32_t grid_x, uint64_t *b
 }
 
 template <int X, int Y>
-void launch_sync_step(const float *g, float *c, float *update, uint32_t *bits32, uint64_t d,
+void launch_sync_step(const float *g, float *c, float *update, uint32_t *bits32, uint64_t n_cols,
                       uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1,
                       const PartTable &parts, hipStream_t stream)
 {
-    const uint64_t n_cols = (d + 3) >> 2;
     hipLaunchKernelGGL((sync_step_kernel<X, Y>), dim3(blocks_for(n_cols)), dim3(kBlock), 0, stream,
-                       g, c, update, bits32, d, ld, scale_bits, key0, key1, parts);
+                       g, c, update, bits32, n_cols, ld, scale_bits, key0, key1, parts);
 }
 
 using SyncLauncher = void (*)(const float *, float *, float *, uint32_t *, uint64_t, uint64_t,
@@ -593,22 +607,34 @@ int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *
     uint32_t *bits32 = reinterpret_cast<uint32_t *>(bits_out);
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    // Y == 1 is a ring whatever X was asked as; a single column is a ring over the rows.
-    uint32_t sx = X, sy = Y;
-    const SyncLauncher fast = aligned ? find_specialisation(sx, sy) : nullptr;
+    // Whole packed words of an aligned input go to the kernel compiled for this schedule, the
+    // ragged last word (and every input without a compiled schedule or with odd alignment) to the
+    // generic kernel.  The two write disjoint outputs.
+    const SyncLauncher fast = aligned ? find_specialisation(X, Y) : nullptr;
+    uint64_t generic_col_begin = 0;
     if (fast != nullptr) {
-        fast(g, c, update_out, bits32, d, ld, scale_bits, key0, key1, parts, s);
-    } else {
+        const uint64_t fast_cols = (d / 64) * 16;
+        if (fast_cols > 0) {
+            fast(g, c, update_out, bits32, fast_cols, ld, scale_bits, key0, key1, parts, s);
+            const int rc = finish_launch();
+            if (rc != MARSIT_OK)
+                return rc;
+        }
+        generic_col_begin = fast_cols;
+    }
+    const uint64_t n_cols = (d + 3) >> 2;
+    if (generic_col_begin < n_cols) {
         ThresholdTable thresholds;
         thresholds.thr[0] = 0;
         thresholds.thr[1] = 0xFFFFFFFFu;
         for (uint32_t m = 2; m <= MARSIT_MAX_WORKERS; ++m)
             thresholds.thr[m] = keep_threshold(m);
-        hipLaunchKernelGGL(sync_step_generic_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock),
-                           0, s, g, c, update_out, bits32, d, ld, scale_bits, key0, key1, X, Y,
-                           aligned, parts, thresholds);
+        hipLaunchKernelGGL(sync_step_generic_kernel, dim3(blocks_for(n_cols - generic_col_begin)),
+                           dim3(kBlock), 0, s, g, c, update_out, bits32, d, ld, generic_col_begin,
+                           scale_bits, key0, key1, X, Y, aligned, parts, thresholds);
+        return finish_launch();
     }
-    return finish_launch();
+    return MARSIT_OK;
 }
 
 int marsit_full_sync(const float *g, float *c, float *update_out, uint32_t M, uint64_t d,
