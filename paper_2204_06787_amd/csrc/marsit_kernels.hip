@@ -26,7 +26,8 @@
 
 namespace marsit {
 
-constexpr int kBlock = 256;
+constexpr int kBlock = 256;       // every kernel but the fused one
+constexpr int kSyncBlock = 64;    // fused kernel: one wavefront per workgroup
 constexpr uint64_t kMaxElements = static_cast<uint64_t>(1) << 37;   // word index stays below 2^31
 
 // Bounds of the M parts of the packed words (word indices), passed by value in the kernel
@@ -48,19 +49,23 @@ struct ThresholdTable {
 // every column has its 4 elements, every pointer is 16-byte aligned); a ragged tail goes to the
 // generic kernel.
 //
+// Occupancy is throttled from the host (dynamic LDS that the kernel never touches): with 25
+// concurrent streams HBM delivers most when each CU keeps only about 40-50 KB of reads in flight;
+// more resident wavefronts widen the window of open DRAM rows and cost up to 10 % of bandwidth.
+//
 // Order inside a lane: issue all 2M 128-bit loads, then generate the M-1 Philox draws while the
 // loads are in flight (they do not depend on the data), then consume.  The two scheduling
 // barriers keep the compiler from sinking the loads next to their uses, which would leave only
 // two loads in flight per wavefront.
 // -------------------------------------------------------------------------------------------------
 template <int X, int Y>
-__global__ void __launch_bounds__(kBlock)
+__global__ void __launch_bounds__(kSyncBlock)
 sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
                  uint32_t *__restrict__ bits32, uint64_t n_cols, uint64_t ld, uint32_t scale_bits,
                  uint32_t key0, uint32_t key1, PartTable parts)
 {
     constexpr int M = X * Y;
-    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
     const uint32_t w = static_cast<uint32_t>(col >> 4);
     const uint32_t q = static_cast<uint32_t>(col) & 15u;
     uint32_t nib = 0;
@@ -465,13 +470,38 @@ int split_bounds_host(uint64_t n_words, uint32_t M, uint32_t grid_x, uint64_t *b
     return MARSIT_OK;
 }
 
+// Dynamic LDS bytes per workgroup that leave room for exactly `waves` one-wavefront workgroups of
+// the fused kernel on a CU.  Measured on MI355X (25.6 M elements): the best count is 3 for M = 8
+// and 16, 5 for M = 4, 10 for M = 2 -- about 40 KB of loads in flight per CU, never fewer than 3.
+inline uint32_t throttle_lds_bytes(uint32_t M)
+{
+    constexpr uint32_t lds_per_cu = 160u * 1024u;   // gfx950; the runtime attribute reports 64 KB
+    uint32_t waves = (20u + M / 2u) / M;
+    if (waves < 3u)
+        waves = 3u;
+    // a few per cent below an even share: with an exact share one workgroup fewer fits
+    return ((lds_per_cu / waves) * 31u / 32u) & ~511u;
+}
+
 template <int X, int Y>
 void launch_sync_step(const float *g, float *c, float *update, uint32_t *bits32, uint64_t n_cols,
                       uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1,
                       const PartTable &parts, hipStream_t stream)
 {
-    hipLaunchKernelGGL((sync_step_kernel<X, Y>), dim3(blocks_for(n_cols)), dim3(kBlock), 0, stream,
-                       g, c, update, bits32, n_cols, ld, scale_bits, key0, key1, parts);
+    const uint32_t lds = throttle_lds_bytes(X * Y);
+    static uint32_t lds_allowed = 0;
+    if (lds > lds_allowed) {
+        // above 64 KB of dynamic LDS the limit has to be raised once per kernel
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&sync_step_kernel<X, Y>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                static_cast<int>(lds)) == hipSuccess)
+            lds_allowed = lds;
+        else
+            (void)hipGetLastError();
+    }
+    const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
+    hipLaunchKernelGGL((sync_step_kernel<X, Y>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,
+                       update, bits32, n_cols, ld, scale_bits, key0, key1, parts);
 }
 
 using SyncLauncher = void (*)(const float *, float *, float *, uint32_t *, uint64_t, uint64_t,
