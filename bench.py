@@ -33,11 +33,15 @@ MEASURED_TRAFFIC_BYTES = {
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet50")
     ap.add_argument("--seed", type=int, default=2022)
-    ap.add_argument("--pool", type=int, default=0, help="gradient sets kept in HBM (0: one per step)")
+    ap.add_argument("--pool", type=int, default=10,
+                    help="distinct gradient sets kept in HBM and cycled through (0: one per step)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also launch one plain device copy of one gradient set (known size: reads and "
+                         "writes 4*M*d bytes), the yardstick for the rocprofv3 --pmc byte counters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=0)
     return ap.parse_args()
@@ -101,6 +105,12 @@ def main():
         marsit.marsit_ring_step_sim(grads[t % pool], c, update, bits, wl.scale,
                                     workloads.step_seed(args.seed, t), grid_x=wl.grid_x,
                                     stream=stream)
+
+    if args.copy_calibration:
+        scratch = torch.empty_like(grads[0])
+        scratch.copy_(grads[0])
+        torch.cuda.synchronize()
+        del scratch
 
     for t in range(Wm):
         step(t)

@@ -1,0 +1,102 @@
+"""Algorithm 1 as a whole (one-bit rounds and the full-precision round every K) and the model update
+of Algorithm 2, HIP path against the oracle."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import marsit_oracle as orc
+from paper_2204_06787_amd import marsit, workloads
+from gpu_util import assert_f32_parity, dev, host_bits, host_f32, unaligned_rows
+
+pytestmark = pytest.mark.gpu
+
+
+def _mean_tolerance(s64: np.ndarray, M: int) -> np.ndarray:
+    """fp32 running sum over m (M-1 roundings) and one division, against the oracle's double sum
+    rounded once: |err| <= M * 2^-24 * mean_m |s| (first order), plus one ulp of the result."""
+    return (M * 2.0 ** -24) * np.abs(s64).sum(axis=0) / M * 1.01 + 1e-45
+
+
+@pytest.mark.parametrize("M,d,ld,aligned", [(1, 100, 100, True), (3, 4099, 4100, True), (8, 100_000, 100_000, True),
+                                             (16, 33_333, 33_336, True), (8, 5001, 5003, False), (64, 777, 780, True)])
+def test_full_sync(M, d, ld, aligned):
+    rng = np.random.default_rng(M + d)
+    g_h = rng.standard_normal((M, ld)).astype(np.float32)
+    c_h = rng.standard_normal((M, ld)).astype(np.float32)
+    if aligned:
+        g_d, c_d = dev(g_h), dev(c_h)
+    else:
+        g_d, c_d = unaligned_rows(M, ld), unaligned_rows(M, ld)
+        g_d.copy_(dev(g_h))
+        c_d.copy_(dev(c_h))
+    pad_before = c_h[:, d:].copy()
+    s64 = g_h[:, :d].astype(np.float64) + c_h[:, :d]
+    want = orc.full_sync(g_h, c_h, d=d)
+    u = torch.empty(d, dtype=torch.float32, device="cuda")
+    marsit.marsit_full_sync(g_d, c_d, u, d=d)
+    torch.cuda.synchronize()
+    got = host_f32(u)
+    assert np.all(np.abs(got.astype(np.float64) - want) <= _mean_tolerance(s64, M) + np.spacing(np.abs(want)))
+    got_c = host_f32(c_d)
+    assert not got_c[:, :d].any()                                # c <- 0
+    assert np.array_equal(got_c[:, d:], pad_before)              # padding untouched
+    assert np.array_equal(c_h[:, :d], got_c[:, :d])
+
+
+def test_full_sync_single_worker_is_exact():
+    rng = np.random.default_rng(3)
+    g_h = rng.standard_normal((1, 1000)).astype(np.float32)
+    c_h = rng.standard_normal((1, 1000)).astype(np.float32)
+    want = orc.full_sync(g_h.copy(), c_h.copy())
+    u = torch.empty(1000, dtype=torch.float32, device="cuda")
+    marsit.marsit_full_sync(dev(g_h), dev(c_h), u)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_f32(u), want)
+
+
+@pytest.mark.parametrize("d", [1, 5, 4096, 100_003])
+def test_apply_update(d):
+    rng = np.random.default_rng(d)
+    x_h = rng.standard_normal(d).astype(np.float32)
+    u_h = (1e-3 * np.sign(rng.standard_normal(d))).astype(np.float32)
+    x_d = dev(x_h)
+    marsit.marsit_apply_update(x_d, dev(u_h))
+    torch.cuda.synchronize()
+    assert_f32_parity(host_f32(x_d), orc.apply_update(x_h.copy(), u_h), "x")
+
+
+@pytest.mark.parametrize("M,grid_x,K", [(8, 0, 4), (16, 4, 3), (3, 0, 1), (5, 0, 100)])
+def test_marsit_driven_sgd_loop(M, grid_x, K):
+    """Algorithm 2 with Algorithm 1 inside: T rounds, a full-precision round whenever t mod K == 0,
+    x <- x - g_t after every round.  One-bit rounds must match the oracle bit for bit; the
+    full-precision rounds within the fp32 summation tolerance."""
+    d, T, scale, seed0 = 20_000 + 7, 9, 1e-3, 31
+    wl = workloads.Workload("loop", M=M, d=d, grid_x=grid_x, steps=T, scale=scale, dist="normal", std=0.01)
+    x_d = torch.zeros(d, dtype=torch.float32, device="cuda")
+    x_h = np.zeros(d, dtype=np.float32)
+    c_d = workloads.zero_compensation(wl, device="cuda")
+    c_h = np.zeros((M, d), dtype=np.float32)
+    u_d = torch.empty(d, dtype=torch.float32, device="cuda")
+    bits = marsit.new_bitmap(d)
+    for t in range(T):
+        g_d = workloads.make_gradients(wl, t, seed=seed0, device="cuda")
+        g_h = host_f32(g_d).copy()
+        sd = workloads.step_seed(seed0, t)
+        marsit.marsit_step(t, K, g_d, c_d, u_d, bits, scale, sd, grid_x=grid_x)
+        marsit.marsit_apply_update(x_d, u_d)
+        torch.cuda.synchronize()
+        if t % K != 0:
+            want_u, want_b, _ = orc.sync_step(g_h, c_h, scale, sd, grid_x=grid_x)
+            assert np.array_equal(host_bits(bits), want_b), t
+            assert np.array_equal(host_f32(u_d), want_u), t
+            assert_f32_parity(host_f32(c_d), c_h, f"c, round {t}")
+        else:
+            s64 = g_h.astype(np.float64) + c_h
+            want_u = orc.full_sync(g_h, c_h)
+            got_u = host_f32(u_d)
+            assert np.all(np.abs(got_u.astype(np.float64) - want_u) <= _mean_tolerance(s64, M) + np.spacing(np.abs(want_u))), t
+            assert not host_f32(c_d).any()
+        # the model: apply the GPU's own update on the host copy, must agree exactly
+        x_h = orc.apply_update(x_h, host_f32(u_d).copy())
+        assert np.array_equal(host_f32(x_d), x_h), t
