@@ -44,6 +44,8 @@ def parse_args():
                     help="also launch one plain device copy of one gradient set (known size: reads and "
                          "writes 4*M*d bytes), the yardstick for the rocprofv3 --pmc byte counters")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-unfused", action="store_true", help="skip timing the hop-by-hop chain")
+    ap.add_argument("--no-aux", action="store_true", help="skip timing the other entry points")
     ap.add_argument("--cpu-threads", type=int, default=0)
     return ap.parse_args()
 
@@ -152,6 +154,64 @@ def main():
                      "kernel": "sync_step_kernel", "avg_launch_ms": avg_kernel_ms,
                      "min_launch_ms": min(per_launch_ms), "max_launch_ms": max(per_launch_ms)},
     }
+
+    if not args.no_unfused:
+        # what the fusion buys: the same pass hop by hop (M compress, M(M-1) hop merges, M decodes)
+        ws = torch.empty(marsit.marsit_chain_workspace_words(wl.M, wl.d, wl.grid_x), dtype=torch.int64,
+                         device="cuda")
+        c2 = workloads.zero_compensation(wl, device="cuda")
+
+        def chain(t):
+            marsit.marsit_chain_step_sim(grads[t % pool], c2, update, bits, ws, wl.scale,
+                                         workloads.step_seed(args.seed, t), grid_x=wl.grid_x, stream=stream)
+        for t in range(2):
+            chain(t)
+        torch.cuda.synchronize()
+        n_chain = 5
+        t0 = time.perf_counter()
+        for t in range(n_chain):
+            chain(2 + t)
+        torch.cuda.synchronize()
+        chain_ms = (time.perf_counter() - t0) * 1e3 / n_chain
+        out["unfused_chain"] = {"ms_per_step": chain_ms, "value": nbytes / (chain_ms * 1e-3) / 1e9,
+                                "unit": "GB/s (same algorithmic bytes)", "steps": n_chain,
+                                "launches_per_step": 2 * wl.M + wl.M * (wl.M - 1) + wl.M}
+        del ws, c2
+
+    if not args.no_aux:
+        # the other entry points on the same workload, each timed with events over 10 launches
+        def timed(fn, reps=10):
+            for _ in range(2):
+                fn()
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record(stream)
+            for _ in range(reps):
+                fn()
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            return ev0.elapsed_time(ev1) / reps
+
+        def entry(ms, nb):
+            return {"ms": ms, "GB/s": nb / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                    "algorithmic_bytes": nb}
+        M, d = wl.M, wl.d
+        c3 = workloads.zero_compensation(wl, device="cuda")
+        x = torch.zeros(d, dtype=torch.float32, device="cuda")
+        one_bits = marsit.new_bitmap(d)
+        aux = {}
+        aux["marsit_full_sync"] = entry(timed(lambda: marsit.marsit_full_sync(grads[0], c3, update, stream=stream)),
+                                        12 * M * d + 4 * d)
+        aux["marsit_apply_update"] = entry(timed(lambda: marsit.marsit_apply_update(x, update, stream=stream)), 12 * d)
+        aux["marsit_compress"] = entry(timed(lambda: marsit.marsit_compress(grads[0][0], c3[0], one_bits, stream=stream)),
+                                       8 * d + d // 8)
+        aux["marsit_decode_compensate"] = entry(timed(lambda: marsit.marsit_decode_compensate(
+            one_bits, grads[0][0], c3[0], wl.scale, update, c3[0], stream=stream)), 16 * d + d // 8)
+        seg = (d // 64) // M
+        aux["marsit_hop_merge"] = entry(timed(lambda: marsit.marsit_hop_merge(
+            one_bits[:seg], bits[:seg], one_bits[:seg], 0, seg, 3, 2, args.seed, stream=stream)), 24 * seg)
+        aux["marsit_hop_merge"]["note"] = f"one part of {seg} packed words ({8 * seg} B message); ALU-bound by design"
+        out["other_entry_points"] = aux
+        del c3, x, one_bits
 
     if not args.no_cpu_baseline:
         threads = args.cpu_threads or min(16, os.cpu_count() or 1)

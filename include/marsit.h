@@ -126,6 +126,25 @@ int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *
                          uint32_t grid_x, void *stream);
 
 /*
+ * The same pass as marsit_ring_step_sim, hop by hop, as a real transport would run it: one
+ * marsit_compress per worker, then for every part the chain of M-1 marsit_hop_merge launches over
+ * that part's words (row chains, then column chains on a torus), then one marsit_decode_compensate
+ * per worker.  All launches go to `stream` in order.  Results are bit-identical to the fused pass;
+ * it moves about 20*M*d bytes instead of 12*M*d and exists to show what the fusion buys and as the
+ * skeleton for a transport between the hops.
+ *   workspace  device scratch owned by the caller, marsit_chain_workspace_words(M, d, grid_x)
+ *              64-bit words: the M per-worker bitmaps, then (torus only) the Y row results.
+ *   bits_out   [ceil(d/64)] final merged bitmap; required here (the chains are built in it).
+ * Other arguments as in marsit_ring_step_sim.
+ */
+int marsit_chain_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                          uint64_t *workspace, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                          uint64_t seed, uint32_t grid_x, void *stream);
+
+/* Host-side: size of the workspace of marsit_chain_step_sim in 64-bit words (0 for bad arguments). */
+uint64_t marsit_chain_workspace_words(uint32_t M, uint64_t d, uint32_t grid_x);
+
+/*
  * Algorithm 1, lines 11-13 (the full-precision round) for M simulated workers:
  *     update_out[e] = (1/M) * sum_m (g[m][e] + c[m][e]);   c[m][e] = 0.
  * The sum runs over m = 0..M-1 in fp32, then one division by M.

@@ -67,11 +67,16 @@ __device__ __forceinline__ uint32_t f32_bits(float x) { return __float_as_uint(x
 // ---- 128-bit / guarded accesses ---------------------------------------------------------------
 
 // Four consecutive floats at p.  `vec`: p is 16-byte aligned and all four are inside the vector.
-// Otherwise the first n_valid (0..4) are read one by one, the rest are +0.
+// Otherwise the first n_valid (0..4) are read one by one, the rest are +0.  STREAMING marks data
+// that is read once (non-temporal hint).
+template <bool STREAMING = true>
 __device__ __forceinline__ f32x4 load4(const float *p, bool vec, uint32_t n_valid)
 {
-    if (vec)
+    if (vec) {
+        if (STREAMING)
+            return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
         return *reinterpret_cast<const f32x4 *>(p);
+    }
     f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
     if (n_valid > 0) v.x = p[0];
     if (n_valid > 1) v.y = p[1];

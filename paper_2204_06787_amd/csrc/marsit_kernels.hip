@@ -297,8 +297,8 @@ compress_kernel(const float *__restrict__ g, const float *__restrict__ c,
     for (int i = 0; i < kWordsPerWave; ++i) {
         const uint64_t e = (w0 + i) * 64u + lane;
         valid[i] = e < d;
-        const float gv = valid[i] ? g[e] : 0.0f;
-        const float cv = (valid[i] && c != nullptr) ? c[e] : 0.0f;
+        const float gv = valid[i] ? __builtin_nontemporal_load(g + e) : 0.0f;
+        const float cv = (valid[i] && c != nullptr) ? __builtin_nontemporal_load(c + e) : 0.0f;
         s[i] = gv + cv;
     }
 #pragma unroll
@@ -377,10 +377,10 @@ decode_compensate_kernel(const uint32_t *__restrict__ bits32, const float *__res
 // -------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kBlock)
 full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
-                 uint32_t M, uint64_t d, uint64_t ld, bool aligned)
+                 uint32_t M, uint64_t d, uint64_t ld, uint64_t col_begin, bool aligned)
 {
     const uint64_t n_cols = (d + 3) >> 2;
-    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
     if (col >= n_cols)
         return;
     const uint64_t e = col << 2;
@@ -405,6 +405,41 @@ full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
     store4<MARSIT_STREAMING_STORES>(update + e, mean, vec, n_valid);
 }
 
+// The same for a compile-time worker count, whole aligned columns only, launched like the fused
+// one-bit kernel (one-wavefront workgroups, all 2M loads issued up front, throttled occupancy):
+// the traffic pattern is the same 2M read streams and M+1 write streams.
+template <int M>
+__global__ void __launch_bounds__(kSyncBlock)
+full_sync_fast_kernel(const float *__restrict__ g, float *__restrict__ c,
+                      float *__restrict__ update, uint64_t n_cols, uint64_t ld)
+{
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
+    if (col >= n_cols)
+        return;
+    const uint64_t e = col << 2;
+    f32x4 gv[M], cv[M];
+#pragma unroll
+    for (int m = 0; m < M; ++m) {
+        gv[m] = load4_stream(g + static_cast<size_t>(m) * ld + e);
+        cv[m] = load4_stream(c + static_cast<size_t>(m) * ld + e);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    f32x4 acc = gv[0] + cv[0];
+#pragma unroll
+    for (int m = 1; m < M; ++m)
+        acc = acc + (gv[m] + cv[m]);
+    const float fm = static_cast<float>(M);
+    f32x4 mean;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        mean[j] = acc[j] / fm;
+    store4_stream(update + e, mean);
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int m = 0; m < M; ++m)
+        store4_stream(c + static_cast<size_t>(m) * ld + e, zero);
+}
+
 __global__ void __launch_bounds__(kBlock)
 apply_update_kernel(float *__restrict__ x, const float *__restrict__ update, uint64_t d, bool aligned)
 {
@@ -416,8 +451,8 @@ apply_update_kernel(float *__restrict__ x, const float *__restrict__ update, uin
     const bool full = e + 4 <= d;
     const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
     const bool vec = full && aligned;
-    const f32x4 xv = load4(x + e, vec, n_valid);
-    const f32x4 uv = load4(update + e, vec, n_valid);
+    const f32x4 xv = load4<false>(x + e, vec, n_valid);
+    const f32x4 uv = load4<true>(update + e, vec, n_valid);
     store4<false>(x + e, xv - uv, vec, n_valid);
 }
 
@@ -518,6 +553,44 @@ SyncLauncher find_specialisation(uint32_t X, uint32_t Y)
     MARSIT_CASE(3, 3) MARSIT_CASE(4, 4)
 #undef MARSIT_CASE
     return nullptr;
+}
+
+template <int M>
+void launch_full_sync(const float *g, float *c, float *update, uint64_t n_cols, uint64_t ld,
+                      hipStream_t stream)
+{
+    const uint32_t lds = throttle_lds_bytes(M);
+    static uint32_t lds_allowed = 0;
+    if (lds > lds_allowed) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&full_sync_fast_kernel<M>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize,
+                                static_cast<int>(lds)) == hipSuccess)
+            lds_allowed = lds;
+        else
+            (void)hipGetLastError();
+    }
+    const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
+    hipLaunchKernelGGL((full_sync_fast_kernel<M>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,
+                       update, n_cols, ld);
+}
+
+using FullSyncLauncher = void (*)(const float *, float *, float *, uint64_t, uint64_t, hipStream_t);
+
+FullSyncLauncher find_full_sync(uint32_t M)
+{
+    switch (M) {
+    case 1: return &launch_full_sync<1>;
+    case 2: return &launch_full_sync<2>;
+    case 3: return &launch_full_sync<3>;
+    case 4: return &launch_full_sync<4>;
+    case 5: return &launch_full_sync<5>;
+    case 6: return &launch_full_sync<6>;
+    case 7: return &launch_full_sync<7>;
+    case 8: return &launch_full_sync<8>;
+    case 12: return &launch_full_sync<12>;
+    case 16: return &launch_full_sync<16>;
+    default: return nullptr;
+    }
 }
 
 }   // namespace marsit
@@ -667,6 +740,102 @@ int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *
     return MARSIT_OK;
 }
 
+uint64_t marsit_chain_workspace_words(uint32_t M, uint64_t d, uint32_t grid_x)
+{
+    if (M == 0 || M > MARSIT_MAX_WORKERS || d > kMaxElements)
+        return 0;
+    const uint32_t X = (grid_x == 0) ? M : grid_x;
+    if (M % X != 0)
+        return 0;
+    const uint32_t Y = M / X;
+    const uint64_t n_words = (d + 63) / 64;
+    return (static_cast<uint64_t>(M) + (Y > 1 ? Y : 0)) * n_words;
+}
+
+int marsit_chain_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                          uint64_t *workspace, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                          uint64_t seed, uint32_t grid_x, void *stream)
+{
+    if (g == nullptr || c == nullptr || update_out == nullptr || bits_out == nullptr ||
+        workspace == nullptr || M == 0 || M > MARSIT_MAX_WORKERS || ld < d || !std::isfinite(scale) ||
+        d > kMaxElements)
+        return MARSIT_EINVAL;
+    const uint32_t X = (grid_x == 0) ? M : grid_x;
+    if (M % X != 0)
+        return MARSIT_EINVAL;
+    const uint32_t Y = M / X;
+    if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(update_out, 4) ||
+        !aligned_to(bits_out, 8) || !aligned_to(workspace, 8))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+
+    const uint64_t W = (d + 63) / 64;
+    uint64_t fine[MARSIT_MAX_WORKERS + 1];
+    split_bounds_host(W, M, grid_x, fine);
+    uint64_t *maps = workspace;                    // [M][W]  every worker's own signs (line 5)
+    uint64_t *rows = workspace + static_cast<size_t>(M) * W;   // [Y][W]  row results (torus)
+    int rc;
+
+    for (uint32_t m = 0; m < M; ++m) {
+        rc = marsit_compress(g + static_cast<size_t>(m) * ld, c + static_cast<size_t>(m) * ld,
+                             maps + static_cast<size_t>(m) * W, d, stream);
+        if (rc != MARSIT_OK)
+            return rc;
+    }
+
+    // row phase: row-part a = words [fine[a*Y], fine[(a+1)*Y]); in row y its chain starts at column a.
+    // The first holder sends its own signs (fold 1 copies them), every later hop h folds column (a+h) mod X.
+    for (uint32_t a = 0; a < X; ++a) {
+        const uint64_t lo = fine[a * Y], n = fine[(a + 1) * Y] - lo;
+        if (n == 0)
+            continue;
+        for (uint32_t y = 0; y < Y; ++y) {
+            uint64_t *r = (Y > 1 ? rows + static_cast<size_t>(y) * W : bits_out) + lo;
+            const uint64_t *first = maps + static_cast<size_t>(y * X + a) * W + lo;
+            rc = marsit_hop_merge(first, first, r, lo, n, 1, 0, seed, stream);
+            if (rc != MARSIT_OK)
+                return rc;
+            for (uint32_t h = 1; h < X; ++h) {
+                const uint64_t *local = maps + static_cast<size_t>(y * X + (a + h) % X) * W + lo;
+                rc = marsit_hop_merge(r, local, r, lo, n, h + 1, row_hop_id(y, h), seed, stream);
+                if (rc != MARSIT_OK)
+                    return rc;
+            }
+        }
+    }
+    // column phase over the row results: sub-part b of row-part a starts at row b
+    if (Y > 1) {
+        for (uint32_t f = 0; f < M; ++f) {
+            const uint32_t b = f % Y;
+            const uint64_t lo = fine[f], n = fine[f + 1] - lo;
+            if (n == 0)
+                continue;
+            uint64_t *r = bits_out + lo;
+            const uint64_t *first = rows + static_cast<size_t>(b) * W + lo;
+            rc = marsit_hop_merge(first, first, r, lo, n, 1, 0, seed, stream);
+            if (rc != MARSIT_OK)
+                return rc;
+            for (uint32_t k = 1; k < Y; ++k) {
+                const uint64_t *local = rows + static_cast<size_t>((b + k) % Y) * W + lo;
+                rc = marsit_hop_merge(r, local, r, lo, n, k + 1, col_hop_id(k), seed, stream);
+                if (rc != MARSIT_OK)
+                    return rc;
+            }
+        }
+    }
+
+    for (uint32_t m = 0; m < M; ++m) {
+        rc = marsit_decode_compensate(bits_out, g + static_cast<size_t>(m) * ld,
+                                      c + static_cast<size_t>(m) * ld, scale,
+                                      m == 0 ? update_out : nullptr, c + static_cast<size_t>(m) * ld,
+                                      d, stream);
+        if (rc != MARSIT_OK)
+            return rc;
+    }
+    return MARSIT_OK;
+}
+
 int marsit_full_sync(const float *g, float *c, float *update_out, uint32_t M, uint64_t d,
                      uint64_t ld, void *stream)
 {
@@ -679,9 +848,23 @@ int marsit_full_sync(const float *g, float *c, float *update_out, uint32_t M, ui
         return MARSIT_OK;
     const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
                          (ld % 4 == 0);
-    hipLaunchKernelGGL(full_sync_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock), 0,
-                       static_cast<hipStream_t>(stream), g, c, update_out, M, d, ld, aligned);
-    return finish_launch();
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint64_t col_begin = 0;
+    const FullSyncLauncher fast = aligned ? find_full_sync(M) : nullptr;
+    if (fast != nullptr && d >= 4) {
+        col_begin = d / 4;
+        fast(g, c, update_out, col_begin, ld, s);
+        const int rc = finish_launch();
+        if (rc != MARSIT_OK)
+            return rc;
+    }
+    const uint64_t n_cols = (d + 3) >> 2;
+    if (col_begin < n_cols) {
+        hipLaunchKernelGGL(full_sync_kernel, dim3(blocks_for(n_cols - col_begin)), dim3(kBlock), 0, s,
+                           g, c, update_out, M, d, ld, col_begin, aligned);
+        return finish_launch();
+    }
+    return MARSIT_OK;
 }
 
 int marsit_step(uint64_t t, uint64_t K, const float *g, float *c, float *update_out,

@@ -22,7 +22,8 @@ OK, EINVAL, EALIGN, EHIP = 0, -1, -2, -3
 EXPORTS = (
     "marsit_version", "marsit_last_hip_error", "marsit_status_string", "marsit_philox4x32_10",
     "marsit_split_bounds", "marsit_compress", "marsit_hop_merge", "marsit_decode_compensate",
-    "marsit_ring_step_sim", "marsit_full_sync", "marsit_step", "marsit_apply_update",
+    "marsit_ring_step_sim", "marsit_chain_step_sim", "marsit_chain_workspace_words",
+    "marsit_full_sync", "marsit_step", "marsit_apply_update",
 )
 
 _lib = None
@@ -67,6 +68,10 @@ def load_library(path: str | None = None):
     lib.marsit_decode_compensate.restype = ci
     lib.marsit_ring_step_sim.argtypes = [vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
     lib.marsit_ring_step_sim.restype = ci
+    lib.marsit_chain_step_sim.argtypes = [vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
+    lib.marsit_chain_step_sim.restype = ci
+    lib.marsit_chain_workspace_words.argtypes = [u32, u64, u32]
+    lib.marsit_chain_workspace_words.restype = u64
     lib.marsit_full_sync.argtypes = [vp, vp, vp, u32, u64, u64, vp]
     lib.marsit_full_sync.restype = ci
     lib.marsit_step.argtypes = [u64, u64, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
@@ -186,6 +191,26 @@ def marsit_ring_step_sim(g, c, update_out, bits_out, scale: float, seed: int, gr
         _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
         _bits_ptr(bits_out, "bits_out", True), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF, grid_x,
         _stream(stream)))
+    return update_out, bits_out
+
+
+def marsit_chain_workspace_words(M: int, d: int, grid_x: int = 0) -> int:
+    return int(load_library().marsit_chain_workspace_words(M, d, grid_x))
+
+
+def marsit_chain_step_sim(g, c, update_out, bits_out, workspace, scale: float, seed: int,
+                          grid_x: int = 0, d: int | None = None, stream=None):
+    """The pass hop by hop (un-fused).  ``workspace``: int64 tensor of ``marsit_chain_workspace_words``."""
+    M, ld = _rows(g, "g")
+    if _rows(c, "c") != (M, ld):
+        raise TypeError("g and c must have the same shape and row stride")
+    d = g.shape[1] if d is None else int(d)
+    if workspace.numel() < marsit_chain_workspace_words(M, d, grid_x):
+        raise ValueError("workspace too small")
+    _check("marsit_chain_step_sim", load_library().marsit_chain_step_sim(
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
+        _bits_ptr(bits_out, "bits_out"), _bits_ptr(workspace, "workspace"), M, d, ld, scale,
+        seed & 0xFFFFFFFFFFFFFFFF, grid_x, _stream(stream)))
     return update_out, bits_out
 
 

@@ -123,6 +123,15 @@ def test_other_entry_points_argument_validation(lib):
     assert lib.marsit_step(5, 5, FAKE, FAKE, FAKE, None, 4, 64, 64, float("nan"), 1, 0, None) == marsit.EINVAL
     assert lib.marsit_step(5, 5, FAKE, FAKE, FAKE, None, 4, 0, 0, 1.0, 1, 0, None) == marsit.OK
 
+    assert lib.marsit_chain_step_sim(FAKE, FAKE, FAKE, FAKE, None, 4, 64, 64, 1.0, 1, 0, None) == marsit.EINVAL
+    assert lib.marsit_chain_step_sim(FAKE, FAKE, FAKE, None, FAKE, 4, 64, 64, 1.0, 1, 0, None) == marsit.EINVAL
+    assert lib.marsit_chain_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, 4, 64, 64, 1.0, 1, 3, None) == marsit.EINVAL
+    assert lib.marsit_chain_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE + 4, 4, 64, 64, 1.0, 1, 0, None) == marsit.EALIGN
+    assert lib.marsit_chain_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, 4, 0, 64, 1.0, 1, 0, None) == marsit.OK
+    assert marsit.marsit_chain_workspace_words(8, 25_600_000, 0) == 8 * 400_000
+    assert marsit.marsit_chain_workspace_words(16, 25_600_000, 4) == 20 * 400_000
+    assert marsit.marsit_chain_workspace_words(6, 100, 4) == 0
+
     assert lib.marsit_apply_update(None, FAKE, 64, None) == marsit.EINVAL
     assert lib.marsit_apply_update(FAKE, FAKE, 0, None) == marsit.OK
 

@@ -275,3 +275,27 @@ def test_fused_equals_unfused_chain(M, grid_x, d):
     u1, b1 = fused_step(g1, c1, 1e-3, 4242, grid_x=grid_x)
     u2, b2, _ = unfused_step(g2, c2, 1e-3, 4242, grid_x=grid_x)
     assert torch.equal(b1, b2) and torch.equal(u1, u2) and torch.equal(c1, c2)
+
+
+# ------------------------------------------------------------------------------------------------
+# the native hop-by-hop chain (marsit_chain_step_sim) vs oracle and vs the fused kernel
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,grid_x,d", [(3, 0, 65_536), (8, 0, 400_000 + 21), (16, 4, 200_003), (6, 3, 64 * 5 + 1),
+                                        (5, 0, 7), (9, 3, 33_333), (4, 1, 5000), (12, 0, 100)])
+def test_chain_step(M, grid_x, d):
+    g_h, c_h = _inputs(M, d, seed=11)
+    g1, c1 = dev(g_h), dev(c_h)
+    g2, c2 = dev(g_h), dev(c_h)
+    ws = torch.empty(marsit.marsit_chain_workspace_words(M, d, grid_x), dtype=torch.int64, device="cuda")
+    u1 = torch.empty(d, dtype=torch.float32, device="cuda")
+    b1 = marsit.new_bitmap(d)
+    for t in range(2):
+        sd = workloads.step_seed(909, t)
+        marsit.marsit_chain_step_sim(g1, c1, u1, b1, ws, 1e-3, sd, grid_x=grid_x)
+        u2, b2 = fused_step(g2, c2, 1e-3, sd, grid_x=grid_x)
+        want_u, want_b, _ = oracle_step(g_h, c_h, 1e-3, sd, grid_x=grid_x)
+        assert np.array_equal(host_bits(b1), want_b) and torch.equal(b1, b2)
+        assert np.array_equal(host_f32(u1), want_u) and torch.equal(u1, u2)
+        assert_f32_parity(host_f32(c1), c_h, "compensation (chain)")
+        assert torch.equal(c1, c2)
