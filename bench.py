@@ -210,6 +210,19 @@ def main():
         aux["marsit_hop_merge"] = entry(timed(lambda: marsit.marsit_hop_merge(
             one_bits[:seg], bits[:seg], one_bits[:seg], 0, seg, 3, 2, args.seed, stream=stream)), 24 * seg)
         aux["marsit_hop_merge"]["note"] = f"one part of {seg} packed words ({8 * seg} B message); ALU-bound by design"
+        if not wl.grid_x:
+            # the ring as M workers on M streams, hop by hop (what a transport would sequence)
+            with marsit.RingPipeline(M) as pipe:
+                wsp = torch.empty(pipe.workspace_words(d), dtype=torch.int64, device="cuda")
+                ms = timed(lambda: pipe.ring_step(grads[0], c3, update, one_bits, wsp, wl.scale, args.seed,
+                                                  stream=stream), reps=5)
+                torch.cuda.synchronize()
+            aux["marsit_pipeline_ring_step"] = {
+                "ms_per_step": ms, "streams": M, "launches_per_step": M * M + M * (M - 1) + M,
+                "ms_per_hop_step": ms / (M + 1),
+                "note": "M compress+send steps, M-1 merge hops, 1 decode step; segments of "
+                        f"{8 * ((d // 64) // M)} B"}
+            del wsp
         out["other_entry_points"] = aux
         del c3, x, one_bits
 

@@ -145,6 +145,32 @@ int marsit_chain_step_sim(const float *g, float *c, float *update_out, uint64_t 
 uint64_t marsit_chain_workspace_words(uint32_t M, uint64_t d, uint32_t grid_x);
 
 /*
+ * The ring of Section 4 / Fig. 3 with one HIP stream per worker: every hop of every part is its own
+ * launch and waits only for what a real ring waits for -- the segment from the previous worker
+ * and the release of its own send buffer.  A worker computes the signs of a part right before it
+ * folds them in, so that computation overlaps the wait for the incoming segment (Algorithm 1,
+ * line 5).  The gather period is simulated: the last holder of a part writes it to bits_out, which
+ * every worker reads.  Ring schedule only.  Results are bit-identical to marsit_ring_step_sim.
+ *
+ * marsit_pipeline_create makes the M streams (default priority) and the events; this is the only
+ * call of the library that creates runtime objects, marsit_pipeline_destroy releases them (after
+ * synchronising the worker streams).  marsit_pipeline_ring_step allocates nothing; it returns when
+ * everything is enqueued, and `stream` is made to wait for the workers, so work enqueued on
+ * `stream` afterwards sees the results.  One step at a time per pipeline object.
+ *   workspace  device scratch owned by the caller, marsit_pipeline_workspace_words(M, d) 64-bit
+ *              words: the M per-worker bitmaps and two send buffers per worker.
+ */
+typedef struct marsit_pipeline marsit_pipeline;
+int marsit_pipeline_create(marsit_pipeline **out, uint32_t M);
+int marsit_pipeline_destroy(marsit_pipeline *p);
+uint64_t marsit_pipeline_workspace_words(uint32_t M, uint64_t d);
+int marsit_pipeline_ring_step(marsit_pipeline *p, const float *g, float *c, float *update_out,
+                              uint64_t *bits_out, uint64_t *workspace, uint64_t d, uint64_t ld,
+                              float scale, uint64_t seed, void *stream);
+/* Raw hipError_t of the last failed HIP call of the marsit_pipeline_* functions on this thread. */
+int marsit_pipeline_last_hip_error(void);
+
+/*
  * Algorithm 1, lines 11-13 (the full-precision round) for M simulated workers:
  *     update_out[e] = (1/M) * sum_m (g[m][e] + c[m][e]);   c[m][e] = 0.
  * The sum runs over m = 0..M-1 in fp32, then one division by M.

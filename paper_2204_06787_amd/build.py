@@ -9,7 +9,7 @@ import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
-SOURCES = [os.path.join(PKG, "csrc", "marsit_kernels.hip")]
+SOURCES = [os.path.join(PKG, "csrc", "marsit_kernels.hip"), os.path.join(PKG, "csrc", "marsit_pipeline.hip")]
 HEADERS = [os.path.join(PKG, "csrc", "marsit_device.hpp"), os.path.join(ROOT, "include", "marsit.h")]
 LIB = os.path.join(PKG, "libmarsit.so")
 

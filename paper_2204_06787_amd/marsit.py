@@ -24,6 +24,8 @@ EXPORTS = (
     "marsit_split_bounds", "marsit_compress", "marsit_hop_merge", "marsit_decode_compensate",
     "marsit_ring_step_sim", "marsit_chain_step_sim", "marsit_chain_workspace_words",
     "marsit_full_sync", "marsit_step", "marsit_apply_update",
+    "marsit_pipeline_create", "marsit_pipeline_destroy", "marsit_pipeline_workspace_words",
+    "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
 )
 
 _lib = None
@@ -72,6 +74,16 @@ def load_library(path: str | None = None):
     lib.marsit_chain_step_sim.restype = ci
     lib.marsit_chain_workspace_words.argtypes = [u32, u64, u32]
     lib.marsit_chain_workspace_words.restype = u64
+    lib.marsit_pipeline_create.argtypes = [ctypes.POINTER(vp), u32]
+    lib.marsit_pipeline_create.restype = ci
+    lib.marsit_pipeline_destroy.argtypes = [vp]
+    lib.marsit_pipeline_destroy.restype = ci
+    lib.marsit_pipeline_workspace_words.argtypes = [u32, u64]
+    lib.marsit_pipeline_workspace_words.restype = u64
+    lib.marsit_pipeline_ring_step.argtypes = [vp, vp, vp, vp, vp, vp, u64, u64, f32, u64, vp]
+    lib.marsit_pipeline_ring_step.restype = ci
+    lib.marsit_pipeline_last_hip_error.argtypes = []
+    lib.marsit_pipeline_last_hip_error.restype = ci
     lib.marsit_full_sync.argtypes = [vp, vp, vp, u32, u64, u64, vp]
     lib.marsit_full_sync.restype = ci
     lib.marsit_step.argtypes = [u64, u64, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
@@ -212,6 +224,43 @@ def marsit_chain_step_sim(g, c, update_out, bits_out, workspace, scale: float, s
         _bits_ptr(bits_out, "bits_out"), _bits_ptr(workspace, "workspace"), M, d, ld, scale,
         seed & 0xFFFFFFFFFFFFFFFF, grid_x, _stream(stream)))
     return update_out, bits_out
+
+
+class RingPipeline:
+    """Handle of ``marsit_pipeline_*``: a ring of M workers, one HIP stream each."""
+
+    def __init__(self, M: int):
+        self._h = ctypes.c_void_p()
+        self.M = int(M)
+        _check("marsit_pipeline_create", load_library().marsit_pipeline_create(ctypes.byref(self._h), M))
+
+    def workspace_words(self, d: int) -> int:
+        return int(load_library().marsit_pipeline_workspace_words(self.M, d))
+
+    def ring_step(self, g, c, update_out, bits_out, workspace, scale: float, seed: int,
+                  d: int | None = None, stream=None):
+        M, ld = _rows(g, "g")
+        if M != self.M or _rows(c, "c") != (M, ld):
+            raise TypeError("g and c must be [M, ld] with the pipeline's M")
+        d = g.shape[1] if d is None else int(d)
+        if workspace.numel() < self.workspace_words(d):
+            raise ValueError("workspace too small")
+        _check("marsit_pipeline_ring_step", load_library().marsit_pipeline_ring_step(
+            self._h, _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
+            _bits_ptr(bits_out, "bits_out"), _bits_ptr(workspace, "workspace"), d, ld, scale,
+            seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
+        return update_out, bits_out
+
+    def close(self):
+        if self._h:
+            _check("marsit_pipeline_destroy", load_library().marsit_pipeline_destroy(self._h))
+            self._h = ctypes.c_void_p()
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
 
 
 def marsit_full_sync(g, c, update_out, d: int | None = None, stream=None):

@@ -132,6 +132,12 @@ def test_other_entry_points_argument_validation(lib):
     assert marsit.marsit_chain_workspace_words(16, 25_600_000, 4) == 20 * 400_000
     assert marsit.marsit_chain_workspace_words(6, 100, 4) == 0
 
+    assert lib.marsit_pipeline_create(None, 4) == marsit.EINVAL
+    assert lib.marsit_pipeline_destroy(None) == marsit.EINVAL
+    assert lib.marsit_pipeline_ring_step(None, FAKE, FAKE, FAKE, FAKE, FAKE, 64, 64, 1.0, 1, None) == marsit.EINVAL
+    assert lib.marsit_pipeline_workspace_words(8, 25_600_000) == 8 * 400_000 + 16 * 50_001
+    assert lib.marsit_pipeline_workspace_words(0, 100) == 0
+
     assert lib.marsit_apply_update(None, FAKE, 64, None) == marsit.EINVAL
     assert lib.marsit_apply_update(FAKE, FAKE, 0, None) == marsit.OK
 

@@ -299,3 +299,45 @@ def test_chain_step(M, grid_x, d):
         assert np.array_equal(host_f32(u1), want_u) and torch.equal(u1, u2)
         assert_f32_parity(host_f32(c1), c_h, "compensation (chain)")
         assert torch.equal(c1, c2)
+
+
+# ------------------------------------------------------------------------------------------------
+# the ring as M workers on M streams (marsit_pipeline_*) vs oracle and vs the fused kernel
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,d", [(1, 1000), (2, 64 * 9 + 3), (3, 65_536), (5, 7), (8, 400_000 + 21), (8, 64 * 3),
+                                 (16, 200_003)])
+def test_ring_pipeline(M, d):
+    g_h, c_h = _inputs(M, d, seed=12)
+    g1, c1 = dev(g_h), dev(c_h)
+    g2, c2 = dev(g_h), dev(c_h)
+    u1 = torch.empty(d, dtype=torch.float32, device="cuda")
+    b1 = marsit.new_bitmap(d)
+    with marsit.RingPipeline(M) as pipe:
+        ws = torch.empty(pipe.workspace_words(d), dtype=torch.int64, device="cuda")
+        for t in range(3):                                   # the same events are used again every step
+            sd = workloads.step_seed(4711, t)
+            pipe.ring_step(g1, c1, u1, b1, ws, 1e-3, sd)
+            torch.cuda.synchronize()
+            u2, b2 = fused_step(g2, c2, 1e-3, sd)
+            want_u, want_b, _ = oracle_step(g_h, c_h, 1e-3, sd)
+            assert np.array_equal(host_bits(b1), want_b) and torch.equal(b1, b2), t
+            assert np.array_equal(host_f32(u1), want_u) and torch.equal(u1, u2), t
+            assert_f32_parity(host_f32(c1), c_h, f"compensation (pipeline), step {t}")
+
+
+def test_ring_pipeline_orders_with_the_callers_stream():
+    """Work enqueued on the caller's stream after the step sees the results without a device sync."""
+    M, d = 8, 300_000
+    g_h, c_h = _inputs(M, d, seed=13)
+    g1, c1 = dev(g_h), dev(c_h)
+    u1 = torch.empty(d, dtype=torch.float32, device="cuda")
+    b1 = marsit.new_bitmap(d)
+    with marsit.RingPipeline(M) as pipe:
+        ws = torch.empty(pipe.workspace_words(d), dtype=torch.int64, device="cuda")
+        torch.cuda.synchronize()
+        pipe.ring_step(g1, c1, u1, b1, ws, 1e-3, 5)
+        u_copy = u1.clone()                                  # on the current stream, ordered after the step
+        torch.cuda.synchronize()
+    want_u, _, _ = oracle_step(g_h, c_h, 1e-3, 5)
+    assert np.array_equal(host_f32(u_copy), want_u)
