@@ -53,10 +53,10 @@ struct ThresholdTable {
 // concurrent streams HBM delivers most when each CU keeps only about 40-50 KB of reads in flight;
 // more resident wavefronts widen the window of open DRAM rows and cost up to 10 % of bandwidth.
 //
-// Order inside a lane: issue all 2M 128-bit loads, then generate the M-1 Philox draws while the
-// loads are in flight (they do not depend on the data), then consume.  The two scheduling
-// barriers keep the compiler from sinking the loads next to their uses, which would leave only
-// two loads in flight per wavefront.
+// Order inside a lane, per row of the schedule: issue the row's 2X 128-bit loads (one row ahead),
+// generate the row's Philox draws while they are in flight (the draws do not depend on the data),
+// then consume.  The scheduling barriers keep the compiler from sinking the loads next to their
+// uses, which would leave only two loads in flight per wavefront.
 // -------------------------------------------------------------------------------------------------
 template <int X, int Y>
 __global__ void __launch_bounds__(kSyncBlock)
@@ -81,11 +81,14 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
         const uint32_t a = f / Y;
         const uint32_t b = f % Y;
 
-        // line 1, first half: fetch g and c of every worker, in chain order
+        // Rows are taken one after the other (a ring is a single row).  The 2X loads of a row are
+        // issued one row ahead of the row being folded, and the row's Philox draws run while they
+        // are in flight; the scheduling barriers keep that order.
         size_t off[Y][X];
-        f32x4 gv[Y][X], cv[Y][X];
-#pragma unroll
-        for (int ky = 0; ky < Y; ++ky) {
+        f32x4 s[Y][X];              // line 1: s = g + c, kept for line 10
+        f32x4 gv[2][X], cv[2][X];   // the row in flight and the row being folded
+        uint32_t row_res[Y][4];     // raw fp32 word whose sign is the row's merged sign, per bit
+        auto fetch_row = [&](int ky) {
             uint32_t y = b + ky;
             y = (y >= Y) ? y - Y : y;
 #pragma unroll
@@ -93,72 +96,63 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
                 uint32_t x = a + kx;
                 x = (x >= X) ? x - X : x;
                 off[ky][kx] = static_cast<size_t>(y * X + x) * ld + e;
-                gv[ky][kx] = load4_stream(g + off[ky][kx]);
-                cv[ky][kx] = load4_stream(c + off[ky][kx]);
+                gv[ky & 1][kx] = load4_stream(g + off[ky][kx]);
+                cv[ky & 1][kx] = load4_stream(c + off[ky][kx]);
             }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-
-        // Eq. 2 draws: which hop's local sign survives, for each of the lane's four bits
-        uint32_t pick_row[Y][4];
+        };
+        fetch_row(0);
+        uint32_t pick_col[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int ky = 0; ky < Y; ++ky) {
+            if (ky + 1 < Y)
+                fetch_row(ky + 1);
+            __builtin_amdgcn_sched_barrier(0);
+
+            // Eq. 2 draws of this row's chain (and of the column chain's hop ky): which hop's
+            // local sign is the last to be taken, for each of the lane's four bits
             uint32_t y = b + ky;
             y = (y >= Y) ? y - Y : y;
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                pick_row[ky][j] = 0;
+            uint32_t pick_row[4] = {0, 0, 0, 0};
 #pragma unroll
             for (int h = 1; h < X; ++h) {
                 uint32_t u[4];
                 philox4x32_10(q, row_hop_id(y, h), w, 0u, key0, key1, u);
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    pick_row[ky][j] = (u[j] < keep_threshold(h + 1)) ? h : pick_row[ky][j];
+                    pick_row[j] = (u[j] < keep_threshold(h + 1)) ? h : pick_row[j];
             }
-        }
-        uint32_t pick_col[4] = {0, 0, 0, 0};
+            if (ky > 0) {
+                uint32_t u[4];
+                philox4x32_10(q, col_hop_id(ky), w, 0u, key0, key1, u);
 #pragma unroll
-        for (int k = 1; k < Y; ++k) {
-            uint32_t u[4];
-            philox4x32_10(q, col_hop_id(k), w, 0u, key0, key1, u);
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                pick_col[j] = (u[j] < keep_threshold(k + 1)) ? k : pick_col[j];
-        }
-        __builtin_amdgcn_sched_barrier(0);
+                for (int j = 0; j < 4; ++j)
+                    pick_col[j] = (u[j] < keep_threshold(ky + 1)) ? ky : pick_col[j];
+            }
+            __builtin_amdgcn_sched_barrier(0);
 
-        // line 1, second half: s = g + c
-        f32x4 s[Y][X];
-#pragma unroll
-        for (int ky = 0; ky < Y; ++ky)
+            // line 1, then lines 4-8 for this row: the chain as a selection on the raw fp32 words
 #pragma unroll
             for (int kx = 0; kx < X; ++kx)
-                s[ky][kx] = gv[ky][kx] + cv[ky][kx];
-
-        // lines 4-8: the chains, as selections on the raw fp32 words
-        uint32_t fin[4];
-        {
-            uint32_t row_res[Y][4];
-#pragma unroll
-            for (int ky = 0; ky < Y; ++ky) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    uint32_t r = f32_bits(s[ky][0][j]);
-#pragma unroll
-                    for (int h = 1; h < X; ++h)
-                        r = (pick_row[ky][j] == static_cast<uint32_t>(h)) ? f32_bits(s[ky][h][j]) : r;
-                    row_res[ky][j] = r;
-                }
-            }
+                s[ky][kx] = gv[ky & 1][kx] + cv[ky & 1][kx];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                uint32_t r = row_res[0][j];
+                uint32_t r = f32_bits(s[ky][0][j]);
 #pragma unroll
-                for (int k = 1; k < Y; ++k)
-                    r = (pick_col[j] == static_cast<uint32_t>(k)) ? row_res[k][j] : r;
-                fin[j] = r;
+                for (int h = 1; h < X; ++h)
+                    r = (pick_row[j] == static_cast<uint32_t>(h)) ? f32_bits(s[ky][h][j]) : r;
+                row_res[ky][j] = r;
             }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // column chain over the row results
+        uint32_t fin[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t r = row_res[0][j];
+#pragma unroll
+            for (int k = 1; k < Y; ++k)
+                r = (pick_col[j] == static_cast<uint32_t>(k)) ? row_res[k][j] : r;
+            fin[j] = r;
         }
 
         // line 9: update = +scale where the final sign bit is clear, -scale where it is set
