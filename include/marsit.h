@@ -187,6 +187,25 @@ int marsit_step(uint64_t t, uint64_t K, const float *g, float *c, float *update_
                 uint64_t *bits_out, uint32_t M, uint64_t d, uint64_t ld, float scale,
                 uint64_t seed, uint32_t grid_x, void *stream);
 
+/*
+ * Diagnostics of Section 3.2.2 / Fig. 2(b).  The matching rate of a sign vector is the share of
+ * elements whose sign equals the sign of the non-compressed aggregate.
+ *
+ * marsit_aggregate_sign: bit e of bits_out = sgn(sum_m (g[m][e] + c[m][e])); every term is the fp32
+ *   sum of Algorithm 1 line 1, the sum over m runs in double, in worker order.
+ * marsit_majority_vote: bit e = 1 where at least as many workers have a + sign as a - sign
+ *   (signSGD with majority vote; a tie counts as +).
+ * marsit_count_matching: *count_out (DEVICE memory, one 64-bit word, overwritten) = number of
+ *   positions e < d at which the two bitmaps agree.
+ * g, c [M][ld]; bits_out, bits_a, bits_b [ceil(d/64)].
+ */
+int marsit_aggregate_sign(const float *g, const float *c, uint64_t *bits_out, uint32_t M, uint64_t d,
+                          uint64_t ld, void *stream);
+int marsit_majority_vote(const float *g, const float *c, uint64_t *bits_out, uint32_t M, uint64_t d,
+                         uint64_t ld, void *stream);
+int marsit_count_matching(const uint64_t *bits_a, const uint64_t *bits_b, uint64_t d,
+                          uint64_t *count_out, void *stream);
+
 /* Algorithm 2, line 6:  x[e] <- x[e] - update[e]. */
 int marsit_apply_update(float *x, const float *update, uint64_t d, void *stream);
 

@@ -354,3 +354,59 @@ void oracle_apply_update(float *x, const float *update, uint64_t d)
         x[e] = x[e] - update[e];
     }
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Diagnostics of Section 3.2.2 / Fig. 2(b): the "matching rate" of a sign vector is the share of
+ * elements whose sign equals the sign of the non-compressed aggregate sum_m (g^(m) + c^(m)).
+ * The aggregate is summed in double, in worker order.
+ * ---------------------------------------------------------------------------------------- */
+void oracle_aggregate_sign(const float *g, const float *c, uint64_t *bits, uint32_t M, uint64_t d,
+                           uint64_t ld)
+{
+    uint64_t n_words = (d + 63u) / 64u;
+    for (uint64_t w = 0; w < n_words; ++w)
+        bits[w] = 0;
+    for (uint64_t e = 0; e < d; ++e) {
+        double acc = 0.0;
+        for (uint32_t m = 0; m < M; ++m) {
+            float sm = g[(size_t)m * ld + e] + c[(size_t)m * ld + e];     /* Algorithm 1 line 1, fp32 */
+            acc += (double)sm;
+        }
+        uint64_t raw;
+        memcpy(&raw, &acc, sizeof raw);
+        if ((raw >> 63) == 0)
+            bits[e / 64u] |= (uint64_t)1 << (e % 64u);
+    }
+}
+
+/* signSGD with majority vote (one of the paper's comparison points): +1 where at least as many
+ * workers have a + sign as a - sign (a tie counts as +). */
+void oracle_majority_vote(const float *g, const float *c, uint64_t *bits, uint32_t M, uint64_t d,
+                          uint64_t ld)
+{
+    uint64_t n_words = (d + 63u) / 64u;
+    for (uint64_t w = 0; w < n_words; ++w)
+        bits[w] = 0;
+    for (uint64_t e = 0; e < d; ++e) {
+        uint32_t plus = 0;
+        for (uint32_t m = 0; m < M; ++m) {
+            float sm = g[(size_t)m * ld + e] + c[(size_t)m * ld + e];
+            plus += sign_bit_plus(sm);
+        }
+        if (2u * plus >= M)
+            bits[e / 64u] |= (uint64_t)1 << (e % 64u);
+    }
+}
+
+/* Number of positions e < d at which two sign bitmaps agree. */
+uint64_t oracle_count_matching(const uint64_t *a, const uint64_t *b, uint64_t d)
+{
+    uint64_t count = 0;
+    for (uint64_t e = 0; e < d; ++e) {
+        unsigned ba = (unsigned)((a[e / 64u] >> (e % 64u)) & 1u);
+        unsigned bb = (unsigned)((b[e / 64u] >> (e % 64u)) & 1u);
+        if (ba == bb)
+            ++count;
+    }
+    return count;
+}

@@ -75,6 +75,12 @@ def _load():
     lib.oracle_full_sync.restype = ctypes.c_int
     lib.oracle_apply_update.argtypes = [vp, vp, u64]
     lib.oracle_apply_update.restype = None
+    lib.oracle_aggregate_sign.argtypes = [vp, vp, vp, u32, u64, u64]
+    lib.oracle_aggregate_sign.restype = None
+    lib.oracle_majority_vote.argtypes = [vp, vp, vp, u32, u64, u64]
+    lib.oracle_majority_vote.restype = None
+    lib.oracle_count_matching.argtypes = [vp, vp, u64]
+    lib.oracle_count_matching.restype = u64
     _lib = lib
     return lib
 
@@ -240,3 +246,33 @@ def apply_update(x, update):
     assert x.shape == update.shape
     _load().oracle_apply_update(_ptr(x), _ptr(update), x.size)
     return x
+
+
+# --- diagnostics (Section 3.2.2, Fig. 2b) ------------------------------------------------------
+
+def _vote(fn, g, c, d):
+    g = _f32(g, "g")
+    c = _f32(c, "c")
+    assert g.ndim == 2 and g.shape == c.shape
+    M, ld = g.shape
+    d = ld if d is None else int(d)
+    bits = np.zeros(n_words(d), dtype=np.uint64)
+    fn(_ptr(g), _ptr(c), _ptr(bits), M, d, ld)
+    return bits
+
+
+def aggregate_sign(g, c, d: int | None = None):
+    """Packed sign of the non-compressed aggregate sum_m (g[m] + c[m])."""
+    return _vote(_load().oracle_aggregate_sign, g, c, d)
+
+
+def majority_vote(g, c, d: int | None = None):
+    """Packed majority vote over the workers' signs (ties count as +)."""
+    return _vote(_load().oracle_majority_vote, g, c, d)
+
+
+def count_matching(a, b, d: int) -> int:
+    a = _u64(a, "a")
+    b = _u64(b, "b")
+    assert a.size >= n_words(d) and b.size >= n_words(d)
+    return int(_load().oracle_count_matching(_ptr(a), _ptr(b), d))

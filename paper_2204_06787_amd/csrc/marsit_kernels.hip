@@ -451,6 +451,77 @@ apply_update_kernel(float *__restrict__ x, const float *__restrict__ update, uin
 }
 
 // -------------------------------------------------------------------------------------------------
+// Diagnostics of Section 3.2.2 / Fig. 2(b): sign of the non-compressed aggregate, majority vote,
+// and the number of positions at which two sign bitmaps agree (numerator of the matching rate).
+// -------------------------------------------------------------------------------------------------
+enum VoteMode { kAggregateSign = 0, kMajorityVote = 1 };
+
+template <int MODE>
+__global__ void __launch_bounds__(kBlock)
+vote_kernel(const float *__restrict__ g, const float *__restrict__ c, uint32_t *__restrict__ bits32,
+            uint32_t M, uint64_t d, uint64_t ld, bool aligned)
+{
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint32_t w = static_cast<uint32_t>(col >> 4);
+    const uint32_t q = static_cast<uint32_t>(col) & 15u;
+    uint32_t nib = 0;
+    if (col < n_cols) {
+        const uint64_t e = col << 2;
+        const bool full = e + 4 <= d;
+        const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+        const bool vec = full && aligned;
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};   // aggregate in double, in worker order
+        uint32_t plus[4] = {0, 0, 0, 0};        // workers with a + sign
+#pragma unroll 4
+        for (uint32_t m = 0; m < M; ++m) {
+            const size_t off = static_cast<size_t>(m) * ld + e;
+            const f32x4 sv = load4(g + off, vec, n_valid) + load4(c + off, vec, n_valid);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (MODE == kAggregateSign)
+                    acc[j] += static_cast<double>(sv[j]);
+                else
+                    plus[j] += (f32_bits(sv[j]) >> 31) ^ 1u;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bool positive = (MODE == kAggregateSign)
+                ? ((__double_as_longlong(acc[j]) >> 63) == 0)
+                : (2u * plus[j] >= M);
+            nib |= (static_cast<uint32_t>(j) < n_valid && positive) ? (1u << j) : 0u;
+        }
+    }
+    const uint32_t half = gather_half_word(nib, q);
+    if ((q & 7u) == 0u && static_cast<uint64_t>(w) * 64u < d)
+        bits32[2u * static_cast<size_t>(w) + (q >> 3)] = half;
+}
+
+__global__ void zero_counter_kernel(unsigned long long *count) { *count = 0ull; }
+
+__global__ void __launch_bounds__(kBlock)
+count_matching_kernel(const uint64_t *__restrict__ a, const uint64_t *__restrict__ b, uint64_t d,
+                      uint64_t n_words, unsigned long long *count)
+{
+    const uint64_t i = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    unsigned long long n = 0;
+    if (i < n_words) {
+        uint64_t same = ~(a[i] ^ b[i]);
+        const uint64_t valid = d - i * 64u;                 // elements of this word that exist
+        if (valid < 64u)
+            same &= (static_cast<uint64_t>(1) << valid) - 1u;
+        n = static_cast<unsigned long long>(__popcll(same));
+    }
+    // sum over the wavefront, one atomic per wavefront (integer: the order does not matter)
+#pragma unroll
+    for (int offset = 32; offset > 0; offset >>= 1)
+        n += __shfl_down(n, offset, 64);
+    if ((threadIdx.x & 63u) == 0u && n != 0ull)
+        atomicAdd(count, n);
+}
+
+// -------------------------------------------------------------------------------------------------
 // Host side
 // -------------------------------------------------------------------------------------------------
 thread_local int tls_last_hip_error = 0;
@@ -875,6 +946,58 @@ int marsit_step(uint64_t t, uint64_t K, const float *g, float *c, float *update_
     if (!aligned_to(bits_out, 8))
         return MARSIT_EALIGN;
     return marsit_full_sync(g, c, update_out, M, d, ld, stream);
+}
+
+static int launch_vote(int mode, const float *g, const float *c, uint64_t *bits_out, uint32_t M,
+                       uint64_t d, uint64_t ld, void *stream)
+{
+    if (g == nullptr || c == nullptr || bits_out == nullptr || M == 0 || M > MARSIT_MAX_WORKERS ||
+        ld < d || d > kMaxElements)
+        return MARSIT_EINVAL;
+    if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(bits_out, 8))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && (ld % 4 == 0);
+    const dim3 grid(blocks_for((d + 3) >> 2)), block(kBlock);
+    uint32_t *bits32 = reinterpret_cast<uint32_t *>(bits_out);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (mode == kAggregateSign)
+        hipLaunchKernelGGL(vote_kernel<kAggregateSign>, grid, block, 0, s, g, c, bits32, M, d, ld, aligned);
+    else
+        hipLaunchKernelGGL(vote_kernel<kMajorityVote>, grid, block, 0, s, g, c, bits32, M, d, ld, aligned);
+    return finish_launch();
+}
+
+int marsit_aggregate_sign(const float *g, const float *c, uint64_t *bits_out, uint32_t M, uint64_t d,
+                          uint64_t ld, void *stream)
+{
+    return launch_vote(kAggregateSign, g, c, bits_out, M, d, ld, stream);
+}
+
+int marsit_majority_vote(const float *g, const float *c, uint64_t *bits_out, uint32_t M, uint64_t d,
+                         uint64_t ld, void *stream)
+{
+    return launch_vote(kMajorityVote, g, c, bits_out, M, d, ld, stream);
+}
+
+int marsit_count_matching(const uint64_t *bits_a, const uint64_t *bits_b, uint64_t d,
+                          uint64_t *count_out, void *stream)
+{
+    if (bits_a == nullptr || bits_b == nullptr || count_out == nullptr || d > kMaxElements)
+        return MARSIT_EINVAL;
+    if (!aligned_to(bits_a, 8) || !aligned_to(bits_b, 8) || !aligned_to(count_out, 8))
+        return MARSIT_EALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    unsigned long long *count = reinterpret_cast<unsigned long long *>(count_out);
+    hipLaunchKernelGGL(zero_counter_kernel, dim3(1), dim3(1), 0, s, count);
+    int rc = finish_launch();
+    if (rc != MARSIT_OK || d == 0)
+        return rc;
+    const uint64_t n_words = (d + 63) / 64;
+    hipLaunchKernelGGL(count_matching_kernel, dim3(blocks_for(n_words)), dim3(kBlock), 0, s, bits_a,
+                       bits_b, d, n_words, count);
+    return finish_launch();
 }
 
 int marsit_apply_update(float *x, const float *update, uint64_t d, void *stream)

@@ -26,6 +26,7 @@ EXPORTS = (
     "marsit_full_sync", "marsit_step", "marsit_apply_update",
     "marsit_pipeline_create", "marsit_pipeline_destroy", "marsit_pipeline_workspace_words",
     "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
+    "marsit_aggregate_sign", "marsit_majority_vote", "marsit_count_matching",
 )
 
 _lib = None
@@ -84,6 +85,12 @@ def load_library(path: str | None = None):
     lib.marsit_pipeline_ring_step.restype = ci
     lib.marsit_pipeline_last_hip_error.argtypes = []
     lib.marsit_pipeline_last_hip_error.restype = ci
+    lib.marsit_aggregate_sign.argtypes = [vp, vp, vp, u32, u64, u64, vp]
+    lib.marsit_aggregate_sign.restype = ci
+    lib.marsit_majority_vote.argtypes = [vp, vp, vp, u32, u64, u64, vp]
+    lib.marsit_majority_vote.restype = ci
+    lib.marsit_count_matching.argtypes = [vp, vp, u64, vp, vp]
+    lib.marsit_count_matching.restype = ci
     lib.marsit_full_sync.argtypes = [vp, vp, vp, u32, u64, u64, vp]
     lib.marsit_full_sync.restype = ci
     lib.marsit_step.argtypes = [u64, u64, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
@@ -292,3 +299,31 @@ def marsit_apply_update(x, update, d: int | None = None, stream=None):
     _check("marsit_apply_update", load_library().marsit_apply_update(
         _f32_ptr(x, "x"), _f32_ptr(update, "update"), d, _stream(stream)))
     return x
+
+
+# --- diagnostics (Section 3.2.2, Fig. 2b) --------------------------------------------------------
+
+def _vote(name, g, c, bits_out, d, stream):
+    M, ld = _rows(g, "g")
+    if _rows(c, "c") != (M, ld):
+        raise TypeError("g and c must have the same shape and row stride")
+    d = g.shape[1] if d is None else int(d)
+    _check(name, getattr(load_library(), name)(
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _bits_ptr(bits_out, "bits_out"), M, d, ld, _stream(stream)))
+    return bits_out
+
+
+def marsit_aggregate_sign(g, c, bits_out, d: int | None = None, stream=None):
+    return _vote("marsit_aggregate_sign", g, c, bits_out, d, stream)
+
+
+def marsit_majority_vote(g, c, bits_out, d: int | None = None, stream=None):
+    return _vote("marsit_majority_vote", g, c, bits_out, d, stream)
+
+
+def marsit_count_matching(bits_a, bits_b, d: int, count_out, stream=None):
+    """``count_out``: one-element int64 tensor in device memory (overwritten)."""
+    _check("marsit_count_matching", load_library().marsit_count_matching(
+        _bits_ptr(bits_a, "bits_a"), _bits_ptr(bits_b, "bits_b"), d, _bits_ptr(count_out, "count_out"),
+        _stream(stream)))
+    return count_out

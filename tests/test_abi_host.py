@@ -138,6 +138,12 @@ def test_other_entry_points_argument_validation(lib):
     assert lib.marsit_pipeline_workspace_words(8, 25_600_000) == 8 * 400_000 + 16 * 50_001
     assert lib.marsit_pipeline_workspace_words(0, 100) == 0
 
+    assert lib.marsit_aggregate_sign(FAKE, None, FAKE, 4, 64, 64, None) == marsit.EINVAL
+    assert lib.marsit_majority_vote(FAKE, FAKE, FAKE, 65, 64, 64, None) == marsit.EINVAL
+    assert lib.marsit_majority_vote(FAKE, FAKE, FAKE + 4, 4, 64, 64, None) == marsit.EALIGN
+    assert lib.marsit_aggregate_sign(FAKE, FAKE, FAKE, 4, 0, 0, None) == marsit.OK
+    assert lib.marsit_count_matching(FAKE, FAKE, 64, None, None) == marsit.EINVAL
+
     assert lib.marsit_apply_update(None, FAKE, 64, None) == marsit.EINVAL
     assert lib.marsit_apply_update(FAKE, FAKE, 0, None) == marsit.OK
 

@@ -500,3 +500,46 @@ def test_apply_update():
     x = np.array([1.0, 2.0, -3.0], dtype=np.float32)
     u = np.array([0.5, -0.5, 0.25], dtype=np.float32)
     assert np.array_equal(orc.apply_update(x, u), np.array([0.5, 2.5, -3.25], dtype=np.float32))
+
+
+# ---------------------------------------------------------------------------------------------
+# Matching-rate diagnostics (Section 3.2.2, Fig. 2b)
+# ---------------------------------------------------------------------------------------------
+
+def test_aggregate_sign_and_majority_vote_match_numpy():
+    rng = np.random.default_rng(20)
+    M, d = 7, 64 * 30 + 11
+    g = rng.standard_normal((M, d)).astype(np.float32)
+    c = (0.2 * rng.standard_normal((M, d))).astype(np.float32)
+    s = g + c
+    agg = ~np.signbit(s.astype(np.float64).sum(axis=0))
+    maj = (2 * (~np.signbit(s)).sum(axis=0) >= M)
+
+    def unpack(bits):
+        e = np.arange(d)
+        return ((bits[e // 64] >> (e % 64).astype(np.uint64)) & np.uint64(1)).astype(bool)
+    assert np.array_equal(unpack(orc.aggregate_sign(g, c)), agg)
+    assert np.array_equal(unpack(orc.majority_vote(g, c)), maj)
+    a, b = orc.aggregate_sign(g, c), orc.majority_vote(g, c)
+    assert orc.count_matching(a, b, d) == int((agg == maj).sum())
+    assert orc.count_matching(a, a, d) == d
+    assert int(a[-1]) >> (d % 64) == 0
+
+
+@pytest.mark.parametrize("M", [2, 3, 8, 16])
+def test_marsit_matching_rate_closed_form(M):
+    """For i.i.d. zero-mean Gaussian workers the merged bit is the sign of a uniformly drawn worker,
+    and P(sign(s_m) == sign(sum_k s_k)) = 1/2 + arcsin(1/sqrt(M)) / pi  (bivariate normal, correlation
+    1/sqrt(M)).  The oracle's pass must reproduce that rate within a binomial bound."""
+    rng = np.random.default_rng(30 + M)
+    d = 1 << 19
+    g = rng.standard_normal((M, d)).astype(np.float32)
+    c = np.zeros_like(g)
+    ref = orc.aggregate_sign(g, c)
+    _, bits, _ = orc.sync_step(g, c.copy(), 1.0, 77 + M, threads=8)
+    rate = orc.count_matching(bits, ref, d) / d
+    want = 0.5 + np.arcsin(1.0 / np.sqrt(M)) / np.pi
+    assert abs(rate - want) <= 5 * np.sqrt(want * (1 - want) / d)
+    # the majority vote matches the aggregate more often (for M = 2 every disagreement is a tie)
+    if M >= 3:
+        assert orc.count_matching(orc.majority_vote(g, c), ref, d) / d > rate
