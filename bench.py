@@ -210,6 +210,8 @@ def main():
         aux["marsit_hop_merge"] = entry(timed(lambda: marsit.marsit_hop_merge(
             one_bits[:seg], bits[:seg], one_bits[:seg], 0, seg, 3, 2, args.seed, stream=stream)), 24 * seg)
         aux["marsit_hop_merge"]["note"] = f"one part of {seg} packed words ({8 * seg} B message); ALU-bound by design"
+        aux["marsit_tree_step_sim"] = entry(timed(lambda: marsit.marsit_tree_step_sim(
+            grads[0], c3, update, one_bits, wl.scale, args.seed, stream=stream)), nbytes)
         if not wl.grid_x:
             # the ring as M workers on M streams, hop by hop (what a transport would sequence)
             with marsit.RingPipeline(M) as pipe:

@@ -126,6 +126,31 @@ int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *
                          uint32_t grid_x, void *stream);
 
 /*
+ * Other multi-hop schedules (Section 5 names tree all-reduce and others as easy extensions, without
+ * detail).  Reading taken: when the two operands of a merge stand for different numbers of workers,
+ * Eq. 2 is used with the local share in place of 1/m, i.e. the local sign is kept with probability
+ * w_local / (w_recv + w_local), decided by u < floor(2^32 * w_local / (w_recv + w_local)).
+ * marsit_hop_merge(fold) is marsit_hop_merge_weighted(w_recv = fold - 1, w_local = 1).
+ *   w_local >= 1; w_recv = 0: out = local.  Other arguments as in marsit_hop_merge.
+ */
+int marsit_hop_merge_weighted(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                              uint64_t word_begin, uint64_t n_words, uint32_t w_recv,
+                              uint32_t w_local, uint32_t hop_id, uint64_t seed, void *stream);
+
+/*
+ * The one-bit pass over a binary reduction tree, fused in one kernel: whole vectors, no split in
+ * parts; at level l (stride 2^l) worker k = 0, 2*2^l, 4*2^l, ... receives the sign vector of worker
+ * k + 2^l and folds it into its own, each side weighted by the workers of its subtree (so any M
+ * works, not only powers of two); after ceil(log2 M) levels worker 0 holds the final vector.
+ * hop id of a merge: (2 << 16) | (level << 8) | receiver.  A hierarchical ("segmented") ring of
+ * groups is the torus schedule of marsit_ring_step_sim with grid_x = group size.
+ * Arguments as in marsit_ring_step_sim.
+ */
+int marsit_tree_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                         uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed,
+                         void *stream);
+
+/*
  * The same pass as marsit_ring_step_sim, hop by hop, as a real transport would run it: one
  * marsit_compress per worker, then for every part the chain of M-1 marsit_hop_merge launches over
  * that part's words (row chains, then column chains on a torus), then one marsit_decode_compensate

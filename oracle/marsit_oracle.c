@@ -410,3 +410,91 @@ uint64_t oracle_count_matching(const uint64_t *a, const uint64_t *b, uint64_t d)
     }
     return count;
 }
+
+/* ------------------------------------------------------------------------------------------
+ * Other multi-hop schedules (Section 5 says the method extends to tree all-reduce and others, with
+ * no detail).  Reading taken: when the two operands of a merge stand for different numbers of
+ * workers, Eq. 2 is used with the local share in place of 1/m:
+ *     b_j = w_recv / (w_recv + w_local)  if v*_j = 0,   w_local / (w_recv + w_local)  if v*_j = 1,
+ * i.e. the local sign is kept with probability w_local / (w_recv + w_local), decided by
+ * u < floor(2^32 * w_local / (w_recv + w_local)).  w_local = 1, w_recv = m - 1 is Eq. 2 itself.
+ * ---------------------------------------------------------------------------------------- */
+uint64_t oracle_weighted_threshold(uint32_t w_recv, uint32_t w_local)
+{
+    return (((uint64_t)w_local) << 32) / ((uint64_t)w_recv + (uint64_t)w_local);   /* 2^32 if w_recv == 0 */
+}
+
+uint64_t oracle_merge_word_weighted(uint64_t recv, uint64_t local, uint32_t w_recv, uint32_t w_local,
+                                    uint32_t hop_id, uint64_t seed, uint64_t word_index)
+{
+    uint64_t threshold = oracle_weighted_threshold(w_recv, w_local);
+    uint64_t keep = 0;
+    for (unsigned j = 0; j < 64; ++j) {
+        uint64_t u = oracle_stream_u32(seed, hop_id, word_index, j);
+        if (u < threshold)
+            keep |= (uint64_t)1 << j;
+    }
+    uint64_t v = oracle_transient_from_keep(local, keep);
+    return oracle_odot(recv, local, v);
+}
+
+int oracle_hop_merge_weighted(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                              uint64_t word_begin, uint64_t n_words, uint32_t w_recv, uint32_t w_local,
+                              uint32_t hop_id, uint64_t seed)
+{
+    if (w_local == 0)
+        return -1;
+    for (uint64_t i = 0; i < n_words; ++i)
+        out[i] = oracle_merge_word_weighted(recv[i], local[i], w_recv, w_local, hop_id, seed,
+                                            word_begin + i);
+    return 0;
+}
+
+/* hop id of a tree merge: phase 2, the level and the receiving worker. */
+uint32_t oracle_tree_hop_id(uint32_t level, uint32_t receiver)
+{
+    return (2u << 16) | (level << 8) | receiver;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * The one-bit pass over a binary reduction tree (whole vectors, no split in parts): at level l
+ * (stride 2^l) worker k = 0, 2*2^l, 4*2^l, ... receives the sign vector of worker k + 2^l and
+ * folds it into its own; each side stands for the workers of its subtree.  After ceil(log2 M)
+ * levels worker 0 holds the final vector (then broadcast).  Same arguments as oracle_sync_step.
+ * ---------------------------------------------------------------------------------------- */
+int oracle_tree_step(const float *g, float *c, float *update, uint64_t *bits_final, uint32_t M,
+                     uint64_t d, uint64_t ld, float scale, uint64_t seed)
+{
+    if (M == 0 || M > ORACLE_MAX_WORKERS || ld < d || g == NULL || c == NULL || update == NULL)
+        return -1;
+    if (d == 0)
+        return 0;
+    uint64_t W = (d + 63u) / 64u;
+    float *s = (float *)malloc((size_t)M * d * sizeof(float));
+    uint64_t *B = (uint64_t *)malloc((size_t)M * W * sizeof(uint64_t));
+    if (s == NULL || B == NULL) {
+        free(s); free(B);
+        return -2;
+    }
+    for (uint32_t m = 0; m < M; ++m) {
+        oracle_add_compensation(g + (size_t)m * ld, c + (size_t)m * ld, s + (size_t)m * d, d);
+        oracle_sign_pack(s + (size_t)m * d, B + (size_t)m * W, d);
+    }
+    uint32_t level = 0;
+    for (uint32_t stride = 1; stride < M; stride *= 2, ++level) {
+        for (uint32_t k = 0; k + stride < M; k += 2 * stride) {
+            uint32_t src = k + stride;
+            uint32_t w_local = (M - k < stride) ? (M - k) : stride;       /* workers under k so far   */
+            uint32_t w_recv = (M - src < stride) ? (M - src) : stride;    /* workers under the sender */
+            oracle_hop_merge_weighted(B + (size_t)src * W, B + (size_t)k * W, B + (size_t)k * W, 0, W,
+                                      w_recv, w_local, oracle_tree_hop_id(level, k), seed);
+        }
+    }
+    oracle_decode(B, scale, update, d);
+    for (uint32_t m = 0; m < M; ++m)
+        oracle_compensate(s + (size_t)m * d, update, c + (size_t)m * ld, d);
+    if (bits_final != NULL)
+        memcpy(bits_final, B, (size_t)W * sizeof(uint64_t));
+    free(s); free(B);
+    return 0;
+}

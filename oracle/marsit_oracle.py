@@ -81,6 +81,16 @@ def _load():
     lib.oracle_majority_vote.restype = None
     lib.oracle_count_matching.argtypes = [vp, vp, u64]
     lib.oracle_count_matching.restype = u64
+    lib.oracle_weighted_threshold.argtypes = [u32, u32]
+    lib.oracle_weighted_threshold.restype = u64
+    lib.oracle_merge_word_weighted.argtypes = [u64, u64, u32, u32, u32, u64, u64]
+    lib.oracle_merge_word_weighted.restype = u64
+    lib.oracle_hop_merge_weighted.argtypes = [vp, vp, vp, u64, u64, u32, u32, u32, u64]
+    lib.oracle_hop_merge_weighted.restype = ctypes.c_int
+    lib.oracle_tree_hop_id.argtypes = [u32, u32]
+    lib.oracle_tree_hop_id.restype = u32
+    lib.oracle_tree_step.argtypes = [vp, vp, vp, vp, u32, u64, u64, f32, u64]
+    lib.oracle_tree_step.restype = ctypes.c_int
     _lib = lib
     return lib
 
@@ -276,3 +286,46 @@ def count_matching(a, b, d: int) -> int:
     b = _u64(b, "b")
     assert a.size >= n_words(d) and b.size >= n_words(d)
     return int(_load().oracle_count_matching(_ptr(a), _ptr(b), d))
+
+
+# --- other schedules: weighted merge, reduction tree -------------------------------------------
+
+def weighted_threshold(w_recv: int, w_local: int) -> int:
+    return int(_load().oracle_weighted_threshold(w_recv, w_local))
+
+
+def merge_word_weighted(recv: int, local: int, w_recv: int, w_local: int, hop: int, seed: int,
+                        word_index: int) -> int:
+    return int(_load().oracle_merge_word_weighted(recv, local, w_recv, w_local, hop, seed, word_index))
+
+
+def hop_merge_weighted(recv, local, word_begin: int, w_recv: int, w_local: int, hop: int, seed: int):
+    recv = _u64(recv, "recv")
+    local = _u64(local, "local")
+    assert recv.shape == local.shape
+    out = np.empty_like(recv)
+    rc = _load().oracle_hop_merge_weighted(_ptr(recv), _ptr(local), _ptr(out), word_begin, recv.size,
+                                           w_recv, w_local, hop, seed)
+    if rc != 0:
+        raise ValueError(f"oracle_hop_merge_weighted: bad argument (rc={rc})")
+    return out
+
+
+def tree_hop_id(level: int, receiver: int) -> int:
+    return int(_load().oracle_tree_hop_id(level, receiver))
+
+
+def tree_step(g, c, scale: float, seed: int, d: int | None = None):
+    """One one-bit pass over a binary reduction tree; ``c`` is updated in place.
+    Returns ``(update[d], bits_final[W])``."""
+    g = _f32(g, "g")
+    c = _f32(c, "c")
+    assert g.ndim == 2 and g.shape == c.shape
+    M, ld = g.shape
+    d = ld if d is None else int(d)
+    update = np.empty(d, dtype=np.float32)
+    bits = np.zeros(n_words(d), dtype=np.uint64)
+    rc = _load().oracle_tree_step(_ptr(g), _ptr(c), _ptr(update), _ptr(bits), M, d, ld, scale, seed)
+    if rc != 0:
+        raise ValueError(f"oracle_tree_step failed (rc={rc})")
+    return update, bits

@@ -62,6 +62,21 @@ __host__ __device__ constexpr uint32_t keep_threshold(uint32_t fold)
 __host__ __device__ constexpr uint32_t row_hop_id(uint32_t row, uint32_t hop) { return (row << 8) | hop; }
 __host__ __device__ constexpr uint32_t col_hop_id(uint32_t hop) { return (1u << 16) | hop; }
 
+// Reduction tree: hop id of the merge at `level` whose receiver is worker `receiver`.
+__host__ __device__ constexpr uint32_t tree_hop_id(uint32_t level, uint32_t receiver)
+{
+    return (2u << 16) | (level << 8) | receiver;
+}
+
+// Keep-local threshold when the received vector stands for w_recv workers and the local one for
+// w_local (Eq. 2 with the local share in place of 1/m): floor(2^32 * w_local / (w_recv + w_local)).
+// w_recv must be >= 1 (w_recv = 0 means "always local" and is handled by the callers).
+__host__ __device__ constexpr uint32_t weighted_threshold(uint32_t w_recv, uint32_t w_local)
+{
+    return static_cast<uint32_t>((static_cast<uint64_t>(w_local) << 32) /
+                                 (static_cast<uint64_t>(w_recv) + w_local));
+}
+
 __device__ __forceinline__ uint32_t f32_bits(float x) { return __float_as_uint(x); }
 
 // ---- 128-bit / guarded accesses ---------------------------------------------------------------

@@ -269,6 +269,151 @@ sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
 }
 
 // -------------------------------------------------------------------------------------------------
+// Fused pass over a binary reduction tree (whole vectors, no parts): at level l worker
+// k = 0, 2*2^l, ... folds the vector of worker k + 2^l into its own; each side stands for the
+// workers of its subtree.  Same lane layout and launch shape as the ring kernel.
+// -------------------------------------------------------------------------------------------------
+template <int M>
+__global__ void __launch_bounds__(kSyncBlock)
+tree_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
+                 uint32_t *__restrict__ bits32, uint64_t n_cols, uint64_t ld, uint32_t scale_bits,
+                 uint32_t key0, uint32_t key1)
+{
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
+    const uint32_t w = static_cast<uint32_t>(col >> 4);
+    const uint32_t q = static_cast<uint32_t>(col) & 15u;
+    uint32_t nib = 0;
+
+    if (col < n_cols) {
+        const uint64_t e = col << 2;
+        f32x4 gv[M], cv[M];
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            gv[m] = load4_stream(g + static_cast<size_t>(m) * ld + e);
+            cv[m] = load4_stream(c + static_cast<size_t>(m) * ld + e);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // one draw per merge and bit: bit (4*i + j) of `take` = merge i keeps the receiver's own sign
+        uint64_t take = 0;
+        {
+            int i = 0;
+#pragma unroll
+            for (int stride = 1, level = 0; stride < M; stride *= 2, ++level) {
+#pragma unroll
+                for (int k = 0; k + stride < M; k += 2 * stride, ++i) {
+                    const int src = k + stride;
+                    const uint32_t w_recv = (M - src < stride) ? (M - src) : stride;
+                    uint32_t u[4];
+                    philox4x32_10(q, tree_hop_id(level, k), w, 0u, key0, key1, u);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        take |= (u[j] < weighted_threshold(w_recv, stride))
+                                    ? (static_cast<uint64_t>(1) << (4 * i + j)) : 0ull;
+                }
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        f32x4 s[M];
+#pragma unroll
+        for (int m = 0; m < M; ++m)
+            s[m] = gv[m] + cv[m];
+
+        // the tree, bottom level first, as selections on the raw fp32 words
+        uint32_t fin[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t val[M];
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+                val[m] = f32_bits(s[m][j]);
+            int i = 0;
+#pragma unroll
+            for (int stride = 1; stride < M; stride *= 2) {
+#pragma unroll
+                for (int k = 0; k + stride < M; k += 2 * stride, ++i)
+                    val[k] = ((take >> (4 * i + j)) & 1ull) ? val[k] : val[k + stride];
+            }
+            fin[j] = val[0];
+        }
+
+        f32x4 upd;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t sign = fin[j] & 0x80000000u;
+            upd[j] = __uint_as_float(scale_bits ^ sign);
+            nib |= (sign == 0u) ? (1u << j) : 0u;
+        }
+        store4_stream(update + e, upd);
+#pragma unroll
+        for (int m = 0; m < M; ++m)
+            store4_stream(c + static_cast<size_t>(m) * ld + e, s[m] - upd);
+    }
+
+    const uint32_t half = gather_half_word(nib, q);
+    if (bits32 != nullptr && (q & 7u) == 0u && col < n_cols)
+        bits32[2u * static_cast<size_t>(w) + (q >> 3)] = half;
+}
+
+// Any M, any alignment, ragged tails.  Only the merges on the way from the root to the chosen
+// leaf decide a bit (all draws are independent), so every bit walks down the tree with at most
+// ceil(log2 M) draws, fetches the sign of the one worker it ends at, and a second sweep writes
+// the compensation.
+__global__ void __launch_bounds__(kBlock)
+tree_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
+                         float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
+                         uint64_t ld, uint64_t col_begin, uint32_t scale_bits, uint32_t key0,
+                         uint32_t key1, uint32_t M, uint32_t top_level, bool aligned)
+{
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint32_t w = static_cast<uint32_t>(col >> 4);
+    const uint32_t q = static_cast<uint32_t>(col) & 15u;
+    uint32_t nib = 0;
+
+    if (col < n_cols) {
+        const uint64_t e = col << 2;
+        const bool full = e + 4 <= d;
+        const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+        const bool vec = full && aligned;
+
+        f32x4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (uint32_t j = 0; j < n_valid; ++j) {
+            uint32_t k = 0;
+            for (uint32_t level = top_level; level-- > 0;) {
+                const uint32_t stride = 1u << level;
+                const uint32_t src = k + stride;
+                if (src >= M)
+                    continue;
+                const uint32_t w_recv = (M - src < stride) ? (M - src) : stride;
+                const uint32_t thr = (w_recv == stride) ? 0x80000000u : weighted_threshold(w_recv, stride);
+                uint32_t u[4];
+                philox4x32_10(q, tree_hop_id(level, k), w, 0u, key0, key1, u);
+                const uint32_t uj = (j == 0) ? u[0] : (j == 1) ? u[1] : (j == 2) ? u[2] : u[3];
+                k = (uj < thr) ? k : src;
+            }
+            const size_t at = static_cast<size_t>(k) * ld + e + j;
+            const float sv = g[at] + c[at];
+            const uint32_t sign = f32_bits(sv) & 0x80000000u;
+            const float uval = __uint_as_float(scale_bits ^ sign);
+            if (j == 0) upd.x = uval; else if (j == 1) upd.y = uval; else if (j == 2) upd.z = uval; else upd.w = uval;
+            nib |= (sign == 0u) ? (1u << j) : 0u;
+        }
+        store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
+        for (uint32_t m = 0; m < M; ++m) {
+            const size_t off = static_cast<size_t>(m) * ld + e;
+            const f32x4 sv = load4(g + off, vec, n_valid) + load4(c + off, vec, n_valid);
+            store4<MARSIT_STREAMING_STORES>(c + off, sv - upd, vec, n_valid);
+        }
+    }
+
+    const uint32_t half = gather_half_word(nib, q);
+    if (bits32 != nullptr && (q & 7u) == 0u && static_cast<uint64_t>(w) * 64u < d)
+        bits32[2u * static_cast<size_t>(w) + (q >> 3)] = half;
+}
+
+// -------------------------------------------------------------------------------------------------
 // marsit_compress: a wavefront takes 64 consecutive elements per packed word, one per lane, and
 // the 64-lane ballot of "sign bit clear" IS the word.  Four words per wavefront per trip keep
 // eight independent 256-byte loads in flight.
@@ -579,7 +724,8 @@ inline uint32_t throttle_lds_bytes(uint32_t M)
     uint32_t waves = (20u + M / 2u) / M;
     if (waves < 3u)
         waves = 3u;
-    // a few per cent below an even share: with an exact share one workgroup fewer fits
+    // a few per cent below an even share: with an exact share one workgroup fewer fits.  At least
+    // 3 workgroups per CU keeps the request under the 64 KB a launch may ask for without opting in.
     return ((lds_per_cu / waves) * 31u / 32u) & ~511u;
 }
 
@@ -589,16 +735,6 @@ void launch_sync_step(const float *g, float *c, float *update, uint32_t *bits32,
                       const PartTable &parts, hipStream_t stream)
 {
     const uint32_t lds = throttle_lds_bytes(X * Y);
-    static uint32_t lds_allowed = 0;
-    if (lds > lds_allowed) {
-        // above 64 KB of dynamic LDS the limit has to be raised once per kernel
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&sync_step_kernel<X, Y>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                static_cast<int>(lds)) == hipSuccess)
-            lds_allowed = lds;
-        else
-            (void)hipGetLastError();
-    }
     const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
     hipLaunchKernelGGL((sync_step_kernel<X, Y>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,
                        update, bits32, n_cols, ld, scale_bits, key0, key1, parts);
@@ -625,18 +761,40 @@ void launch_full_sync(const float *g, float *c, float *update, uint64_t n_cols, 
                       hipStream_t stream)
 {
     const uint32_t lds = throttle_lds_bytes(M);
-    static uint32_t lds_allowed = 0;
-    if (lds > lds_allowed) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(&full_sync_fast_kernel<M>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                static_cast<int>(lds)) == hipSuccess)
-            lds_allowed = lds;
-        else
-            (void)hipGetLastError();
-    }
     const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
     hipLaunchKernelGGL((full_sync_fast_kernel<M>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,
                        update, n_cols, ld);
+}
+
+template <int M>
+void launch_tree_step(const float *g, float *c, float *update, uint32_t *bits32, uint64_t n_cols,
+                      uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1,
+                      hipStream_t stream)
+{
+    const uint32_t lds = throttle_lds_bytes(M);
+    const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
+    hipLaunchKernelGGL((tree_step_kernel<M>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c, update,
+                       bits32, n_cols, ld, scale_bits, key0, key1);
+}
+
+using TreeLauncher = void (*)(const float *, float *, float *, uint32_t *, uint64_t, uint64_t, uint32_t,
+                              uint32_t, uint32_t, hipStream_t);
+
+TreeLauncher find_tree(uint32_t M)
+{
+    switch (M) {
+    case 1: return &launch_tree_step<1>;
+    case 2: return &launch_tree_step<2>;
+    case 3: return &launch_tree_step<3>;
+    case 4: return &launch_tree_step<4>;
+    case 5: return &launch_tree_step<5>;
+    case 6: return &launch_tree_step<6>;
+    case 7: return &launch_tree_step<7>;
+    case 8: return &launch_tree_step<8>;
+    case 12: return &launch_tree_step<12>;
+    case 16: return &launch_tree_step<16>;
+    default: return nullptr;
+    }
 }
 
 using FullSyncLauncher = void (*)(const float *, float *, float *, uint64_t, uint64_t, hipStream_t);
@@ -704,25 +862,41 @@ int marsit_compress(const float *g, const float *c, uint64_t *bits_out, uint64_t
     return finish_launch();
 }
 
-int marsit_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_t *out,
-                     uint64_t word_begin, uint64_t n_words, uint32_t fold, uint32_t hop_id,
-                     uint64_t seed, void *stream)
+static int launch_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                            uint64_t word_begin, uint64_t n_words, uint32_t w_recv, uint32_t w_local,
+                            uint32_t hop_id, uint64_t seed, void *stream)
 {
-    if (recv == nullptr || local == nullptr || out == nullptr || fold == 0 ||
-        n_words > kMaxElements / 64)
+    if (recv == nullptr || local == nullptr || out == nullptr || w_local == 0 ||
+        w_recv > 0x7FFFFFFFu || w_local > 0x7FFFFFFFu || n_words > kMaxElements / 64)
         return MARSIT_EINVAL;
     if (!aligned_to(recv, 8) || !aligned_to(local, 8) || !aligned_to(out, 8))
         return MARSIT_EALIGN;
     if (n_words == 0)
         return MARSIT_OK;
-    const bool always_local = (fold == 1);
-    const uint32_t threshold = always_local ? 0xFFFFFFFFu : keep_threshold(fold);
+    const bool always_local = (w_recv == 0);
+    const uint32_t threshold = always_local ? 0xFFFFFFFFu : weighted_threshold(w_recv, w_local);
     hipLaunchKernelGGL(hop_merge_kernel, dim3(blocks_for(n_words * 16)), dim3(kBlock), 0,
                        static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(recv),
                        reinterpret_cast<const uint32_t *>(local), reinterpret_cast<uint32_t *>(out),
                        word_begin, n_words, threshold, always_local, hop_id,
                        static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32));
     return finish_launch();
+}
+
+int marsit_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                     uint64_t word_begin, uint64_t n_words, uint32_t fold, uint32_t hop_id,
+                     uint64_t seed, void *stream)
+{
+    if (fold == 0)
+        return MARSIT_EINVAL;
+    return launch_hop_merge(recv, local, out, word_begin, n_words, fold - 1, 1, hop_id, seed, stream);
+}
+
+int marsit_hop_merge_weighted(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                              uint64_t word_begin, uint64_t n_words, uint32_t w_recv,
+                              uint32_t w_local, uint32_t hop_id, uint64_t seed, void *stream)
+{
+    return launch_hop_merge(recv, local, out, word_begin, n_words, w_recv, w_local, hop_id, seed, stream);
 }
 
 int marsit_decode_compensate(const uint64_t *bits, const float *g, const float *c, float scale,
@@ -800,6 +974,49 @@ int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *
         hipLaunchKernelGGL(sync_step_generic_kernel, dim3(blocks_for(n_cols - generic_col_begin)),
                            dim3(kBlock), 0, s, g, c, update_out, bits32, d, ld, generic_col_begin,
                            scale_bits, key0, key1, X, Y, aligned, parts, thresholds);
+        return finish_launch();
+    }
+    return MARSIT_OK;
+}
+
+int marsit_tree_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                         uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed, void *stream)
+{
+    if (g == nullptr || c == nullptr || update_out == nullptr || M == 0 ||
+        M > MARSIT_MAX_WORKERS || ld < d || !std::isfinite(scale) || d > kMaxElements)
+        return MARSIT_EINVAL;
+    if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(update_out, 4) ||
+        !aligned_to(bits_out, 8))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
+                         (ld % 4 == 0);
+    const uint32_t scale_bits = float_bits_host(scale);
+    const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
+    uint32_t *bits32 = reinterpret_cast<uint32_t *>(bits_out);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+
+    const TreeLauncher fast = aligned ? find_tree(M) : nullptr;
+    uint64_t generic_col_begin = 0;
+    if (fast != nullptr) {
+        const uint64_t fast_cols = (d / 64) * 16;
+        if (fast_cols > 0) {
+            fast(g, c, update_out, bits32, fast_cols, ld, scale_bits, key0, key1, s);
+            const int rc = finish_launch();
+            if (rc != MARSIT_OK)
+                return rc;
+        }
+        generic_col_begin = fast_cols;
+    }
+    const uint64_t n_cols = (d + 3) >> 2;
+    if (generic_col_begin < n_cols) {
+        uint32_t top_level = 0;
+        while ((1u << top_level) < M)
+            ++top_level;
+        hipLaunchKernelGGL(tree_step_generic_kernel, dim3(blocks_for(n_cols - generic_col_begin)),
+                           dim3(kBlock), 0, s, g, c, update_out, bits32, d, ld, generic_col_begin,
+                           scale_bits, key0, key1, M, top_level, aligned);
         return finish_launch();
     }
     return MARSIT_OK;

@@ -27,6 +27,7 @@ EXPORTS = (
     "marsit_pipeline_create", "marsit_pipeline_destroy", "marsit_pipeline_workspace_words",
     "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
     "marsit_aggregate_sign", "marsit_majority_vote", "marsit_count_matching",
+    "marsit_hop_merge_weighted", "marsit_tree_step_sim",
 )
 
 _lib = None
@@ -85,6 +86,10 @@ def load_library(path: str | None = None):
     lib.marsit_pipeline_ring_step.restype = ci
     lib.marsit_pipeline_last_hip_error.argtypes = []
     lib.marsit_pipeline_last_hip_error.restype = ci
+    lib.marsit_hop_merge_weighted.argtypes = [vp, vp, vp, u64, u64, u32, u32, u32, u64, vp]
+    lib.marsit_hop_merge_weighted.restype = ci
+    lib.marsit_tree_step_sim.argtypes = [vp, vp, vp, vp, u32, u64, u64, f32, u64, vp]
+    lib.marsit_tree_step_sim.restype = ci
     lib.marsit_aggregate_sign.argtypes = [vp, vp, vp, u32, u64, u64, vp]
     lib.marsit_aggregate_sign.restype = ci
     lib.marsit_majority_vote.argtypes = [vp, vp, vp, u32, u64, u64, vp]
@@ -327,3 +332,27 @@ def marsit_count_matching(bits_a, bits_b, d: int, count_out, stream=None):
         _bits_ptr(bits_a, "bits_a"), _bits_ptr(bits_b, "bits_b"), d, _bits_ptr(count_out, "count_out"),
         _stream(stream)))
     return count_out
+
+
+# --- other schedules -----------------------------------------------------------------------------
+
+def marsit_hop_merge_weighted(recv, local, out, word_begin: int, n_words_: int, w_recv: int,
+                              w_local: int, hop_id: int, seed: int, stream=None):
+    _check("marsit_hop_merge_weighted", load_library().marsit_hop_merge_weighted(
+        _bits_ptr(recv, "recv"), _bits_ptr(local, "local"), _bits_ptr(out, "out"), word_begin,
+        n_words_, w_recv, w_local, hop_id, seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
+    return out
+
+
+def marsit_tree_step_sim(g, c, update_out, bits_out, scale: float, seed: int, d: int | None = None,
+                         stream=None):
+    """The one-bit pass over a binary reduction tree; ``c`` is updated in place."""
+    M, ld = _rows(g, "g")
+    if _rows(c, "c") != (M, ld):
+        raise TypeError("g and c must have the same shape and row stride")
+    d = g.shape[1] if d is None else int(d)
+    _check("marsit_tree_step_sim", load_library().marsit_tree_step_sim(
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
+        _bits_ptr(bits_out, "bits_out", True), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF,
+        _stream(stream)))
+    return update_out, bits_out

@@ -144,6 +144,13 @@ def test_other_entry_points_argument_validation(lib):
     assert lib.marsit_aggregate_sign(FAKE, FAKE, FAKE, 4, 0, 0, None) == marsit.OK
     assert lib.marsit_count_matching(FAKE, FAKE, 64, None, None) == marsit.EINVAL
 
+    assert lib.marsit_hop_merge_weighted(FAKE, FAKE, FAKE, 0, 10, 3, 0, 1, 5, None) == marsit.EINVAL   # w_local 0
+    assert lib.marsit_hop_merge_weighted(FAKE, FAKE, FAKE, 0, 0, 3, 1, 1, 5, None) == marsit.OK
+    assert lib.marsit_tree_step_sim(FAKE, FAKE, FAKE, None, 0, 64, 64, 1.0, 1, None) == marsit.EINVAL
+    assert lib.marsit_tree_step_sim(FAKE, FAKE, FAKE, None, 8, 64, 32, 1.0, 1, None) == marsit.EINVAL
+    assert lib.marsit_tree_step_sim(FAKE, FAKE + 2, FAKE, None, 8, 64, 64, 1.0, 1, None) == marsit.EALIGN
+    assert lib.marsit_tree_step_sim(FAKE, FAKE, FAKE, None, 8, 0, 64, 1.0, 1, None) == marsit.OK
+
     assert lib.marsit_apply_update(None, FAKE, 64, None) == marsit.EINVAL
     assert lib.marsit_apply_update(FAKE, FAKE, 0, None) == marsit.OK
 

@@ -543,3 +543,95 @@ def test_marsit_matching_rate_closed_form(M):
     # the majority vote matches the aggregate more often (for M = 2 every disagreement is a tie)
     if M >= 3:
         assert orc.count_matching(orc.majority_vote(g, c), ref, d) / d > rate
+
+
+# ---------------------------------------------------------------------------------------------
+# Weighted merge and the reduction-tree schedule
+# ---------------------------------------------------------------------------------------------
+
+def test_weighted_threshold_generalises_eq2():
+    for m in range(1, 17):
+        assert orc.weighted_threshold(m - 1, 1) == (1 << 32) // m          # Eq. 2 itself
+    assert orc.weighted_threshold(4, 4) == 1 << 31
+    assert orc.weighted_threshold(2, 1) == (1 << 32) // 3
+    assert orc.weighted_threshold(1, 2) == (2 << 32) // 3
+    # same stream, same decision rule as the unweighted merge
+    recv, local = 0x0123456789ABCDEF, 0xFEDCBA9876543210
+    for m in (2, 3, 7):
+        assert orc.merge_word_weighted(recv, local, m - 1, 1, 5, 99, 1234) == orc.merge_word(recv, local, m, 5, 99, 1234)
+
+
+def _tree_merges(M):
+    """(level, receiver, sender, w_local, w_recv) of the binary reduction tree, bottom level first."""
+    out, stride, level = [], 1, 0
+    while stride < M:
+        for k in range(0, M - stride, 2 * stride):
+            src = k + stride
+            out.append((level, k, src, min(stride, M - k), min(stride, M - src)))
+        stride *= 2
+        level += 1
+    return out
+
+
+@pytest.mark.parametrize("M", [2, 3, 4, 5, 6, 7])
+def test_exact_unbiasedness_tree(M):
+    merges = _tree_merges(M)
+    assert len(merges) == M - 1
+    for bits in itertools.product((0, 1), repeat=M):
+        total = Fraction(0)
+        for draws in itertools.product((0, 1), repeat=len(merges)):
+            val = list(bits)
+            weight = Fraction(1)
+            for (level, k, src, wl, wr), t in zip(merges, draws):
+                p = Fraction(wl, wl + wr)
+                weight *= p if t else 1 - p
+                val[k] = orc.odot(val[src], val[k], orc.transient_from_keep(val[k], t)) & 1
+            total += weight * val[0]
+        assert total == Fraction(sum(bits), M)
+
+
+def _tree_leaf(M, seed, w, j):
+    """Second formulation: walk from the root towards the leaves; at every merge on the way the
+    draw decides between the receiver's own subtree and the sender's."""
+    top = 0
+    while (1 << top) < M:
+        top += 1
+    k = 0
+    for level in range(top - 1, -1, -1):
+        stride = 1 << level
+        src = k + stride
+        if src >= M:
+            continue
+        wl, wr = min(stride, M - k), min(stride, M - src)
+        u = philox_ref.stream_u32(seed, (2 << 16) | (level << 8) | k, w, j)
+        if not u < (wl << 32) // (wl + wr):
+            k = src
+    return k
+
+
+@pytest.mark.parametrize("M,d", [(2, 64 * 3 + 5), (3, 64 * 4), (5, 64 * 3 + 63), (8, 64 * 6 + 1), (11, 64 * 2 + 9)])
+def test_tree_second_formulation(M, d):
+    rng = np.random.default_rng(200 + M)
+    g = rng.standard_normal((M, d)).astype(np.float32)
+    c = (0.3 * rng.standard_normal((M, d))).astype(np.float32)
+    seed = 0xFACE0000 + M
+    s = g + c
+    want = np.array([0 if np.signbit(s[_tree_leaf(M, seed, e // 64, e % 64), e]) else 1 for e in range(d)],
+                    dtype=np.uint8)
+    c_before = c.copy()
+    update, bits = orc.tree_step(g, c, 0.25, seed)
+    got = ((bits[np.arange(d) // 64] >> (np.arange(d) % 64).astype(np.uint64)) & np.uint64(1)).astype(np.uint8)
+    assert np.array_equal(got, want)
+    assert np.array_equal(update, np.where(want == 1, np.float32(0.25), np.float32(-0.25)))
+    assert np.array_equal(c.view(np.uint32), ((g + c_before) - update[None, :]).view(np.uint32))
+
+
+@pytest.mark.parametrize("M,patterns", [(3, list(range(8))), (6, [0, 1, 32, 7, 56, 21, 63, 44]), (8, [0x01, 0x80, 0x0F, 0xAA, 0x7F, 0xFF])])
+def test_tree_empirical_unbiasedness(M, patterns):
+    n_rep = 1 << 17
+    g = _pattern_inputs(patterns, M, n_rep)
+    update, _ = orc.tree_step(g, np.zeros_like(g), 1.0, 0xABCD + M)
+    plus = (update > 0).reshape(len(patterns), n_rep)
+    for p, pat in enumerate(patterns):
+        mean = bin(pat).count("1") / M
+        assert abs(plus[p].mean() - mean) <= 5.0 * np.sqrt(max(mean * (1 - mean), 1e-12) / n_rep)
