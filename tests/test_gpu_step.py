@@ -100,3 +100,42 @@ def test_marsit_driven_sgd_loop(M, grid_x, K):
         # the model: apply the GPU's own update on the host copy, must agree exactly
         x_h = orc.apply_update(x_h, host_f32(u_d).copy())
         assert np.array_equal(host_f32(x_d), x_h), t
+
+
+def test_step_can_be_captured_in_a_hip_graph():
+    """The library launches kernels only (no memset, no allocation, no synchronisation), so a step
+    can be captured and replayed; every replay must reproduce the eager result, with eager work
+    and synchronisations between the replays."""
+    M, d, scale, seed = 8, 300_000 + 5, 1e-3, 2718
+    rng = np.random.default_rng(5)
+    g_h = rng.standard_normal((M, d)).astype(np.float32)
+    g_d = dev(g_h)
+    c_static = torch.zeros((M, d), dtype=torch.float32, device="cuda")
+    u_static = torch.empty(d, dtype=torch.float32, device="cuda")
+    b_static = marsit.new_bitmap(d)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # warm-up outside the capture
+        marsit.marsit_step(3, 100, g_d, c_static, u_static, b_static, scale, seed)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+
+    graph = torch.cuda.CUDAGraph()
+    c_static.zero_()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        marsit.marsit_step(3, 100, g_d, c_static, u_static, b_static, scale, seed)
+        marsit.marsit_step(4, 100, g_d, c_static, u_static, b_static, scale, seed + 1)
+
+    c_h = np.zeros((M, d), dtype=np.float32)
+    for replay in range(3):
+        graph.replay()
+        torch.cuda.synchronize()
+        orc.sync_step(g_h, c_h, scale, seed)
+        want_u, want_b, _ = orc.sync_step(g_h, c_h, scale, seed + 1)
+        assert np.array_equal(host_bits(b_static), want_b), replay
+        assert np.array_equal(host_f32(u_static), want_u), replay
+        assert_f32_parity(host_f32(c_static), c_h, f"c after replay {replay}")
+        # eager work between replays
+        scratch = torch.randn(1000, device="cuda").sum().item()
+        assert np.isfinite(scratch)
