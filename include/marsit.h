@@ -231,6 +231,34 @@ int marsit_majority_vote(const float *g, const float *c, uint64_t *bits_out, uin
 int marsit_count_matching(const uint64_t *bits_a, const uint64_t *bits_b, uint64_t d,
                           uint64_t *count_out, void *stream);
 
+/*
+ * The strawman of Section 3.2 -- a comparison point, NOT part of Marsit: SSDM's stochastic sign
+ * Q(.) (Appendix A: +1 with probability 1/2 + v_j / (2 ||v||)) and cascading compression
+ * (receive, recover, aggregate, compress, send).
+ *
+ * marsit_ssdm_cascade_hop, one hop on a run of n elements (element 0 = bit 0 of bits word 0):
+ *     t[e]    = (recv_bits ? (+-*recv_norm by the received sign) : 0) + (g[e] + c[e])       fp32
+ *     *norm_out = sqrtf((float) sum_e (double)t[e]^2)
+ *     bit e of bits_out = (double)u_e < (double)(0.5f + t[e] / (2.0f * *norm_out)) * 2^32
+ *   u_e from the Philox stream of (seed, hop_id, word_begin + e/64), position e%64; p = 0.5 when the
+ *   norm is 0.  recv_bits == NULL: the first holder (t = g + c).  bits_out may be recv_bits;
+ *   norm_out must not be recv_norm.  recv_norm, norm_out: DEVICE floats.
+ *   workspace: DEVICE scratch of MARSIT_CASCADE_WORKSPACE_BYTES bytes, 8-byte aligned.
+ *
+ * marsit_cascade_ring_step_sim, the whole strawman over the ring of M workers: part i of the
+ * word-aligned split starts at worker i as Q(s^(i)) and takes M-1 cascade hops (hop id (3<<16)|h);
+ * update_out[e] = (+-final norm of the part) / M; norms_out [M] (DEVICE) final norm per part.
+ * c is read (s = g + c) but not updated: the strawman has no compensation step.
+ */
+#define MARSIT_CASCADE_WORKSPACE_BYTES 8256u
+int marsit_ssdm_cascade_hop(const uint64_t *recv_bits, const float *recv_norm, const float *g,
+                            const float *c, uint64_t *bits_out, float *norm_out, void *workspace,
+                            uint64_t word_begin, uint64_t n, uint32_t hop_id, uint64_t seed,
+                            void *stream);
+int marsit_cascade_ring_step_sim(const float *g, const float *c, float *update_out, uint64_t *bits_out,
+                                 float *norms_out, void *workspace, uint32_t M, uint64_t d, uint64_t ld,
+                                 uint64_t seed, void *stream);
+
 /* Algorithm 2, line 6:  x[e] <- x[e] - update[e]. */
 int marsit_apply_update(float *x, const float *update, uint64_t d, void *stream);
 

@@ -44,6 +44,7 @@
 #include <stddef.h>
 #include <stdlib.h>
 #include <string.h>
+#include <math.h>
 
 #define ORACLE_MAX_WORKERS 64
 
@@ -496,5 +497,115 @@ int oracle_tree_step(const float *g, float *c, float *update, uint64_t *bits_fin
     if (bits_final != NULL)
         memcpy(bits_final, B, (size_t)W * sizeof(uint64_t));
     free(s); free(B);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * The strawman of Section 3.2: SSDM's stochastic sign Q(.) and cascading compression.
+ *
+ * Appendix A: an element v_j is compressed to +1 with probability 1/2 + v_j / (2 ||v||), to -1
+ * otherwise; Q(v) = ||v|| * sign~(v), an unbiased estimate of v.  (Section 3.2 prints the
+ * probability as 1/2 + |g_i| / ||g||; the appendix form is the one whose expectation the proof
+ * uses, and the one taken here.)
+ *
+ * Arithmetic, fixed so that the stochastic decision is the same integer on every machine:
+ *   norm   = sqrtf( (float) sum_j (double)t_j * (double)t_j )        (sum in double)
+ *   p_j    = 0.5f + t_j / (2.0f * norm)     in fp32, one rounding per operation; 0.5f if norm == 0
+ *   bit_j  = 1  iff  (double)u_j < (double)p_j * 2^32,
+ * u_j being the j-th 32-bit word of the Philox stream of (seed, hop id, packed word).
+ * ---------------------------------------------------------------------------------------- */
+float oracle_l2_norm(const float *t, uint64_t n)
+{
+    double acc = 0.0;
+    for (uint64_t e = 0; e < n; ++e)
+        acc += (double)t[e] * (double)t[e];
+    return sqrtf((float)acc);
+}
+
+/* bits[] covers the n elements starting at bit 0 of word 0; word_begin keys the stream. */
+void oracle_ssdm_sign(const float *t, float norm, uint64_t *bits, uint64_t n, uint64_t word_begin,
+                      uint32_t hop_id, uint64_t seed)
+{
+    uint64_t n_words = (n + 63u) / 64u;
+    for (uint64_t w = 0; w < n_words; ++w)
+        bits[w] = 0;
+    for (uint64_t e = 0; e < n; ++e) {
+        float p = 0.5f;
+        if (norm != 0.0f) {
+            float twice = 2.0f * norm;
+            float q = t[e] / twice;
+            p = 0.5f + q;
+        }
+        uint32_t u = oracle_stream_u32(seed, hop_id, word_begin + e / 64u, (uint32_t)(e % 64u));
+        if ((double)u < (double)p * 4294967296.0)
+            bits[e / 64u] |= (uint64_t)1 << (e % 64u);
+    }
+}
+
+/* hop ids of the cascading chain: phase 3, hop h (h = 0 is the first holder's own compression). */
+uint32_t oracle_cascade_hop_id(uint32_t hop)
+{
+    return (3u << 16) | hop;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Cascading compression over the ring (Section 3.2's five steps), per part i of the word-aligned
+ * split: the first holder sends Q(s^(i)); at hop h worker (i+h) mod M receives (norm, signs),
+ * recovers w = norm * signs, aggregates t = w + s^(local), compresses Q(t) and sends it on.
+ * After M-1 hops the part's result is (1/M) * norm * signs.
+ *   g, c        [M][ld]; s = g + c as in Algorithm 1 line 1 (c is NOT updated: the strawman has no
+ *               compensation step)
+ *   bits_final  [W] final signs;  norms_final [M] final norm of every part
+ *   update      [d]  (1/M) * norm_part * (+-1)
+ * Returns 0, -1 for bad arguments, -2 if memory ran out.
+ * ---------------------------------------------------------------------------------------- */
+int oracle_cascade_ring_step(const float *g, const float *c, float *update, uint64_t *bits_final,
+                             float *norms_final, uint32_t M, uint64_t d, uint64_t ld, uint64_t seed)
+{
+    if (M == 0 || M > ORACLE_MAX_WORKERS || ld < d || g == NULL || c == NULL || update == NULL ||
+        bits_final == NULL || norms_final == NULL)
+        return -1;
+    if (d == 0)
+        return 0;
+    uint64_t W = (d + 63u) / 64u;
+    uint64_t bounds[ORACLE_MAX_WORKERS + 1];
+    oracle_split_bounds(0, W, M, bounds);
+    uint64_t max_elems = (W / M + 1u) * 64u;
+    float *t = (float *)malloc((size_t)max_elems * sizeof(float));
+    uint64_t *bits = (uint64_t *)malloc((size_t)(W / M + 1u) * sizeof(uint64_t));
+    if (t == NULL || bits == NULL) {
+        free(t); free(bits);
+        return -2;
+    }
+    for (uint32_t i = 0; i < M; ++i) {
+        uint64_t lo = bounds[i], hi = bounds[i + 1];
+        norms_final[i] = 0.0f;
+        if (hi == lo)
+            continue;
+        uint64_t e0 = lo * 64u, e1 = (hi * 64u < d) ? hi * 64u : d, n = e1 - e0;
+        float norm = 0.0f;
+        for (uint32_t h = 0; h < M; ++h) {
+            uint32_t worker = (i + h) % M;
+            for (uint64_t e = 0; e < n; ++e) {
+                float local = g[(size_t)worker * ld + e0 + e] + c[(size_t)worker * ld + e0 + e];
+                if (h == 0) {
+                    t[e] = local;                                   /* first holder: its own vector */
+                } else {
+                    float recovered = ((bits[e / 64u] >> (e % 64u)) & 1u) ? norm : -norm;   /* recover */
+                    t[e] = recovered + local;                        /* aggregate */
+                }
+            }
+            norm = oracle_l2_norm(t, n);                             /* compress ... */
+            oracle_ssdm_sign(t, norm, bits, n, lo, oracle_cascade_hop_id(h), seed);
+        }                                                            /* ... and send */
+        norms_final[i] = norm;
+        for (uint64_t w = lo; w < hi; ++w)
+            bits_final[w] = bits[w - lo];
+        for (uint64_t e = 0; e < n; ++e) {
+            float v = ((bits[e / 64u] >> (e % 64u)) & 1u) ? norm : -norm;
+            update[e0 + e] = v / (float)M;
+        }
+    }
+    free(t); free(bits);
     return 0;
 }

@@ -29,7 +29,7 @@ def build_oracle(force: bool = False) -> str:
     """Compile the C oracle into ``oracle/libmarsit_oracle.so`` and return its path."""
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-std=c11", "-O2", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
-               "-fno-fast-math", "-Wall", "-Wextra", "-o", _SO, _SRC]
+               "-fno-fast-math", "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _SO
 
@@ -89,6 +89,14 @@ def _load():
     lib.oracle_hop_merge_weighted.restype = ctypes.c_int
     lib.oracle_tree_hop_id.argtypes = [u32, u32]
     lib.oracle_tree_hop_id.restype = u32
+    lib.oracle_l2_norm.argtypes = [vp, u64]
+    lib.oracle_l2_norm.restype = f32
+    lib.oracle_ssdm_sign.argtypes = [vp, f32, vp, u64, u64, u32, u64]
+    lib.oracle_ssdm_sign.restype = None
+    lib.oracle_cascade_hop_id.argtypes = [u32]
+    lib.oracle_cascade_hop_id.restype = u32
+    lib.oracle_cascade_ring_step.argtypes = [vp, vp, vp, vp, vp, u32, u64, u64, u64]
+    lib.oracle_cascade_ring_step.restype = ctypes.c_int
     lib.oracle_tree_step.argtypes = [vp, vp, vp, vp, u32, u64, u64, f32, u64]
     lib.oracle_tree_step.restype = ctypes.c_int
     _lib = lib
@@ -329,3 +337,38 @@ def tree_step(g, c, scale: float, seed: int, d: int | None = None):
     if rc != 0:
         raise ValueError(f"oracle_tree_step failed (rc={rc})")
     return update, bits
+
+
+# --- the strawman of Section 3.2: SSDM stochastic sign, cascading compression -----------------
+
+def l2_norm(t) -> float:
+    t = _f32(t, "t")
+    return float(_load().oracle_l2_norm(_ptr(t), t.size))
+
+
+def ssdm_sign(t, norm: float, word_begin: int, hop: int, seed: int):
+    t = _f32(t, "t")
+    bits = np.zeros(n_words(t.size), dtype=np.uint64)
+    _load().oracle_ssdm_sign(_ptr(t), norm, _ptr(bits), t.size, word_begin, hop, seed)
+    return bits
+
+
+def cascade_hop_id(hop: int) -> int:
+    return int(_load().oracle_cascade_hop_id(hop))
+
+
+def cascade_ring_step(g, c, seed: int, d: int | None = None):
+    """Cascading compression with SSDM over the ring.  Returns ``(update[d], bits[W], norms[M])``."""
+    g = _f32(g, "g")
+    c = _f32(c, "c")
+    assert g.ndim == 2 and g.shape == c.shape
+    M, ld = g.shape
+    d = ld if d is None else int(d)
+    update = np.zeros(d, dtype=np.float32)
+    bits = np.zeros(n_words(d), dtype=np.uint64)
+    norms = np.zeros(M, dtype=np.float32)
+    rc = _load().oracle_cascade_ring_step(_ptr(g), _ptr(c), _ptr(update), _ptr(bits), _ptr(norms),
+                                          M, d, ld, seed)
+    if rc != 0:
+        raise ValueError(f"oracle_cascade_ring_step failed (rc={rc})")
+    return update, bits, norms

@@ -28,6 +28,7 @@ EXPORTS = (
     "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
     "marsit_aggregate_sign", "marsit_majority_vote", "marsit_count_matching",
     "marsit_hop_merge_weighted", "marsit_tree_step_sim",
+    "marsit_ssdm_cascade_hop", "marsit_cascade_ring_step_sim",
 )
 
 _lib = None
@@ -90,6 +91,10 @@ def load_library(path: str | None = None):
     lib.marsit_hop_merge_weighted.restype = ci
     lib.marsit_tree_step_sim.argtypes = [vp, vp, vp, vp, u32, u64, u64, f32, u64, vp]
     lib.marsit_tree_step_sim.restype = ci
+    lib.marsit_ssdm_cascade_hop.argtypes = [vp, vp, vp, vp, vp, vp, vp, u64, u64, u32, u64, vp]
+    lib.marsit_ssdm_cascade_hop.restype = ci
+    lib.marsit_cascade_ring_step_sim.argtypes = [vp, vp, vp, vp, vp, vp, u32, u64, u64, u64, vp]
+    lib.marsit_cascade_ring_step_sim.restype = ci
     lib.marsit_aggregate_sign.argtypes = [vp, vp, vp, u32, u64, u64, vp]
     lib.marsit_aggregate_sign.restype = ci
     lib.marsit_majority_vote.argtypes = [vp, vp, vp, u32, u64, u64, vp]
@@ -356,3 +361,38 @@ def marsit_tree_step_sim(g, c, update_out, bits_out, scale: float, seed: int, d:
         _bits_ptr(bits_out, "bits_out", True), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF,
         _stream(stream)))
     return update_out, bits_out
+
+
+# --- the strawman of Section 3.2 (comparison point) ------------------------------------------------
+
+CASCADE_WORKSPACE_BYTES = 8256
+
+
+def new_cascade_workspace(device="cuda") -> torch.Tensor:
+    return torch.empty(CASCADE_WORKSPACE_BYTES // 8, dtype=torch.int64, device=device)
+
+
+def marsit_ssdm_cascade_hop(recv_bits, recv_norm, g, c, bits_out, norm_out, workspace, word_begin: int,
+                            n: int, hop_id: int, seed: int, stream=None):
+    """``recv_norm``/``norm_out``: one-element float32 tensors in device memory."""
+    _check("marsit_ssdm_cascade_hop", load_library().marsit_ssdm_cascade_hop(
+        _bits_ptr(recv_bits, "recv_bits", True), _f32_ptr(recv_norm, "recv_norm", True), _f32_ptr(g, "g"),
+        _f32_ptr(c, "c"), _bits_ptr(bits_out, "bits_out"), _f32_ptr(norm_out, "norm_out"),
+        _bits_ptr(workspace, "workspace"), word_begin, n, hop_id, seed & 0xFFFFFFFFFFFFFFFF,
+        _stream(stream)))
+    return bits_out, norm_out
+
+
+def marsit_cascade_ring_step_sim(g, c, update_out, bits_out, norms_out, workspace, seed: int,
+                                 d: int | None = None, stream=None):
+    M, ld = _rows(g, "g")
+    if _rows(c, "c") != (M, ld):
+        raise TypeError("g and c must have the same shape and row stride")
+    d = g.shape[1] if d is None else int(d)
+    if norms_out.numel() < M:
+        raise ValueError("norms_out needs M elements")
+    _check("marsit_cascade_ring_step_sim", load_library().marsit_cascade_ring_step_sim(
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
+        _bits_ptr(bits_out, "bits_out"), _f32_ptr(norms_out, "norms_out"),
+        _bits_ptr(workspace, "workspace"), M, d, ld, seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
+    return update_out, bits_out, norms_out

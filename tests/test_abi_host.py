@@ -151,6 +151,13 @@ def test_other_entry_points_argument_validation(lib):
     assert lib.marsit_tree_step_sim(FAKE, FAKE + 2, FAKE, None, 8, 64, 64, 1.0, 1, None) == marsit.EALIGN
     assert lib.marsit_tree_step_sim(FAKE, FAKE, FAKE, None, 8, 0, 64, 1.0, 1, None) == marsit.OK
 
+    assert lib.marsit_ssdm_cascade_hop(None, None, FAKE, FAKE, FAKE, None, FAKE, 0, 64, 1, 5, None) == marsit.EINVAL
+    assert lib.marsit_ssdm_cascade_hop(FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, 0, 64, 1, 5, None) == marsit.EINVAL
+    assert lib.marsit_ssdm_cascade_hop(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 0, 64, 1, 5, None) == marsit.EINVAL
+    assert lib.marsit_ssdm_cascade_hop(None, None, FAKE, FAKE, FAKE, FAKE, FAKE, 0, 0, 1, 5, None) == marsit.OK
+    assert lib.marsit_cascade_ring_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, None, 4, 64, 64, 5, None) == marsit.EINVAL
+    assert lib.marsit_cascade_ring_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, 0, 64, 5, None) == marsit.OK
+
     assert lib.marsit_apply_update(None, FAKE, 64, None) == marsit.EINVAL
     assert lib.marsit_apply_update(FAKE, FAKE, 0, None) == marsit.OK
 

@@ -635,3 +635,102 @@ def test_tree_empirical_unbiasedness(M, patterns):
     for p, pat in enumerate(patterns):
         mean = bin(pat).count("1") / M
         assert abs(plus[p].mean() - mean) <= 5.0 * np.sqrt(max(mean * (1 - mean), 1e-12) / n_rep)
+
+
+# ---------------------------------------------------------------------------------------------
+# The strawman of Section 3.2: SSDM's stochastic sign and cascading compression
+# ---------------------------------------------------------------------------------------------
+
+def test_l2_norm_matches_numpy():
+    rng = np.random.default_rng(40)
+    t = rng.standard_normal(10_001).astype(np.float32)
+    want = np.sqrt(np.float32(np.sum(t.astype(np.float64) ** 2)))
+    assert orc.l2_norm(t) == float(np.float32(want))
+    assert orc.l2_norm(np.zeros(5, dtype=np.float32)) == 0.0
+
+
+def test_ssdm_sign_probability_is_the_appendix_formula():
+    """Count, over the whole stream definition, how often +1 comes out: for one element the decision
+    is u < p * 2^32 with p = 1/2 + v/(2||v||) evaluated in fp32, so P(+1) = ceil(p * 2^32) / 2^32."""
+    v = np.array([3.0, -4.0, 0.0, 12.0], dtype=np.float32)          # ||v|| = 13
+    norm = orc.l2_norm(v)
+    assert norm == 13.0
+    # empirical frequency over many packed words (same 4 values replicated in the first bits)
+    n_words = 1 << 15
+    t = np.zeros(n_words * 64, dtype=np.float32)
+    t.reshape(n_words, 64)[:, :4] = v
+    bits = orc.ssdm_sign(t, norm, 0, orc.cascade_hop_id(0), 4242)
+    for j, vj in enumerate(v):
+        freq = float(((bits >> np.uint64(j)) & np.uint64(1)).mean())
+        p = 0.5 + float(vj) / 26.0
+        assert abs(freq - p) <= 5 * np.sqrt(p * (1 - p) / n_words), (j, freq, p)
+    # zero entries are fair coins, and so is everything when the norm is zero
+    freq0 = float(((bits >> np.uint64(10)) & np.uint64(1)).mean())
+    assert abs(freq0 - 0.5) <= 5 * 0.5 / np.sqrt(n_words)
+    z = orc.ssdm_sign(np.zeros(64 * 4096, dtype=np.float32), 0.0, 0, 1, 7)
+    ones = sum(bin(int(x)).count("1") for x in z)
+    assert abs(ones / (64 * 4096) - 0.5) <= 5 * 0.5 / np.sqrt(64 * 4096)
+
+
+def test_ssdm_decision_rule_against_python():
+    rng = np.random.default_rng(41)
+    t = rng.standard_normal(64 * 3 + 7).astype(np.float32)
+    norm = np.float32(orc.l2_norm(t))
+    seed, hop, begin = 99, orc.cascade_hop_id(3), 1000
+    bits = orc.ssdm_sign(t, float(norm), begin, hop, seed)
+    for e in range(t.size):
+        p = np.float32(0.5) + t[e] / (np.float32(2.0) * norm)
+        u = philox_ref.stream_u32(seed, hop, begin + e // 64, e % 64)
+        want = 1 if float(u) < float(p) * 4294967296.0 else 0
+        assert (int(bits[e // 64]) >> (e % 64)) & 1 == want
+
+
+def test_ssdm_is_unbiased():
+    """Appendix A: E[ ||v|| * sign~(v) ] = v."""
+    rng = np.random.default_rng(42)
+    v = rng.standard_normal(64).astype(np.float32)
+    norm = orc.l2_norm(v)
+    n = 20_000
+    acc = np.zeros(64)
+    for s in range(n):
+        b = int(orc.ssdm_sign(v, norm, 0, 1, 1000 + s)[0])
+        acc += np.array([1.0 if (b >> j) & 1 else -1.0 for j in range(64)])
+    est = norm * acc / n
+    assert np.all(np.abs(est - v) <= 5 * norm / np.sqrt(n))
+
+
+def test_cascading_compression_is_unbiased_for_the_sum():
+    """Section 3.2: the expected result of cascading compression equals the sum of all gradients
+    (update * M estimates sum_m s^(m)); checked on a tiny vector over many seeds."""
+    rng = np.random.default_rng(43)
+    M, d = 3, 64
+    g = rng.standard_normal((M, d)).astype(np.float32)
+    c = np.zeros_like(g)
+    n = 6000
+    acc = np.zeros(d)
+    worst = 0.0
+    for s in range(n):
+        upd, bits, norms = orc.cascade_ring_step(g, c, 5000 + s)
+        acc += upd.astype(np.float64) * M
+        worst = max(worst, float(norms.max()))
+    total = g.astype(np.float64).sum(axis=0)
+    assert np.all(np.abs(acc / n - total) <= 5 * worst / np.sqrt(n))
+
+
+def test_cascading_matching_rate_is_near_a_coin_flip_and_below_marsit():
+    """Fig. 2(b)'s ordering on synthetic data: with a large part the l2 norm swamps every element,
+    the stochastic sign is nearly a fair coin, and cascading compression matches the sign of the
+    true aggregate far less often than Marsit's merged signs (and those less often than a majority
+    vote)."""
+    rng = np.random.default_rng(44)
+    M, d = 3, 1 << 17
+    g = rng.standard_normal((M, d)).astype(np.float32)
+    c = np.zeros_like(g)
+    ref = orc.aggregate_sign(g, c)
+    _, cas_bits, _ = orc.cascade_ring_step(g, c, 11)
+    _, mar_bits, _ = orc.sync_step(g, c.copy(), 1.0, 11, threads=4)
+    r_cas = orc.count_matching(cas_bits, ref, d) / d
+    r_mar = orc.count_matching(mar_bits, ref, d) / d
+    r_maj = orc.count_matching(orc.majority_vote(g, c), ref, d) / d
+    assert 0.5 - 0.01 < r_cas < 0.52
+    assert r_cas + 0.1 < r_mar < r_maj
