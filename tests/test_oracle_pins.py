@@ -734,3 +734,30 @@ def test_cascading_matching_rate_is_near_a_coin_flip_and_below_marsit():
     r_maj = orc.count_matching(orc.majority_vote(g, c), ref, d) / d
     assert 0.5 - 0.01 < r_cas < 0.52
     assert r_cas + 0.1 < r_mar < r_maj
+
+
+@pytest.mark.parametrize("M", [1, 2, 3, 5, 8])
+def test_cascading_on_a_single_element_is_the_exact_mean(M):
+    """With one element the l2 norm is |t|, the stochastic sign is certain (p is 0 or 1), and every
+    hop recovers the running sum exactly: the result is the plain mean, whatever the seed."""
+    rng = np.random.default_rng(50 + M)
+    for trial in range(20):
+        s = rng.standard_normal((M, 1)).astype(np.float32)
+        upd, bits, norms = orc.cascade_ring_step(s, np.zeros_like(s), 1000 + trial)
+        # the last part's chain starts at worker M-1 and goes round the ring
+        order = [(M - 1 + h) % M for h in range(M)]
+        run = np.float32(s[order[0], 0])
+        for m in order[1:]:
+            run = np.float32(run + s[m, 0])
+        assert upd[0] == np.float32(run / np.float32(M))
+        assert int(bits[0]) == (0 if np.signbit(run) else 1)
+        assert norms[M - 1] == np.float32(abs(run))      # the only packed word falls in the last part
+
+
+def test_majority_vote_ties_count_as_plus():
+    g = np.array([[1.0, -1.0, 2.0, -2.0], [-1.0, 1.0, 2.0, -2.0]], dtype=np.float32)
+    assert int(orc.majority_vote(g, np.zeros_like(g))[0]) == 0b0111
+    g4 = np.array([[1.0], [1.0], [-1.0], [-1.0]], dtype=np.float32)
+    assert int(orc.majority_vote(g4, np.zeros_like(g4))[0]) == 1
+    g4[0, 0] = -1.0
+    assert int(orc.majority_vote(g4, np.zeros_like(g4))[0]) == 0
