@@ -34,8 +34,8 @@ def inputs(M: int, d: int, step: int) -> np.ndarray:
     """Integer-hash based values in [-1, 1): identical on every machine and library version."""
     m = np.arange(M, dtype=np.uint64)[:, None]
     e = np.arange(d, dtype=np.uint64)[None, :]
-    x = (m * np.uint64(0x9E3779B97F4A7C15) + e * np.uint64(0xBF58476D1CE4E5B9) +
-         np.uint64(step) * np.uint64(0x94D049BB133111EB) + np.uint64(12345))
+    offset = np.uint64((step * 0x94D049BB133111EB + 12345) & 0xFFFFFFFFFFFFFFFF)
+    x = m * np.uint64(0x9E3779B97F4A7C15) + e * np.uint64(0xBF58476D1CE4E5B9) + offset
     x ^= x >> np.uint64(31)
     x *= np.uint64(0xD6E8FEB86659FD93)
     x ^= x >> np.uint64(29)
