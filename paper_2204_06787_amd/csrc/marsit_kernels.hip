@@ -181,8 +181,9 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
 
 // -------------------------------------------------------------------------------------------------
 // Fused pass, any schedule (X, Y at run time), any alignment, ragged tails.  Covers columns
-// col_begin .. ceil(d/4)-1 (col_begin is a multiple of 16).  Two sweeps over the workers: the first
-// carries the chains, the second re-reads g and c to write the compensation.
+// col_begin .. ceil(d/4)-1 (col_begin is a multiple of 16).  The chains are evaluated on the draws
+// alone (which worker does each bit end up taking), that worker's sign is fetched, and one sweep
+// over the workers writes the compensation: 12*M + 12 bytes per element.
 // -------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kBlock)
 sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
@@ -210,49 +211,58 @@ sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
         const uint32_t a = f / Y;
         const uint32_t b = f % Y;
 
-        uint32_t fin[4] = {0, 0, 0, 0};
-        for (uint32_t ky = 0; ky < Y; ++ky) {
-            uint32_t y = b + ky;
-            y = (y >= Y) ? y - Y : y;
-            uint32_t row_res[4] = {0, 0, 0, 0};
-            for (uint32_t kx = 0; kx < X; ++kx) {
-                uint32_t x = a + kx;
-                x = (x >= X) ? x - X : x;
-                const size_t off = static_cast<size_t>(y * X + x) * ld + e;
-                const f32x4 sv = load4(g + off, vec, n_valid) + load4(c + off, vec, n_valid);
-                if (kx == 0) {
+        // The draws do not depend on the data, and only the last successful draw of a chain
+        // matters: find the picked worker of every bit first, then fetch that one sign.
+        // Column chain (shared by the lane's four bits): which row result survives.
+        uint32_t pick_col[4] = {0, 0, 0, 0};
+        for (uint32_t ky = 1; ky < Y; ++ky) {
+            uint32_t u[4];
+            philox4x32_10(q, col_hop_id(ky), w, 0u, key0, key1, u);
+            const uint32_t thr = thresholds.thr[ky + 1];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        row_res[j] = f32_bits(sv[j]);
-                } else {
-                    uint32_t u[4];
-                    philox4x32_10(q, row_hop_id(y, kx), w, 0u, key0, key1, u);
-                    const uint32_t thr = thresholds.thr[kx + 1];
+            for (int j = 0; j < 4; ++j)
+                pick_col[j] = (u[j] < thr) ? ky : pick_col[j];
+        }
+        // Row chain of the surviving row.  On a ring all four bits share the one row and one call
+        // per hop serves them; on a torus the rows differ per bit.
+        uint32_t row_of[4], pick_row[4] = {0, 0, 0, 0};
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        row_res[j] = (u[j] < thr) ? f32_bits(sv[j]) : row_res[j];
-                }
-            }
-            if (ky == 0) {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    fin[j] = row_res[j];
-            } else {
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t y = b + pick_col[j];
+            row_of[j] = (y >= Y) ? y - Y : y;
+        }
+        if (Y == 1) {
+            for (uint32_t kx = 1; kx < X; ++kx) {
                 uint32_t u[4];
-                philox4x32_10(q, col_hop_id(ky), w, 0u, key0, key1, u);
-                const uint32_t thr = thresholds.thr[ky + 1];
+                philox4x32_10(q, row_hop_id(0, kx), w, 0u, key0, key1, u);
+                const uint32_t thr = thresholds.thr[kx + 1];
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    fin[j] = (u[j] < thr) ? row_res[j] : fin[j];
+                    pick_row[j] = (u[j] < thr) ? kx : pick_row[j];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                for (uint32_t kx = 1; kx < X; ++kx) {
+                    uint32_t u[4];
+                    philox4x32_10(q, row_hop_id(row_of[j], kx), w, 0u, key0, key1, u);
+                    pick_row[j] = (u[j] < thresholds.thr[kx + 1]) ? kx : pick_row[j];
+                }
             }
         }
 
-        f32x4 upd;
+        f32x4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const uint32_t sign = fin[j] & 0x80000000u;
-            upd[j] = __uint_as_float(scale_bits ^ sign);
-            nib |= ((static_cast<uint32_t>(j) < n_valid) && sign == 0u) ? (1u << j) : 0u;
+            if (static_cast<uint32_t>(j) < n_valid) {
+                uint32_t x = a + pick_row[j];
+                x = (x >= X) ? x - X : x;
+                const size_t at = static_cast<size_t>(row_of[j] * X + x) * ld + e + j;
+                const float sv = g[at] + c[at];                       // line 1 for the picked worker
+                const uint32_t sign = f32_bits(sv) & 0x80000000u;
+                upd[j] = __uint_as_float(scale_bits ^ sign);          // line 9
+                nib |= (sign == 0u) ? (1u << j) : 0u;
+            }
         }
         store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
 
