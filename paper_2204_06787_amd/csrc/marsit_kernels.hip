@@ -179,13 +179,100 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
         bits32[2u * static_cast<size_t>(w) + (q >> 3)] = half;
 }
 
+// Staging area of the generic kernels: s = g + c of every worker for the wavefront's 64 columns,
+// [M][64] 128-bit entries in dynamic LDS (M KB per one-wavefront workgroup).  A lane only ever
+// touches its own entries, so no barrier is needed.  With it g and c are read once and c is
+// written once, whatever M is.
+extern __shared__ __align__(16) unsigned char marsit_dynamic_lds[];
+
+constexpr int kSweepBatch = 8;   // workers whose loads are issued back to back
+
+// Algorithm 1, line 1 for a run-time number of workers: s -> LDS.
+__device__ __forceinline__ void stage_sums(const float *__restrict__ g, const float *c, f32x4 *stage,
+                                           uint32_t M, uint64_t ld, uint64_t e, bool vec,
+                                           uint32_t n_valid)
+{
+    for (uint32_t m0 = 0; m0 < M; m0 += kSweepBatch) {
+        f32x4 gv[kSweepBatch], cv[kSweepBatch];
+#pragma unroll
+        for (int i = 0; i < kSweepBatch; ++i) {
+            if (m0 + i < M) {
+                const size_t off = static_cast<size_t>(m0 + i) * ld + e;
+                gv[i] = load4(g + off, vec, n_valid);
+                cv[i] = load4(c + off, vec, n_valid);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kSweepBatch; ++i)
+            if (m0 + i < M)
+                stage[static_cast<size_t>(m0 + i) * kSyncBlock + threadIdx.x] = gv[i] + cv[i];
+    }
+}
+
+// Algorithm 1, line 10 for a run-time number of workers: c <- s - update, s from LDS.
+__device__ __forceinline__ void compensate_from_stage(float *c, const f32x4 *stage, f32x4 upd,
+                                                      uint32_t M, uint64_t ld, uint64_t e, bool vec,
+                                                      uint32_t n_valid)
+{
+#pragma unroll 4
+    for (uint32_t m = 0; m < M; ++m) {
+        const f32x4 sv = stage[static_cast<size_t>(m) * kSyncBlock + threadIdx.x];
+        store4<MARSIT_STREAMING_STORES>(c + static_cast<size_t>(m) * ld + e, sv - upd, vec, n_valid);
+    }
+}
+
+// The same without the staging area (for M so large that the area would leave too few wavefronts
+// per CU): g and c are read again.
+__device__ __forceinline__ void compensate_from_memory(const float *__restrict__ g, float *c, f32x4 upd,
+                                                       uint32_t M, uint64_t ld, uint64_t e, bool vec,
+                                                       uint32_t n_valid)
+{
+    for (uint32_t m0 = 0; m0 < M; m0 += kSweepBatch) {
+        f32x4 gv[kSweepBatch], cv[kSweepBatch];
+#pragma unroll
+        for (int i = 0; i < kSweepBatch; ++i) {
+            if (m0 + i < M) {
+                const size_t off = static_cast<size_t>(m0 + i) * ld + e;
+                gv[i] = load4(g + off, vec, n_valid);
+                cv[i] = load4(c + off, vec, n_valid);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kSweepBatch; ++i) {
+            if (m0 + i < M) {
+                const size_t off = static_cast<size_t>(m0 + i) * ld + e;
+                store4<MARSIT_STREAMING_STORES>(c + off, (gv[i] + cv[i]) - upd, vec, n_valid);
+            }
+        }
+    }
+}
+
+// Sign word of element j of worker `worker`: from the staging area, or straight from memory.
+template <bool STAGED>
+__device__ __forceinline__ uint32_t picked_sign(const f32x4 *stage, const float *__restrict__ g,
+                                                const float *c, uint32_t worker, uint64_t ld,
+                                                uint64_t e, int j)
+{
+    if (STAGED) {
+        const f32x4 sv = stage[static_cast<size_t>(worker) * kSyncBlock + threadIdx.x];
+        const float v = (j == 0) ? sv.x : (j == 1) ? sv.y : (j == 2) ? sv.z : sv.w;
+        return f32_bits(v) & 0x80000000u;
+    }
+    const size_t at = static_cast<size_t>(worker) * ld + e + static_cast<uint32_t>(j);
+    return f32_bits(g[at] + c[at]) & 0x80000000u;
+}
+
 // -------------------------------------------------------------------------------------------------
 // Fused pass, any schedule (X, Y at run time), any alignment, ragged tails.  Covers columns
-// col_begin .. ceil(d/4)-1 (col_begin is a multiple of 16).  The chains are evaluated on the draws
-// alone (which worker does each bit end up taking), that worker's sign is fetched, and one sweep
-// over the workers writes the compensation: 12*M + 12 bytes per element.
+// col_begin .. ceil(d/4)-1 (col_begin is a multiple of 16).  s of every worker is staged in LDS,
+// the chains are evaluated on the draws alone (which worker does each bit end up taking), that
+// worker's sign is looked up in LDS, and the compensation is written from LDS: 12*M + 4 bytes per
+// element, like the compiled schedules.
 // -------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kBlock)
+template <bool STAGED>
+__global__ void __launch_bounds__(kSyncBlock)
 sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
                          float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
                          uint64_t ld, uint64_t col_begin, uint32_t scale_bits, uint32_t key0,
@@ -194,7 +281,7 @@ sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
 {
     const uint32_t M = X * Y;
     const uint64_t n_cols = (d + 3) >> 2;
-    const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
     const uint32_t w = static_cast<uint32_t>(col >> 4);
     const uint32_t q = static_cast<uint32_t>(col) & 15u;
     uint32_t nib = 0;
@@ -211,8 +298,13 @@ sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
         const uint32_t a = f / Y;
         const uint32_t b = f % Y;
 
+        // line 1: every worker's s into LDS
+        f32x4 *stage = reinterpret_cast<f32x4 *>(marsit_dynamic_lds);
+        if (STAGED)
+            stage_sums(g, c, stage, M, ld, e, vec, n_valid);
+
         // The draws do not depend on the data, and only the last successful draw of a chain
-        // matters: find the picked worker of every bit first, then fetch that one sign.
+        // matters: find the picked worker of every bit, then look its sign up.
         // Column chain (shared by the lane's four bits): which row result survives.
         uint32_t pick_col[4] = {0, 0, 0, 0};
         for (uint32_t ky = 1; ky < Y; ++ky) {
@@ -257,20 +349,17 @@ sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
             if (static_cast<uint32_t>(j) < n_valid) {
                 uint32_t x = a + pick_row[j];
                 x = (x >= X) ? x - X : x;
-                const size_t at = static_cast<size_t>(row_of[j] * X + x) * ld + e + j;
-                const float sv = g[at] + c[at];                       // line 1 for the picked worker
-                const uint32_t sign = f32_bits(sv) & 0x80000000u;
+                const uint32_t sign = picked_sign<STAGED>(stage, g, c, row_of[j] * X + x, ld, e, j);
                 upd[j] = __uint_as_float(scale_bits ^ sign);          // line 9
                 nib |= (sign == 0u) ? (1u << j) : 0u;
             }
         }
         store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
 
-        for (uint32_t m = 0; m < M; ++m) {
-            const size_t off = static_cast<size_t>(m) * ld + e;
-            const f32x4 sv = load4(g + off, vec, n_valid) + load4(c + off, vec, n_valid);
-            store4<MARSIT_STREAMING_STORES>(c + off, sv - upd, vec, n_valid);
-        }
+        if (STAGED)
+            compensate_from_stage(c, stage, upd, M, ld, e, vec, n_valid);
+        else
+            compensate_from_memory(g, c, upd, M, ld, e, vec, n_valid);
     }
 
     const uint32_t half = gather_half_word(nib, q);
@@ -368,16 +457,17 @@ tree_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
 
 // Any M, any alignment, ragged tails.  Only the merges on the way from the root to the chosen
 // leaf decide a bit (all draws are independent), so every bit walks down the tree with at most
-// ceil(log2 M) draws, fetches the sign of the one worker it ends at, and a second sweep writes
-// the compensation.
-__global__ void __launch_bounds__(kBlock)
+// ceil(log2 M) draws and looks up the sign of the one worker it ends at; s of every worker is
+// staged in LDS as in the generic ring kernel.
+template <bool STAGED>
+__global__ void __launch_bounds__(kSyncBlock)
 tree_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
                          float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
                          uint64_t ld, uint64_t col_begin, uint32_t scale_bits, uint32_t key0,
                          uint32_t key1, uint32_t M, uint32_t top_level, bool aligned)
 {
     const uint64_t n_cols = (d + 3) >> 2;
-    const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
     const uint32_t w = static_cast<uint32_t>(col >> 4);
     const uint32_t q = static_cast<uint32_t>(col) & 15u;
     uint32_t nib = 0;
@@ -387,6 +477,10 @@ tree_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
         const bool full = e + 4 <= d;
         const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
         const bool vec = full && aligned;
+
+        f32x4 *stage = reinterpret_cast<f32x4 *>(marsit_dynamic_lds);
+        if (STAGED)
+            stage_sums(g, c, stage, M, ld, e, vec, n_valid);
 
         f32x4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
         for (uint32_t j = 0; j < n_valid; ++j) {
@@ -403,19 +497,16 @@ tree_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
                 const uint32_t uj = (j == 0) ? u[0] : (j == 1) ? u[1] : (j == 2) ? u[2] : u[3];
                 k = (uj < thr) ? k : src;
             }
-            const size_t at = static_cast<size_t>(k) * ld + e + j;
-            const float sv = g[at] + c[at];
-            const uint32_t sign = f32_bits(sv) & 0x80000000u;
+            const uint32_t sign = picked_sign<STAGED>(stage, g, c, k, ld, e, static_cast<int>(j));
             const float uval = __uint_as_float(scale_bits ^ sign);
             if (j == 0) upd.x = uval; else if (j == 1) upd.y = uval; else if (j == 2) upd.z = uval; else upd.w = uval;
             nib |= (sign == 0u) ? (1u << j) : 0u;
         }
         store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
-        for (uint32_t m = 0; m < M; ++m) {
-            const size_t off = static_cast<size_t>(m) * ld + e;
-            const f32x4 sv = load4(g + off, vec, n_valid) + load4(c + off, vec, n_valid);
-            store4<MARSIT_STREAMING_STORES>(c + off, sv - upd, vec, n_valid);
-        }
+        if (STAGED)
+            compensate_from_stage(c, stage, upd, M, ld, e, vec, n_valid);
+        else
+            compensate_from_memory(g, c, upd, M, ld, e, vec, n_valid);
     }
 
     const uint32_t half = gather_half_word(nib, q);
@@ -855,6 +946,18 @@ inline uint32_t throttle_lds_bytes(uint32_t M)
     return ((lds_per_cu / waves) * 31u / 32u) & ~511u;
 }
 
+// Dynamic LDS of the generic kernels: the [M][64] staging area of 128-bit entries (M KB per
+// wavefront).  Above 40 workers it would leave fewer than four wavefronts per CU, and reading g
+// and c twice is faster (measured at M = 64: 62 % against 54 % of HBM peak).
+constexpr uint32_t kMaxStagedWorkers = 40;
+inline uint32_t generic_lds_bytes(uint32_t M)
+{
+    // never less than 20 KB: at most 8 wavefronts per CU (measured best for M = 9, 10: 72 % of peak
+    // against 65 % with 17 wavefronts)
+    const uint32_t need = M * static_cast<uint32_t>(kSyncBlock) * 16u;
+    return need > 20u * 1024u ? need : 20u * 1024u;
+}
+
 template <int X, int Y>
 void launch_sync_step(const float *g, float *c, float *update, uint32_t *bits32, uint64_t n_cols,
                       uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1,
@@ -1097,9 +1200,16 @@ int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *
         thresholds.thr[1] = 0xFFFFFFFFu;
         for (uint32_t m = 2; m <= MARSIT_MAX_WORKERS; ++m)
             thresholds.thr[m] = keep_threshold(m);
-        hipLaunchKernelGGL(sync_step_generic_kernel, dim3(blocks_for(n_cols - generic_col_begin)),
-                           dim3(kBlock), 0, s, g, c, update_out, bits32, d, ld, generic_col_begin,
-                           scale_bits, key0, key1, X, Y, aligned, parts, thresholds);
+        const uint32_t blocks =
+            static_cast<uint32_t>((n_cols - generic_col_begin + kSyncBlock - 1) / kSyncBlock);
+        if (M <= kMaxStagedWorkers)
+            hipLaunchKernelGGL(sync_step_generic_kernel<true>, dim3(blocks), dim3(kSyncBlock),
+                               generic_lds_bytes(M), s, g, c, update_out, bits32, d, ld,
+                               generic_col_begin, scale_bits, key0, key1, X, Y, aligned, parts, thresholds);
+        else
+            hipLaunchKernelGGL(sync_step_generic_kernel<false>, dim3(blocks), dim3(kSyncBlock), 0, s, g, c,
+                               update_out, bits32, d, ld, generic_col_begin, scale_bits, key0, key1, X, Y,
+                               aligned, parts, thresholds);
         return finish_launch();
     }
     return MARSIT_OK;
@@ -1140,9 +1250,16 @@ int marsit_tree_step_sim(const float *g, float *c, float *update_out, uint64_t *
         uint32_t top_level = 0;
         while ((1u << top_level) < M)
             ++top_level;
-        hipLaunchKernelGGL(tree_step_generic_kernel, dim3(blocks_for(n_cols - generic_col_begin)),
-                           dim3(kBlock), 0, s, g, c, update_out, bits32, d, ld, generic_col_begin,
-                           scale_bits, key0, key1, M, top_level, aligned);
+        const uint32_t blocks =
+            static_cast<uint32_t>((n_cols - generic_col_begin + kSyncBlock - 1) / kSyncBlock);
+        if (M <= kMaxStagedWorkers)
+            hipLaunchKernelGGL(tree_step_generic_kernel<true>, dim3(blocks), dim3(kSyncBlock),
+                               generic_lds_bytes(M), s, g, c, update_out, bits32, d, ld,
+                               generic_col_begin, scale_bits, key0, key1, M, top_level, aligned);
+        else
+            hipLaunchKernelGGL(tree_step_generic_kernel<false>, dim3(blocks), dim3(kSyncBlock), 0, s, g, c,
+                               update_out, bits32, d, ld, generic_col_begin, scale_bits, key0, key1, M,
+                               top_level, aligned);
         return finish_launch();
     }
     return MARSIT_OK;
