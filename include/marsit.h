@@ -59,7 +59,7 @@ const char *marsit_status_string(int status);
 void marsit_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
 
 /*
- * Host-side.  "Split into M parts" (Algorithm 1, line 2) on packed words, as the schedules use it.
+ * Host-side.  "Split into M parts" (the split step of Algorithm 1) on packed words, as the schedules use it.
  * Writes M + 1 non-decreasing word indices to bounds_out (HOST memory); part f covers words
  * [bounds_out[f], bounds_out[f+1]).
  *   ring (grid_x == 0 or grid_x == M): part i = [floor(i*W/M), floor((i+1)*W/M)); its chain
@@ -71,14 +71,14 @@ void marsit_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t
 int marsit_split_bounds(uint64_t n_words, uint32_t M, uint32_t grid_x, uint64_t *bounds_out);
 
 /*
- * Algorithm 1, line 1 and line 5 for one worker:  bit e of bits_out = sgn(g[e] + c[e]).
+ * Algorithm 1, compensated gradient and sign step for one worker:  bit e of bits_out = sgn(g[e] + c[e]).
  *   g, c     [d] fp32; c may be NULL (taken as 0).
  *   bits_out [ceil(d/64)] 64-bit words.
  */
 int marsit_compress(const float *g, const float *c, uint64_t *bits_out, uint64_t d, void *stream);
 
 /*
- * Algorithm 1, line 6 for one hop and a run of packed words:
+ * Algorithm 1, merge step (the operator of Section 4.1.1) for one hop and a run of packed words:
  *     out = (recv AND local) OR ((recv XOR local) AND v),  v drawn by Eq. 2 of Section 4.1.1
  * which is the same as: take the local bit where the Bernoulli(1/fold) draw succeeds, else keep
  * the received bit.
@@ -95,7 +95,7 @@ int marsit_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_t *out,
                      uint64_t seed, void *stream);
 
 /*
- * Algorithm 1, lines 9-10 for one worker, from the final bitmap every worker holds after the
+ * Algorithm 1, global update and compensation update for one worker, from the final bitmap every worker holds after the
  * gather period:   update_out[e] = bit ? +scale : -scale;   c_out[e] = (g[e] + c[e]) - update_out[e].
  *   bits       [ceil(d/64)].
  *   g, c       [d]; c may be NULL (taken as 0).
@@ -107,11 +107,11 @@ int marsit_decode_compensate(const uint64_t *bits, const float *g, const float *
                              float *update_out, float *c_out, uint64_t d, void *stream);
 
 /*
- * The whole one-bit pass (Algorithm 1, lines 1-2 and 4-10) for M workers simulated inside one
+ * The whole one-bit pass (Algorithm 1, the branch mod(t,K) != 0) for M workers simulated inside one
  * device, fused in one kernel: compensate, sign, the M-1 merges of every part's chain, decode,
  * global compensation.  Results are bit-identical to chaining marsit_compress, marsit_hop_merge
  * and marsit_decode_compensate along the same schedule.
- *   g          [M][ld] gradients, already multiplied by the local step size (Algorithm 2, line 5).
+ *   g          [M][ld] gradients, already multiplied by the local step size (as Algorithm 2 passes them).
  *   c          [M][ld] compensation; read as c_t, overwritten with c_{t+1}.  Columns >= d untouched.
  *   update_out [d] global update g_t (the same for every worker).
  *   bits_out   [ceil(d/64)] final merged bitmap, or NULL.
@@ -173,8 +173,8 @@ uint64_t marsit_chain_workspace_words(uint32_t M, uint64_t d, uint32_t grid_x);
  * The ring of Section 4 / Fig. 3 with one HIP stream per worker: every hop of every part is its own
  * launch and waits only for what a real ring waits for -- the segment from the previous worker
  * and the release of its own send buffer.  A worker computes the signs of a part right before it
- * folds them in, so that computation overlaps the wait for the incoming segment (Algorithm 1,
- * line 5).  The gather period is simulated: the last holder of a part writes it to bits_out, which
+ * folds them in, so that computation overlaps the wait for the incoming segment (Algorithm 1:
+ * receive in parallel with the sign step).  The gather period is simulated: the last holder of a part writes it to bits_out, which
  * every worker reads.  Ring schedule only.  Results are bit-identical to marsit_ring_step_sim.
  *
  * marsit_pipeline_create makes the M streams (default priority) and the events; this is the only
@@ -196,7 +196,7 @@ int marsit_pipeline_ring_step(marsit_pipeline *p, const float *g, float *c, floa
 int marsit_pipeline_last_hip_error(void);
 
 /*
- * Algorithm 1, lines 11-13 (the full-precision round) for M simulated workers:
+ * Algorithm 1, the branch mod(t,K) == 0 (the full-precision round) for M simulated workers:
  *     update_out[e] = (1/M) * sum_m (g[m][e] + c[m][e]);   c[m][e] = 0.
  * The sum runs over m = 0..M-1 in fp32, then one division by M.
  */
@@ -205,7 +205,7 @@ int marsit_full_sync(const float *g, float *c, float *update_out, uint32_t M, ui
 
 /*
  * Algorithm 1 as a whole: the one-bit pass when t mod K != 0, the full-precision round when
- * t mod K == 0 (line 3).  K == 0 is MARSIT_EINVAL; pass K > t_max for "never".  bits_out is left
+ * t mod K == 0.  K == 0 is MARSIT_EINVAL; pass K > t_max for "never".  bits_out is left
  * untouched by a full-precision round.  Other arguments as in marsit_ring_step_sim.
  */
 int marsit_step(uint64_t t, uint64_t K, const float *g, float *c, float *update_out,
@@ -217,7 +217,7 @@ int marsit_step(uint64_t t, uint64_t K, const float *g, float *c, float *update_
  * elements whose sign equals the sign of the non-compressed aggregate.
  *
  * marsit_aggregate_sign: bit e of bits_out = sgn(sum_m (g[m][e] + c[m][e])); every term is the fp32
- *   sum of Algorithm 1 line 1, the sum over m runs in double, in worker order.
+ *   compensated gradient of Algorithm 1, the sum over m runs in double, in worker order.
  * marsit_majority_vote: bit e = 1 where at least as many workers have a + sign as a - sign
  *   (signSGD with majority vote; a tie counts as +).
  * marsit_count_matching: *count_out (DEVICE memory, one 64-bit word, overwritten) = number of
@@ -259,7 +259,7 @@ int marsit_cascade_ring_step_sim(const float *g, const float *c, float *update_o
                                  float *norms_out, void *workspace, uint32_t M, uint64_t d, uint64_t ld,
                                  uint64_t seed, void *stream);
 
-/* Algorithm 2, line 6:  x[e] <- x[e] - update[e]. */
+/* Algorithm 2, the model update:  x[e] <- x[e] - update[e]. */
 int marsit_apply_update(float *x, const float *update, uint64_t d, void *stream);
 
 #ifdef __cplusplus

@@ -8,12 +8,12 @@
  * product never routes through it.
  *
  * What it follows
- *   - Algorithm 1, lines 1-2 and 4-10 (the branch mod(t,K) != 0): compensated gradient,
+ *   - Algorithm 1, the branch mod(t,K) != 0, step by step in its order: compensated gradient,
  *     split into M parts, per-part chain of "sign, merge, send", decode, global compensation.
  *   - Eq. 2 of Section 4.1.1: the transient Bernoulli vector v.
  *   - The operator  v_i (.) v_i* = (v_i AND v_i*) OR ((v_i XOR v_i*) AND v)  of Section 4.1.1.
- *   - Algorithm 1, lines 11-13 (the branch mod(t,K) == 0): full-precision mean, c <- 0.
- *   - Algorithm 2, line 6: x <- x - g_t.
+ *   - Algorithm 1, the branch mod(t,K) == 0: full-precision mean, c <- 0.
+ *   - Algorithm 2, the model update: x <- x - g_t.
  *
  * Readings taken where the paper is silent (each is listed in the design notes of the build):
  *   - "m" in Eq. 2 is the fold count: how many workers' signs the outgoing vector will stand
@@ -31,7 +31,7 @@
  *     columns inside every row, parts = X row-parts of the W words), then columns (ring over
  *     the Y row results, every row-part split again in Y sub-parts).
  *   - Arithmetic type: the gradients and the compensation are fp32 vectors (Section 1 speaks
- *     of 32-bit single precision), so line 1 and line 10 are one fp32 round-to-nearest-even
+ *     of 32-bit single precision), so the compensated sum and the compensation update are one fp32 round-to-nearest-even
  *     operation each.  Build with -ffp-contract=off and without fast-math.
  *
  * Parity status: the building blocks are pinned by tests (exact enumeration of the
@@ -96,7 +96,7 @@ uint32_t oracle_stream_u32(uint64_t seed, uint32_t hop_id, uint64_t word_index, 
 }
 
 /* ------------------------------------------------------------------------------------------
- * Algorithm 1, line 1:  g <- g + c   (elementwise, fp32).
+ * Algorithm 1, compensated gradient:  g <- g + c   (elementwise, fp32).
  * ---------------------------------------------------------------------------------------- */
 void oracle_add_compensation(const float *g, const float *c, float *s, uint64_t d)
 {
@@ -115,7 +115,7 @@ static unsigned sign_bit_plus(float x)
 }
 
 /* ------------------------------------------------------------------------------------------
- * Algorithm 1, line 5:  v* <- sgn(g_part), stored one bit per element.
+ * Algorithm 1, sign step:  v* <- sgn(g_part), stored one bit per element.
  * bits has ceil(d/64) words; positions >= d stay 0.
  * ---------------------------------------------------------------------------------------- */
 void oracle_sign_pack(const float *s, uint64_t *bits, uint64_t d)
@@ -182,7 +182,7 @@ uint64_t oracle_merge_word(uint64_t recv, uint64_t local, uint32_t fold, uint32_
 }
 
 /* ------------------------------------------------------------------------------------------
- * Algorithm 1, line 6 for a run of words: out = recv (.) local.
+ * Algorithm 1, merge step, for a run of words: out = recv (.) local.
  * word_begin is the global index of the first word (it keys the random stream).
  * Returns 0, or -1 on a bad argument.
  * ---------------------------------------------------------------------------------------- */
@@ -198,7 +198,7 @@ int oracle_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_t *out,
 }
 
 /* ------------------------------------------------------------------------------------------
- * Algorithm 1, line 9:  g_t <- eta_s * (union of the final sign parts): +scale or -scale.
+ * Algorithm 1, aggregation of the global update:  g_t <- eta_s * (union of the final sign parts): +scale or -scale.
  * ---------------------------------------------------------------------------------------- */
 void oracle_decode(const uint64_t *bits, float scale, float *update, uint64_t d)
 {
@@ -208,7 +208,7 @@ void oracle_decode(const uint64_t *bits, float scale, float *update, uint64_t d)
     }
 }
 
-/* Algorithm 1, line 10:  c_{t+1} <- g (the compensated one of line 1) - g_t. */
+/* Algorithm 1, compensation update:  c_{t+1} <- g (the compensated gradient) - g_t. */
 void oracle_compensate(const float *s, const float *update, float *c_next, uint64_t d)
 {
     for (uint64_t e = 0; e < d; ++e) {
@@ -216,7 +216,7 @@ void oracle_compensate(const float *s, const float *update, float *c_next, uint6
     }
 }
 
-/* Algorithm 1, line 2: bounds[i] = floor(i * n / parts) + begin, i = 0..parts. */
+/* Algorithm 1, split step: bounds[i] = floor(i * n / parts) + begin, i = 0..parts. */
 void oracle_split_bounds(uint64_t begin, uint64_t n, uint32_t parts, uint64_t *bounds)
 {
     for (uint32_t i = 0; i <= parts; ++i)
@@ -238,9 +238,9 @@ uint32_t oracle_hop_id(uint32_t phase, uint32_t row, uint32_t hop)
 }
 
 /* ------------------------------------------------------------------------------------------
- * The whole one-bit pass for M simulated workers (Algorithm 1, lines 1-2, 4-10).
+ * The whole one-bit pass for M simulated workers (Algorithm 1, the branch mod(t,K) != 0).
  *
- *   g          [M][ld]  gradients (already scaled by the local step, Algorithm 2 line 5)
+ *   g          [M][ld]  gradients (already scaled by the local step, as Algorithm 2 passes them)
  *   c          [M][ld]  compensation, read as c_t and overwritten with c_{t+1}
  *   update     [d]      g_t
  *   bits_final [W]      the final merged bitmap every worker ends up with (may be NULL)
@@ -274,17 +274,17 @@ int oracle_sync_step(const float *g, float *c, float *update, uint64_t *bits_fin
         return -2;
     }
 
-    /* line 1 and line 5 for every worker */
+    /* compensated gradient and its signs, for every worker */
     for (uint32_t m = 0; m < M; ++m) {
         oracle_add_compensation(g + (size_t)m * ld, c + (size_t)m * ld, s + (size_t)m * d, d);
         oracle_sign_pack(s + (size_t)m * d, L + (size_t)m * W, d);
     }
 
-    /* line 2: the W packed words are split in X row-parts */
+    /* split step: the W packed words are split in X row-parts */
     uint64_t row_bounds[ORACLE_MAX_WORKERS + 1];
     oracle_split_bounds(0, W, X, row_bounds);
 
-    /* lines 4-8, one packed word at a time */
+    /* the loop over the parts (sign, merge, send), one packed word at a time */
     #pragma omp parallel for schedule(static) num_threads(threads) if (threads > 1)
     for (uint64_t w = 0; w < W; ++w) {
         uint32_t a = part_of(w, row_bounds, X);
@@ -313,7 +313,7 @@ int oracle_sync_step(const float *g, float *c, float *update, uint64_t *bits_fin
         B[w] = r;
     }
 
-    /* line 9 and line 10 */
+    /* global update, then compensation update */
     oracle_decode(B, scale, update, d);
     for (uint32_t m = 0; m < M; ++m)
         oracle_compensate(s + (size_t)m * d, update, c + (size_t)m * ld, d);
@@ -327,7 +327,7 @@ int oracle_sync_step(const float *g, float *c, float *update, uint64_t *bits_fin
 }
 
 /* ------------------------------------------------------------------------------------------
- * Algorithm 1, lines 11-13 (full-precision round):  g_t <- (1/M) sum_m (g^(m) + c^(m)),  c <- 0.
+ * Algorithm 1, the branch mod(t,K) == 0 (full-precision round):  g_t <- (1/M) sum_m (g^(m) + c^(m)),  c <- 0.
  * The sum is taken in double and rounded once to fp32.
  * ---------------------------------------------------------------------------------------- */
 int oracle_full_sync(const float *g, float *c, float *update, uint32_t M, uint64_t d, uint64_t ld)
@@ -337,7 +337,7 @@ int oracle_full_sync(const float *g, float *c, float *update, uint32_t M, uint64
     for (uint64_t e = 0; e < d; ++e) {
         double acc = 0.0;
         for (uint32_t m = 0; m < M; ++m) {
-            float sm = g[(size_t)m * ld + e] + c[(size_t)m * ld + e];   /* line 1, fp32 */
+            float sm = g[(size_t)m * ld + e] + c[(size_t)m * ld + e];   /* compensated gradient, fp32 */
             acc += (double)sm;
         }
         update[e] = (float)(acc / (double)M);
@@ -348,7 +348,7 @@ int oracle_full_sync(const float *g, float *c, float *update, uint32_t M, uint64
     return 0;
 }
 
-/* Algorithm 2, line 6:  x <- x - g_t. */
+/* Algorithm 2, model update:  x <- x - g_t. */
 void oracle_apply_update(float *x, const float *update, uint64_t d)
 {
     for (uint64_t e = 0; e < d; ++e) {
@@ -370,7 +370,7 @@ void oracle_aggregate_sign(const float *g, const float *c, uint64_t *bits, uint3
     for (uint64_t e = 0; e < d; ++e) {
         double acc = 0.0;
         for (uint32_t m = 0; m < M; ++m) {
-            float sm = g[(size_t)m * ld + e] + c[(size_t)m * ld + e];     /* Algorithm 1 line 1, fp32 */
+            float sm = g[(size_t)m * ld + e] + c[(size_t)m * ld + e];     /* compensated gradient of Algorithm 1, fp32 */
             acc += (double)sm;
         }
         uint64_t raw;
@@ -553,7 +553,7 @@ uint32_t oracle_cascade_hop_id(uint32_t hop)
  * split: the first holder sends Q(s^(i)); at hop h worker (i+h) mod M receives (norm, signs),
  * recovers w = norm * signs, aggregates t = w + s^(local), compresses Q(t) and sends it on.
  * After M-1 hops the part's result is (1/M) * norm * signs.
- *   g, c        [M][ld]; s = g + c as in Algorithm 1 line 1 (c is NOT updated: the strawman has no
+ *   g, c        [M][ld]; s = g + c as in Algorithm 1 (c is NOT updated: the strawman has no
  *               compensation step)
  *   bits_final  [W] final signs;  norms_final [M] final norm of every part
  *   update      [d]  (1/M) * norm_part * (+-1)

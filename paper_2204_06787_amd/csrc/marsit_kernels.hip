@@ -1,6 +1,6 @@
 // HIP kernels (gfx950) and the C ABI of the Marsit one-bit synchronisation pass.
 //
-// The operation is the one-bit branch of Algorithm 1 of the paper (lines 1-2, 4-10) with the
+// The operation is the one-bit branch of Algorithm 1 of the paper (mod(t,K) != 0) with the
 // transient vector of Eq. 2 and the merge operator of Section 4.1.1.  The merge
 //     (r AND l) OR ((r XOR l) AND v),  v = XNOR(l, t),  t ~ Bernoulli(1/m)
 // reduces, bit by bit, to "t ? l : r" (check the eight cases), so a chain of merges is carried
@@ -73,7 +73,7 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
     if (col < n_cols) {
         const uint64_t e = col << 2;
 
-        // Algorithm 1, line 2: which part does this packed word belong to
+        // Algorithm 1, split step: which part does this packed word belong to
         uint32_t f = 0;
 #pragma unroll
         for (int k = 1; k < M; ++k)
@@ -85,7 +85,7 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
         // issued one row ahead of the row being folded, and the row's Philox draws run while they
         // are in flight; the scheduling barriers keep that order.
         size_t off[Y][X];
-        f32x4 s[Y][X];              // line 1: s = g + c, kept for line 10
+        f32x4 s[Y][X];              // compensated gradient s = g + c, kept for the compensation update
         f32x4 gv[2][X], cv[2][X];   // the row in flight and the row being folded
         uint32_t row_res[Y][4];     // raw fp32 word whose sign is the row's merged sign, per bit
         auto fetch_row = [&](int ky) {
@@ -130,7 +130,7 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
             }
             __builtin_amdgcn_sched_barrier(0);
 
-            // line 1, then lines 4-8 for this row: the chain as a selection on the raw fp32 words
+            // compensated gradient, then this row's chain of merges as a selection on the raw fp32 words
 #pragma unroll
             for (int kx = 0; kx < X; ++kx)
                 s[ky][kx] = gv[ky & 1][kx] + cv[ky & 1][kx];
@@ -155,7 +155,7 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
             fin[j] = r;
         }
 
-        // line 9: update = +scale where the final sign bit is clear, -scale where it is set
+        // global update: +scale where the final sign bit is clear, -scale where it is set
         f32x4 upd;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -165,7 +165,7 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
         }
         store4_stream(update + e, upd);
 
-        // line 10: c <- s - update for every worker
+        // compensation update: c <- s - update for every worker
 #pragma unroll
         for (int ky = 0; ky < Y; ++ky)
 #pragma unroll
@@ -187,7 +187,7 @@ extern __shared__ __align__(16) unsigned char marsit_dynamic_lds[];
 
 constexpr int kSweepBatch = 8;   // workers whose loads are issued back to back
 
-// Algorithm 1, line 1 for a run-time number of workers: s -> LDS.
+// Compensated gradient of Algorithm 1 for a run-time number of workers: s -> LDS.
 __device__ __forceinline__ void stage_sums(const float *__restrict__ g, const float *c, f32x4 *stage,
                                            uint32_t M, uint64_t ld, uint64_t e, bool vec,
                                            uint32_t n_valid)
@@ -210,7 +210,7 @@ __device__ __forceinline__ void stage_sums(const float *__restrict__ g, const fl
     }
 }
 
-// Algorithm 1, line 10 for a run-time number of workers: c <- s - update, s from LDS.
+// Compensation update of Algorithm 1 for a run-time number of workers: c <- s - update, s from LDS.
 __device__ __forceinline__ void compensate_from_stage(float *c, const f32x4 *stage, f32x4 upd,
                                                       uint32_t M, uint64_t ld, uint64_t e, bool vec,
                                                       uint32_t n_valid)
@@ -298,7 +298,7 @@ sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
         const uint32_t a = f / Y;
         const uint32_t b = f % Y;
 
-        // line 1: every worker's s into LDS
+        // compensated gradient of every worker into LDS
         f32x4 *stage = reinterpret_cast<f32x4 *>(marsit_dynamic_lds);
         if (STAGED)
             stage_sums(g, c, stage, M, ld, e, vec, n_valid);
@@ -350,7 +350,7 @@ sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
                 uint32_t x = a + pick_row[j];
                 x = (x >= X) ? x - X : x;
                 const uint32_t sign = picked_sign<STAGED>(stage, g, c, row_of[j] * X + x, ld, e, j);
-                upd[j] = __uint_as_float(scale_bits ^ sign);          // line 9
+                upd[j] = __uint_as_float(scale_bits ^ sign);          // global update
                 nib |= (sign == 0u) ? (1u << j) : 0u;
             }
         }
@@ -613,7 +613,7 @@ decode_compensate_kernel(const uint32_t *__restrict__ bits32, const float *__res
 }
 
 // -------------------------------------------------------------------------------------------------
-// Full-precision round (Algorithm 1, lines 11-13) and the model update (Algorithm 2, line 6).
+// Full-precision round (Algorithm 1, branch mod(t,K) == 0) and the model update of Algorithm 2.
 // -------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kBlock)
 full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
@@ -783,7 +783,7 @@ __device__ __forceinline__ f32x4 cascade_value(const uint32_t *recv32, const flo
                                                bool vec, uint32_t n_valid)
 {
     const uint64_t e = col << 2;
-    f32x4 t = load4(g + e, vec, n_valid) + load4(c + e, vec, n_valid);     // Algorithm 1, line 1
+    f32x4 t = load4(g + e, vec, n_valid) + load4(c + e, vec, n_valid);     // compensated gradient
     if (recv32 != nullptr) {
         const float norm = *recv_norm;
         const uint32_t nib = (recv32[col >> 3] >> ((static_cast<uint32_t>(col) & 7u) * 4u)) & 0xFu;
@@ -1298,7 +1298,7 @@ int marsit_chain_step_sim(const float *g, float *c, float *update_out, uint64_t 
     const uint64_t W = (d + 63) / 64;
     uint64_t fine[MARSIT_MAX_WORKERS + 1];
     split_bounds_host(W, M, grid_x, fine);
-    uint64_t *maps = workspace;                    // [M][W]  every worker's own signs (line 5)
+    uint64_t *maps = workspace;                    // [M][W]  every worker's own signs
     uint64_t *rows = workspace + static_cast<size_t>(M) * W;   // [Y][W]  row results (torus)
     int rc;
 

@@ -8,7 +8,7 @@
 // Schedule (Section 4 of the paper, Fig. 3's reduce period): part i starts at worker i; at hop step
 // h = 1..M-1 worker w folds its own signs of part (w - h) mod M into what worker w-1 sent.  A worker
 // computes the signs of a part right before it needs them, so sign computation overlaps the wait
-// for the incoming segment (Algorithm 1, line 5).  The gather period is a no-op here: the last
+// for the incoming segment (Algorithm 1: receive in parallel with the sign step).  The gather period is a no-op here: the last
 // holder writes the final segment where every worker reads it.
 
 #include <hip/hip_runtime.h>

@@ -126,7 +126,7 @@ def make_gradients(wl: Workload, step: int, seed: int, device="cpu", d: int | No
 
 def zero_compensation(wl: Workload, device="cpu", d: int | None = None,
                       ld: int | None = None) -> torch.Tensor:
-    """c_0 = 0 (Algorithm 2, line 1)."""
+    """c_0 = 0 (the initialisation of Algorithm 2)."""
     d = wl.d if d is None else int(d)
     ld = d if ld is None else int(ld)
     return torch.zeros((wl.M, ld), dtype=torch.float32, device=torch.device(device))

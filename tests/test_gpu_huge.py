@@ -24,7 +24,7 @@ def test_more_than_2_to_32_elements_per_worker():
     for m in range(M):
         g[m].normal_(generator=gen)
         c[m].normal_(generator=gen).mul_(0.25)
-    s = g + c                                           # line 1, fp32, by a different implementation
+    s = g + c                                           # compensated gradient, fp32, by a different implementation
     c_in = None
     update = torch.empty(d, dtype=torch.float32, device="cuda")
     bits = marsit.new_bitmap(d)
@@ -33,7 +33,7 @@ def test_more_than_2_to_32_elements_per_worker():
 
     # properties at full size
     assert bool((update.abs() == np.float32(scale)).all())                      # +-scale everywhere
-    assert bool((c[0] == s[0] - update).all()) and bool((c[1] == s[1] - update).all())   # line 10
+    assert bool((c[0] == s[0] - update).all()) and bool((c[1] == s[1] - update).all())   # compensation update
     plus = update > 0
     pos0, pos1 = s[0] >= 0, s[1] >= 0
     agree = pos0 == pos1

@@ -399,7 +399,7 @@ def test_compensation_invariants_single_step():
     c = c0.copy()
     update, _, _ = orc.sync_step(g, c, 1e-3, 4242)
     s = g + c0
-    # line 10: c_next = s - update, one fp32 rounding
+    # compensation update: c_next = s - update, one fp32 rounding
     assert np.array_equal(c.view(np.uint32), (s - update[None, :]).view(np.uint32))
     # every worker subtracts the same global update
     assert np.allclose((c[0] - c[1]).astype(np.float64), (s[0].astype(np.float64) - s[1]), atol=2e-7 * 8)
@@ -475,7 +475,7 @@ def test_hop_merge_composes_to_sync_step():
 
 
 # ---------------------------------------------------------------------------------------------
-# Full-precision round and model update (Algorithm 1 lines 11-13, Algorithm 2 line 6)
+# Full-precision round (Algorithm 1, branch mod(t,K) == 0) and model update (Algorithm 2)
 # ---------------------------------------------------------------------------------------------
 
 def test_full_sync_is_the_mean_and_resets_compensation():
