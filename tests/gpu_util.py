@@ -6,7 +6,7 @@ import torch
 from oracle import marsit_oracle as orc
 from paper_2204_06787_amd import marsit
 
-REL_TOL = 1e-6          # bar for decoded updates and compensation vectors (fp32), per the benchmark spec
+REL_TOL = 1e-6          # stated bar for decoded updates and compensation vectors (fp32 relative error)
 
 
 def dev(a: np.ndarray) -> torch.Tensor:
