@@ -95,6 +95,17 @@ int marsit_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_t *out,
                      uint64_t seed, void *stream);
 
 /*
+ * marsit_hop_merge with the seed read from DEVICE memory (one 64-bit word, 8-byte aligned) when
+ * the kernel runs, not when it is enqueued: a HIP graph that a caller captures around such launches
+ * can be replayed with a new seed.  marsit_set_device_seed writes that word with a one-thread kernel on `stream`
+ * (no memcpy, so it may sit next to a graph launch).
+ */
+int marsit_hop_merge_device_seed(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                                 uint64_t word_begin, uint64_t n_words, uint32_t fold, uint32_t hop_id,
+                                 const uint64_t *seed_device, void *stream);
+int marsit_set_device_seed(uint64_t *seed_device, uint64_t seed, void *stream);
+
+/*
  * Algorithm 1, global update and compensation update for one worker, from the final bitmap every worker holds after the
  * gather period:   update_out[e] = bit ? +scale : -scale;   c_out[e] = (g[e] + c[e]) - update_out[e].
  *   bits       [ceil(d/64)].

@@ -555,8 +555,14 @@ compress_kernel(const float *__restrict__ g, const float *__restrict__ c,
 __global__ void __launch_bounds__(kBlock)
 hop_merge_kernel(const uint32_t *recv32, const uint32_t *local32, uint32_t *out32,
                  uint64_t word_begin, uint64_t n_words, uint32_t threshold, bool always_local,
-                 uint32_t hop_id, uint32_t key0, uint32_t key1)
+                 uint32_t hop_id, uint32_t key0, uint32_t key1, const uint64_t *seed_ptr)
 {
+    if (seed_ptr != nullptr) {
+        // seed kept in device memory: lets a captured graph be replayed with a new seed
+        const uint64_t seed = *seed_ptr;
+        key0 = static_cast<uint32_t>(seed);
+        key1 = static_cast<uint32_t>(seed >> 32);
+    }
     const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
     const uint64_t i = col >> 4;
     const uint32_t q = static_cast<uint32_t>(col) & 15u;
@@ -1093,7 +1099,8 @@ int marsit_compress(const float *g, const float *c, uint64_t *bits_out, uint64_t
 
 static int launch_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_t *out,
                             uint64_t word_begin, uint64_t n_words, uint32_t w_recv, uint32_t w_local,
-                            uint32_t hop_id, uint64_t seed, void *stream)
+                            uint32_t hop_id, uint64_t seed, void *stream,
+                            const uint64_t *seed_ptr = nullptr)
 {
     if (recv == nullptr || local == nullptr || out == nullptr || w_local == 0 ||
         w_recv > 0x7FFFFFFFu || w_local > 0x7FFFFFFFu || n_words > kMaxElements / 64)
@@ -1108,7 +1115,32 @@ static int launch_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_
                        static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(recv),
                        reinterpret_cast<const uint32_t *>(local), reinterpret_cast<uint32_t *>(out),
                        word_begin, n_words, threshold, always_local, hop_id,
-                       static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32));
+                       static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), seed_ptr);
+    return finish_launch();
+}
+
+int marsit_hop_merge_device_seed(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                                 uint64_t word_begin, uint64_t n_words, uint32_t fold, uint32_t hop_id,
+                                 const uint64_t *seed_device, void *stream)
+{
+    if (fold == 0 || seed_device == nullptr)
+        return MARSIT_EINVAL;
+    if (!aligned_to(seed_device, 8))
+        return MARSIT_EALIGN;
+    return launch_hop_merge(recv, local, out, word_begin, n_words, fold - 1, 1, hop_id, 0, stream,
+                            seed_device);
+}
+
+__global__ void set_seed_kernel(uint64_t *slot, uint64_t seed) { *slot = seed; }
+
+int marsit_set_device_seed(uint64_t *seed_device, uint64_t seed, void *stream)
+{
+    if (seed_device == nullptr)
+        return MARSIT_EINVAL;
+    if (!aligned_to(seed_device, 8))
+        return MARSIT_EALIGN;
+    hipLaunchKernelGGL(set_seed_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream), seed_device,
+                       seed);
     return finish_launch();
 }
 

@@ -29,6 +29,7 @@ EXPORTS = (
     "marsit_aggregate_sign", "marsit_majority_vote", "marsit_count_matching",
     "marsit_hop_merge_weighted", "marsit_tree_step_sim",
     "marsit_ssdm_cascade_hop", "marsit_cascade_ring_step_sim",
+    "marsit_hop_merge_device_seed", "marsit_set_device_seed",
 )
 
 _lib = None
@@ -85,6 +86,10 @@ def load_library(path: str | None = None):
     lib.marsit_pipeline_workspace_words.restype = u64
     lib.marsit_pipeline_ring_step.argtypes = [vp, vp, vp, vp, vp, vp, u64, u64, f32, u64, vp]
     lib.marsit_pipeline_ring_step.restype = ci
+    lib.marsit_hop_merge_device_seed.argtypes = [vp, vp, vp, u64, u64, u32, u32, vp, vp]
+    lib.marsit_hop_merge_device_seed.restype = ci
+    lib.marsit_set_device_seed.argtypes = [vp, u64, vp]
+    lib.marsit_set_device_seed.restype = ci
     lib.marsit_pipeline_last_hip_error.argtypes = []
     lib.marsit_pipeline_last_hip_error.restype = ci
     lib.marsit_hop_merge_weighted.argtypes = [vp, vp, vp, u64, u64, u32, u32, u32, u64, vp]
@@ -197,6 +202,21 @@ def marsit_hop_merge(recv, local, out, word_begin: int, n_words_: int, fold: int
         _bits_ptr(recv, "recv"), _bits_ptr(local, "local"), _bits_ptr(out, "out"), word_begin,
         n_words_, fold, hop_id, seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
     return out
+
+
+def marsit_hop_merge_device_seed(recv, local, out, word_begin: int, n_words_: int, fold: int, hop_id: int,
+                                 seed_device, stream=None):
+    """``seed_device``: one-element int64 tensor in device memory holding the seed."""
+    _check("marsit_hop_merge_device_seed", load_library().marsit_hop_merge_device_seed(
+        _bits_ptr(recv, "recv"), _bits_ptr(local, "local"), _bits_ptr(out, "out"), word_begin,
+        n_words_, fold, hop_id, _bits_ptr(seed_device, "seed_device"), _stream(stream)))
+    return out
+
+
+def marsit_set_device_seed(seed_device, seed: int, stream=None):
+    _check("marsit_set_device_seed", load_library().marsit_set_device_seed(
+        _bits_ptr(seed_device, "seed_device"), seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
+    return seed_device
 
 
 def marsit_decode_compensate(bits, g, c, scale: float, update_out, c_out, d: int | None = None,

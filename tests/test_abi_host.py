@@ -158,6 +158,10 @@ def test_other_entry_points_argument_validation(lib):
     assert lib.marsit_cascade_ring_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, None, 4, 64, 64, 5, None) == marsit.EINVAL
     assert lib.marsit_cascade_ring_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 4, 0, 64, 5, None) == marsit.OK
 
+    assert lib.marsit_hop_merge_device_seed(FAKE, FAKE, FAKE, 0, 10, 2, 1, None, None) == marsit.EINVAL
+    assert lib.marsit_hop_merge_device_seed(FAKE, FAKE, FAKE, 0, 10, 2, 1, FAKE + 4, None) == marsit.EALIGN
+    assert lib.marsit_set_device_seed(None, 5, None) == marsit.EINVAL
+
     assert lib.marsit_apply_update(None, FAKE, 64, None) == marsit.EINVAL
     assert lib.marsit_apply_update(FAKE, FAKE, 0, None) == marsit.OK
 

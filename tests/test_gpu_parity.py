@@ -341,3 +341,44 @@ def test_ring_pipeline_orders_with_the_callers_stream():
         torch.cuda.synchronize()
     want_u, _, _ = oracle_step(g_h, c_h, 1e-3, 5)
     assert np.array_equal(host_f32(u_copy), want_u)
+
+
+def test_hop_merge_with_the_seed_in_device_memory():
+    rng = np.random.default_rng(15)
+    n = 3000
+    recv = rng.integers(0, 2**64, size=n, dtype=np.uint64)
+    local = rng.integers(0, 2**64, size=n, dtype=np.uint64)
+    slot = torch.zeros(1, dtype=torch.int64, device="cuda")
+    out = torch.zeros(n, dtype=torch.int64, device="cuda")
+    for seed in (5, 0xFEDCBA9876543210):
+        marsit.marsit_set_device_seed(slot, seed)
+        marsit.marsit_hop_merge_device_seed(dev(recv), dev(local), out, 40, n, 4, 3, slot)
+        torch.cuda.synchronize()
+        assert np.array_equal(host_bits(out), orc.hop_merge(recv, local, 40, 4, 3, seed))
+
+
+def test_device_seed_lets_a_captured_graph_be_replayed_with_new_seeds():
+    """A caller's single-stream graph around hop merges whose seed lives in device memory: every
+    replay uses the seed written just before it."""
+    rng = np.random.default_rng(16)
+    n = 20_000
+    recv = rng.integers(0, 2**64, size=n, dtype=np.uint64)
+    local = rng.integers(0, 2**64, size=n, dtype=np.uint64)
+    r_d, l_d = dev(recv), dev(local)
+    out = torch.zeros(n, dtype=torch.int64, device="cuda")
+    slot = torch.zeros(1, dtype=torch.int64, device="cuda")
+    marsit.marsit_set_device_seed(slot, 1)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        marsit.marsit_hop_merge_device_seed(r_d, l_d, out, 7, n, 3, 2, slot)      # warm-up
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        marsit.marsit_hop_merge_device_seed(r_d, l_d, out, 7, n, 3, 2, slot)
+    for seed in (11, 0x123456789ABCDEF, 11):
+        marsit.marsit_set_device_seed(slot, seed)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(host_bits(out), orc.hop_merge(recv, local, 7, 3, 2, seed)), seed
