@@ -9,8 +9,14 @@ import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
-SOURCES = [os.path.join(PKG, "csrc", "marsit_kernels.hip"), os.path.join(PKG, "csrc", "marsit_pipeline.hip")]
-HEADERS = [os.path.join(PKG, "csrc", "marsit_device.hpp"), os.path.join(ROOT, "include", "marsit.h")]
+SOURCES = [os.path.join(PKG, "csrc", name) for name in (
+    "marsit_fused.hip",          # fused one-bit pass (ring / torus / tree), full-precision round
+    "marsit_worker_ops.hip",     # per-worker kernels, the chain, host utilities
+    "marsit_diagnostics.hip",    # matching rate, majority vote, SSDM / cascading strawman
+    "marsit_pipeline.hip",       # the ring as one stream per worker
+)]
+HEADERS = [os.path.join(PKG, "csrc", "marsit_device.hpp"), os.path.join(PKG, "csrc", "marsit_host.hpp"),
+           os.path.join(ROOT, "include", "marsit.h")]
 LIB = os.path.join(PKG, "libmarsit.so")
 
 HIPCC_FLAGS = [

@@ -1,0 +1,52 @@
+// Host-side helpers shared by the translation units of libmarsit (internal, not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+
+#include "marsit.h"
+
+#ifndef MARSIT_STREAMING_STORES
+#define MARSIT_STREAMING_STORES 1
+#endif
+
+namespace marsit {
+
+constexpr int kBlock = 256;       // every kernel but the fused ones
+constexpr int kSyncBlock = 64;    // fused kernels: one wavefront per workgroup
+constexpr uint64_t kMaxElements = static_cast<uint64_t>(1) << 37;   // word index stays below 2^31
+
+// hipError_t of the last failed HIP call of this thread (marsit_last_hip_error)
+extern thread_local int tls_last_hip_error;
+
+inline int finish_launch()
+{
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess) {
+        tls_last_hip_error = static_cast<int>(err);
+        return MARSIT_EHIP;
+    }
+    return MARSIT_OK;
+}
+
+inline bool aligned_to(const void *p, uintptr_t n) { return (reinterpret_cast<uintptr_t>(p) % n) == 0; }
+
+inline uint32_t blocks_for(uint64_t n_threads)
+{
+    return static_cast<uint32_t>((n_threads + kBlock - 1) / kBlock);
+}
+
+inline uint32_t float_bits_host(float x)
+{
+    uint32_t u;
+    std::memcpy(&u, &x, sizeof u);
+    return u;
+}
+
+// Fine part bounds of the schedule (see marsit_split_bounds in marsit.h).
+int split_bounds_host(uint64_t n_words, uint32_t M, uint32_t grid_x, uint64_t *bounds);
+
+}   // namespace marsit

@@ -1,0 +1,389 @@
+// Per-worker kernels of the Marsit one-bit pass (compress, one hop of the merge, decode and
+// compensate, model update), the hop-by-hop chain built from them, and the host-side utilities of
+// the C ABI.
+
+#include "marsit_device.hpp"
+#include "marsit_host.hpp"
+
+namespace marsit {
+
+thread_local int tls_last_hip_error = 0;
+
+int split_bounds_host(uint64_t n_words, uint32_t M, uint32_t grid_x, uint64_t *bounds)
+{
+    if (bounds == nullptr || M == 0 || M > MARSIT_MAX_WORKERS)
+        return MARSIT_EINVAL;
+    const uint32_t X = (grid_x == 0) ? M : grid_x;
+    if (X == 0 || M % X != 0)
+        return MARSIT_EINVAL;
+    const uint32_t Y = M / X;
+    for (uint32_t a = 0; a < X; ++a) {
+        const uint64_t lo = static_cast<uint64_t>((static_cast<unsigned __int128>(a) * n_words) / X);
+        const uint64_t hi = static_cast<uint64_t>((static_cast<unsigned __int128>(a + 1) * n_words) / X);
+        const uint64_t n = hi - lo;
+        for (uint32_t b = 0; b < Y; ++b)
+            bounds[a * Y + b] = lo + static_cast<uint64_t>((static_cast<unsigned __int128>(b) * n) / Y);
+    }
+    bounds[M] = n_words;
+    return MARSIT_OK;
+}
+
+// -------------------------------------------------------------------------------------------------
+// marsit_compress: a wavefront takes 64 consecutive elements per packed word, one per lane, and
+// the 64-lane ballot of "sign bit clear" IS the word.  Four words per wavefront per trip keep
+// eight independent 256-byte loads in flight.
+// -------------------------------------------------------------------------------------------------
+constexpr int kWordsPerWave = 4;
+
+__global__ void __launch_bounds__(kBlock)
+compress_kernel(const float *__restrict__ g, const float *__restrict__ c,
+                uint64_t *__restrict__ bits, uint64_t d, uint64_t n_words)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t wave = (static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x) >> 6;
+    const uint64_t w0 = wave * kWordsPerWave;
+    if (w0 >= n_words)
+        return;   // uniform over the wavefront
+
+    float s[kWordsPerWave];
+    bool valid[kWordsPerWave];
+#pragma unroll
+    for (int i = 0; i < kWordsPerWave; ++i) {
+        const uint64_t e = (w0 + i) * 64u + lane;
+        valid[i] = e < d;
+        const float gv = valid[i] ? __builtin_nontemporal_load(g + e) : 0.0f;
+        const float cv = (valid[i] && c != nullptr) ? __builtin_nontemporal_load(c + e) : 0.0f;
+        s[i] = gv + cv;
+    }
+#pragma unroll
+    for (int i = 0; i < kWordsPerWave; ++i) {
+        const uint64_t word = __ballot(valid[i] && (f32_bits(s[i]) >> 31) == 0u);
+        if (lane == 0 && w0 + i < n_words)
+            bits[w0 + i] = word;
+    }
+}
+
+// -------------------------------------------------------------------------------------------------
+// marsit_hop_merge: lane = (packed word i, nibble q); one Philox call per lane.
+// -------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+hop_merge_kernel(const uint32_t *recv32, const uint32_t *local32, uint32_t *out32,
+                 uint64_t word_begin, uint64_t n_words, uint32_t threshold, bool always_local,
+                 uint32_t hop_id, uint32_t key0, uint32_t key1, const uint64_t *seed_ptr)
+{
+    if (seed_ptr != nullptr) {
+        // seed kept in device memory: lets a captured graph be replayed with a new seed
+        const uint64_t seed = *seed_ptr;
+        key0 = static_cast<uint32_t>(seed);
+        key1 = static_cast<uint32_t>(seed >> 32);
+    }
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint64_t i = col >> 4;
+    const uint32_t q = static_cast<uint32_t>(col) & 15u;
+    const size_t half_index = 2u * static_cast<size_t>(i) + (q >> 3);
+    const uint32_t shift = (q & 7u) * 4u;
+    uint32_t nib = 0;
+
+    if (i < n_words) {
+        const uint32_t r = (recv32[half_index] >> shift) & 0xFu;
+        const uint32_t l = (local32[half_index] >> shift) & 0xFu;
+        const uint64_t w = word_begin + i;
+        uint32_t u[4];
+        philox4x32_10(q, hop_id, static_cast<uint32_t>(w), static_cast<uint32_t>(w >> 32), key0,
+                      key1, u);
+        uint32_t t = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            t |= (always_local || u[j] < threshold) ? (1u << j) : 0u;
+        nib = r ^ ((r ^ l) & t);   // t ? l : r
+    }
+
+    const uint32_t half = half_row_or(nib << shift);
+    if (i < n_words && (q & 7u) == 0u)
+        out32[half_index] = half;
+}
+
+// -------------------------------------------------------------------------------------------------
+// marsit_decode_compensate: lane = one column of 4 elements.
+// -------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+decode_compensate_kernel(const uint32_t *__restrict__ bits32, const float *__restrict__ g,
+                         const float *c, float *__restrict__ update, float *c_out, uint64_t d,
+                         uint32_t scale_bits, bool aligned)
+{
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (col >= n_cols)
+        return;
+    const uint64_t e = col << 2;
+    const bool full = e + 4 <= d;
+    const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+    const bool vec = full && aligned;
+
+    const uint32_t nib = (bits32[col >> 3] >> ((static_cast<uint32_t>(col) & 7u) * 4u)) & 0xFu;
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    const f32x4 sv = load4(g + e, vec, n_valid) + ((c != nullptr) ? load4(c + e, vec, n_valid) : zero);
+    f32x4 upd;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        upd[j] = __uint_as_float(scale_bits ^ (((nib >> j) & 1u) ? 0u : 0x80000000u));
+    if (update != nullptr)
+        store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
+    store4<MARSIT_STREAMING_STORES>(c_out + e, sv - upd, vec, n_valid);
+}
+
+__global__ void __launch_bounds__(kBlock)
+apply_update_kernel(float *__restrict__ x, const float *__restrict__ update, uint64_t d, bool aligned)
+{
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (col >= n_cols)
+        return;
+    const uint64_t e = col << 2;
+    const bool full = e + 4 <= d;
+    const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+    const bool vec = full && aligned;
+    const f32x4 xv = load4<false>(x + e, vec, n_valid);
+    const f32x4 uv = load4<true>(update + e, vec, n_valid);
+    store4<false>(x + e, xv - uv, vec, n_valid);
+}
+
+}   // namespace marsit
+
+using namespace marsit;
+
+extern "C" {
+
+int marsit_version(void) { return 100; }
+
+int marsit_last_hip_error(void) { return tls_last_hip_error; }
+
+const char *marsit_status_string(int status)
+{
+    switch (status) {
+    case MARSIT_OK: return "ok";
+    case MARSIT_EINVAL: return "invalid argument";
+    case MARSIT_EALIGN: return "pointer not aligned to its element size";
+    case MARSIT_EHIP: return "HIP call failed (see marsit_last_hip_error)";
+    default: return "unknown status";
+    }
+}
+
+void marsit_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    philox4x32_10(ctr[0], ctr[1], ctr[2], ctr[3], key[0], key[1], out);
+}
+
+int marsit_split_bounds(uint64_t n_words, uint32_t M, uint32_t grid_x, uint64_t *bounds_out)
+{
+    return split_bounds_host(n_words, M, grid_x, bounds_out);
+}
+
+int marsit_compress(const float *g, const float *c, uint64_t *bits_out, uint64_t d, void *stream)
+{
+    if (g == nullptr || bits_out == nullptr || d > kMaxElements)
+        return MARSIT_EINVAL;
+    if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(bits_out, 8))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+    const uint64_t n_words = (d + 63) / 64;
+    const uint64_t n_waves = (n_words + kWordsPerWave - 1) / kWordsPerWave;
+    hipLaunchKernelGGL(compress_kernel, dim3(blocks_for(n_waves * 64)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), g, c, bits_out, d, n_words);
+    return finish_launch();
+}
+
+static int launch_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                            uint64_t word_begin, uint64_t n_words, uint32_t w_recv, uint32_t w_local,
+                            uint32_t hop_id, uint64_t seed, void *stream,
+                            const uint64_t *seed_ptr = nullptr)
+{
+    if (recv == nullptr || local == nullptr || out == nullptr || w_local == 0 ||
+        w_recv > 0x7FFFFFFFu || w_local > 0x7FFFFFFFu || n_words > kMaxElements / 64)
+        return MARSIT_EINVAL;
+    if (!aligned_to(recv, 8) || !aligned_to(local, 8) || !aligned_to(out, 8))
+        return MARSIT_EALIGN;
+    if (n_words == 0)
+        return MARSIT_OK;
+    const bool always_local = (w_recv == 0);
+    const uint32_t threshold = always_local ? 0xFFFFFFFFu : weighted_threshold(w_recv, w_local);
+    hipLaunchKernelGGL(hop_merge_kernel, dim3(blocks_for(n_words * 16)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(recv),
+                       reinterpret_cast<const uint32_t *>(local), reinterpret_cast<uint32_t *>(out),
+                       word_begin, n_words, threshold, always_local, hop_id,
+                       static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), seed_ptr);
+    return finish_launch();
+}
+
+int marsit_hop_merge_device_seed(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                                 uint64_t word_begin, uint64_t n_words, uint32_t fold, uint32_t hop_id,
+                                 const uint64_t *seed_device, void *stream)
+{
+    if (fold == 0 || seed_device == nullptr)
+        return MARSIT_EINVAL;
+    if (!aligned_to(seed_device, 8))
+        return MARSIT_EALIGN;
+    return launch_hop_merge(recv, local, out, word_begin, n_words, fold - 1, 1, hop_id, 0, stream,
+                            seed_device);
+}
+
+__global__ void set_seed_kernel(uint64_t *slot, uint64_t seed) { *slot = seed; }
+
+int marsit_set_device_seed(uint64_t *seed_device, uint64_t seed, void *stream)
+{
+    if (seed_device == nullptr)
+        return MARSIT_EINVAL;
+    if (!aligned_to(seed_device, 8))
+        return MARSIT_EALIGN;
+    hipLaunchKernelGGL(set_seed_kernel, dim3(1), dim3(1), 0, static_cast<hipStream_t>(stream), seed_device,
+                       seed);
+    return finish_launch();
+}
+
+int marsit_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                     uint64_t word_begin, uint64_t n_words, uint32_t fold, uint32_t hop_id,
+                     uint64_t seed, void *stream)
+{
+    if (fold == 0)
+        return MARSIT_EINVAL;
+    return launch_hop_merge(recv, local, out, word_begin, n_words, fold - 1, 1, hop_id, seed, stream);
+}
+
+int marsit_hop_merge_weighted(const uint64_t *recv, const uint64_t *local, uint64_t *out,
+                              uint64_t word_begin, uint64_t n_words, uint32_t w_recv,
+                              uint32_t w_local, uint32_t hop_id, uint64_t seed, void *stream)
+{
+    return launch_hop_merge(recv, local, out, word_begin, n_words, w_recv, w_local, hop_id, seed, stream);
+}
+
+int marsit_decode_compensate(const uint64_t *bits, const float *g, const float *c, float scale,
+                             float *update_out, float *c_out, uint64_t d, void *stream)
+{
+    if (bits == nullptr || g == nullptr || c_out == nullptr || !std::isfinite(scale) ||
+        d > kMaxElements)
+        return MARSIT_EINVAL;
+    if (!aligned_to(bits, 8) || !aligned_to(g, 4) || !aligned_to(c, 4) ||
+        !aligned_to(update_out, 4) || !aligned_to(c_out, 4))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
+                         aligned_to(c_out, 16);
+    hipLaunchKernelGGL(decode_compensate_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(bits), g,
+                       c, update_out, c_out, d, float_bits_host(scale), aligned);
+    return finish_launch();
+}
+
+uint64_t marsit_chain_workspace_words(uint32_t M, uint64_t d, uint32_t grid_x)
+{
+    if (M == 0 || M > MARSIT_MAX_WORKERS || d > kMaxElements)
+        return 0;
+    const uint32_t X = (grid_x == 0) ? M : grid_x;
+    if (M % X != 0)
+        return 0;
+    const uint32_t Y = M / X;
+    const uint64_t n_words = (d + 63) / 64;
+    return (static_cast<uint64_t>(M) + (Y > 1 ? Y : 0)) * n_words;
+}
+
+int marsit_chain_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                          uint64_t *workspace, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                          uint64_t seed, uint32_t grid_x, void *stream)
+{
+    if (g == nullptr || c == nullptr || update_out == nullptr || bits_out == nullptr ||
+        workspace == nullptr || M == 0 || M > MARSIT_MAX_WORKERS || ld < d || !std::isfinite(scale) ||
+        d > kMaxElements)
+        return MARSIT_EINVAL;
+    const uint32_t X = (grid_x == 0) ? M : grid_x;
+    if (M % X != 0)
+        return MARSIT_EINVAL;
+    const uint32_t Y = M / X;
+    if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(update_out, 4) ||
+        !aligned_to(bits_out, 8) || !aligned_to(workspace, 8))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+
+    const uint64_t W = (d + 63) / 64;
+    uint64_t fine[MARSIT_MAX_WORKERS + 1];
+    split_bounds_host(W, M, grid_x, fine);
+    uint64_t *maps = workspace;                    // [M][W]  every worker's own signs
+    uint64_t *rows = workspace + static_cast<size_t>(M) * W;   // [Y][W]  row results (torus)
+    int rc;
+
+    for (uint32_t m = 0; m < M; ++m) {
+        rc = marsit_compress(g + static_cast<size_t>(m) * ld, c + static_cast<size_t>(m) * ld,
+                             maps + static_cast<size_t>(m) * W, d, stream);
+        if (rc != MARSIT_OK)
+            return rc;
+    }
+
+    // row phase: row-part a = words [fine[a*Y], fine[(a+1)*Y]); in row y its chain starts at column a.
+    // The first holder sends its own signs (fold 1 copies them), every later hop h folds column (a+h) mod X.
+    for (uint32_t a = 0; a < X; ++a) {
+        const uint64_t lo = fine[a * Y], n = fine[(a + 1) * Y] - lo;
+        if (n == 0)
+            continue;
+        for (uint32_t y = 0; y < Y; ++y) {
+            uint64_t *r = (Y > 1 ? rows + static_cast<size_t>(y) * W : bits_out) + lo;
+            const uint64_t *first = maps + static_cast<size_t>(y * X + a) * W + lo;
+            rc = marsit_hop_merge(first, first, r, lo, n, 1, 0, seed, stream);
+            if (rc != MARSIT_OK)
+                return rc;
+            for (uint32_t h = 1; h < X; ++h) {
+                const uint64_t *local = maps + static_cast<size_t>(y * X + (a + h) % X) * W + lo;
+                rc = marsit_hop_merge(r, local, r, lo, n, h + 1, row_hop_id(y, h), seed, stream);
+                if (rc != MARSIT_OK)
+                    return rc;
+            }
+        }
+    }
+    // column phase over the row results: sub-part b of row-part a starts at row b
+    if (Y > 1) {
+        for (uint32_t f = 0; f < M; ++f) {
+            const uint32_t b = f % Y;
+            const uint64_t lo = fine[f], n = fine[f + 1] - lo;
+            if (n == 0)
+                continue;
+            uint64_t *r = bits_out + lo;
+            const uint64_t *first = rows + static_cast<size_t>(b) * W + lo;
+            rc = marsit_hop_merge(first, first, r, lo, n, 1, 0, seed, stream);
+            if (rc != MARSIT_OK)
+                return rc;
+            for (uint32_t k = 1; k < Y; ++k) {
+                const uint64_t *local = rows + static_cast<size_t>((b + k) % Y) * W + lo;
+                rc = marsit_hop_merge(r, local, r, lo, n, k + 1, col_hop_id(k), seed, stream);
+                if (rc != MARSIT_OK)
+                    return rc;
+            }
+        }
+    }
+
+    for (uint32_t m = 0; m < M; ++m) {
+        rc = marsit_decode_compensate(bits_out, g + static_cast<size_t>(m) * ld,
+                                      c + static_cast<size_t>(m) * ld, scale,
+                                      m == 0 ? update_out : nullptr, c + static_cast<size_t>(m) * ld,
+                                      d, stream);
+        if (rc != MARSIT_OK)
+            return rc;
+    }
+    return MARSIT_OK;
+}
+
+int marsit_apply_update(float *x, const float *update, uint64_t d, void *stream)
+{
+    if (x == nullptr || update == nullptr || d > kMaxElements)
+        return MARSIT_EINVAL;
+    if (!aligned_to(x, 4) || !aligned_to(update, 4))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+    const bool aligned = aligned_to(x, 16) && aligned_to(update, 16);
+    hipLaunchKernelGGL(apply_update_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), x, update, d, aligned);
+    return finish_launch();
+}
+
+}   // extern "C"
