@@ -379,24 +379,33 @@ tree_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
         }
         __builtin_amdgcn_sched_barrier(0);
 
-        // one draw per merge and bit: bit (4*i + j) of `take` = merge i keeps the receiver's own sign
-        uint64_t take = 0;
+        // Draws first, data later: every node of the tree carries, per bit, the index of the worker
+        // whose sign it currently stands for; a merge keeps the receiver's or takes the sender's.
+        // After the last level node 0 holds the picked worker of every bit.
+        uint32_t pick[4];
         {
-            int i = 0;
+            uint32_t leaf[M][4];
+#pragma unroll
+            for (int m = 0; m < M; ++m)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    leaf[m][j] = m;
 #pragma unroll
             for (int stride = 1, level = 0; stride < M; stride *= 2, ++level) {
 #pragma unroll
-                for (int k = 0; k + stride < M; k += 2 * stride, ++i) {
+                for (int k = 0; k + stride < M; k += 2 * stride) {
                     const int src = k + stride;
                     const uint32_t w_recv = (M - src < stride) ? (M - src) : stride;
                     uint32_t u[4];
                     philox4x32_10(q, tree_hop_id(level, k), w, 0u, key0, key1, u);
 #pragma unroll
                     for (int j = 0; j < 4; ++j)
-                        take |= (u[j] < weighted_threshold(w_recv, stride))
-                                    ? (static_cast<uint64_t>(1) << (4 * i + j)) : 0ull;
+                        leaf[k][j] = (u[j] < weighted_threshold(w_recv, stride)) ? leaf[k][j] : leaf[src][j];
                 }
             }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                pick[j] = leaf[0][j];
         }
         __builtin_amdgcn_sched_barrier(0);
 
@@ -405,22 +414,15 @@ tree_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
         for (int m = 0; m < M; ++m)
             s[m] = gv[m] + cv[m];
 
-        // the tree, bottom level first, as selections on the raw fp32 words
+        // the picked worker's raw fp32 word, per bit
         uint32_t fin[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            uint32_t val[M];
+            uint32_t r = f32_bits(s[0][j]);
 #pragma unroll
-            for (int m = 0; m < M; ++m)
-                val[m] = f32_bits(s[m][j]);
-            int i = 0;
-#pragma unroll
-            for (int stride = 1; stride < M; stride *= 2) {
-#pragma unroll
-                for (int k = 0; k + stride < M; k += 2 * stride, ++i)
-                    val[k] = ((take >> (4 * i + j)) & 1ull) ? val[k] : val[k + stride];
-            }
-            fin[j] = val[0];
+            for (int m = 1; m < M; ++m)
+                r = (pick[j] == static_cast<uint32_t>(m)) ? f32_bits(s[m][j]) : r;
+            fin[j] = r;
         }
 
         f32x4 upd;
