@@ -139,3 +139,33 @@ def test_step_can_be_captured_in_a_hip_graph():
         # eager work between replays
         scratch = torch.randn(1000, device="cuda").sum().item()
         assert np.isfinite(scratch)
+
+
+def test_resume_from_saved_compensation_reproduces_the_run():
+    """The only state carried between rounds is the compensation (and the caller's seed schedule):
+    restarting from a saved c at round k reproduces rounds k.. bit for bit, and launching the same
+    round twice gives the same result (no hidden state, no run-to-run nondeterminism)."""
+    M, d, T, k = 8, 123_457, 6, 3
+    wl = workloads.Workload("resume", M=M, d=d, grid_x=0, steps=T, scale=1e-3, dist="normal", std=0.05)
+    grads = [workloads.make_gradients(wl, t, seed=77, device="cuda") for t in range(T)]
+    c = workloads.zero_compensation(wl, device="cuda")
+    u = torch.empty(d, dtype=torch.float32, device="cuda")
+    b = marsit.new_bitmap(d)
+    history = []
+    saved_c = None
+    for t in range(T):
+        if t == k:
+            saved_c = c.clone()
+        marsit.marsit_ring_step_sim(grads[t], c, u, b, wl.scale, workloads.step_seed(500, t))
+        torch.cuda.synchronize()
+        history.append((u.clone(), b.clone(), c.clone()))
+    c2 = saved_c.clone()
+    for t in range(k, T):
+        marsit.marsit_ring_step_sim(grads[t], c2, u, b, wl.scale, workloads.step_seed(500, t))
+        torch.cuda.synchronize()
+        assert torch.equal(u, history[t][0]) and torch.equal(b, history[t][1]) and torch.equal(c2, history[t][2])
+    # a different seed at round k changes the merged signs (the seed really is the only randomness)
+    c3 = saved_c.clone()
+    marsit.marsit_ring_step_sim(grads[k], c3, u, b, wl.scale, workloads.step_seed(501, k))
+    torch.cuda.synchronize()
+    assert not torch.equal(b, history[k][1])
