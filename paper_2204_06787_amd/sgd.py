@@ -1,0 +1,57 @@
+"""Marsit-driven SGD (Algorithm 2 of the paper) for M workers simulated on one GPU.
+
+A thin driver: it owns the state Algorithm 2 carries between rounds (the model ``x``, the
+compensation vectors ``c``, the round counter) and calls the library once per round for the
+synchronisation (Algorithm 1: one-bit pass, or the full-precision round every ``K`` rounds) and once
+for the model update.  All arithmetic runs in the HIP kernels.
+"""
+
+from __future__ import annotations
+
+import torch
+
+from . import marsit
+
+
+class MarsitSGD:
+    def __init__(self, x: torch.Tensor, M: int, K: int, eta_s: float, seed: int,
+                 schedule: str = "ring", grid_x: int = 0):
+        """``x``: the model, float32 ``[d]`` in device memory, updated in place.
+        ``K``: a full-precision round whenever ``t mod K == 0`` (``t`` starts at 0).
+        ``schedule``: ``"ring"`` (``grid_x`` = 0), ``"torus"`` (``grid_x`` columns) or ``"tree"``."""
+        if schedule not in ("ring", "torus", "tree"):
+            raise ValueError("schedule must be ring, torus or tree")
+        if not (x.is_cuda and x.dtype == torch.float32 and x.dim() == 1 and x.is_contiguous()):
+            raise TypeError("x: need a contiguous 1-D float32 tensor in device memory")
+        if K < 1:
+            raise ValueError("K must be at least 1")
+        self.x, self.M, self.K, self.eta_s, self.seed = x, int(M), int(K), float(eta_s), int(seed)
+        self.schedule = schedule
+        self.grid_x = int(grid_x) if schedule == "torus" else 0
+        d = x.numel()
+        self.c = torch.zeros((self.M, d), dtype=torch.float32, device=x.device)     # c_0 = 0
+        self.update = torch.empty(d, dtype=torch.float32, device=x.device)
+        self.bits = marsit.new_bitmap(d, device=x.device)
+        self.t = 0
+
+    def step(self, scaled_grads: torch.Tensor, stream=None) -> torch.Tensor:
+        """One round.  ``scaled_grads``: ``[M, d]`` float32, worker m's stochastic gradient already
+        multiplied by the local step size.  Returns the global update that was applied to ``x``."""
+        seed = (self.seed + self.t) & 0xFFFFFFFFFFFFFFFF
+        if self.schedule == "tree" and self.t % self.K != 0:
+            marsit.marsit_tree_step_sim(scaled_grads, self.c, self.update, self.bits, self.eta_s, seed,
+                                        stream=stream)
+        else:
+            marsit.marsit_step(self.t, self.K, scaled_grads, self.c, self.update, self.bits, self.eta_s,
+                               seed, grid_x=self.grid_x, stream=stream)
+        marsit.marsit_apply_update(self.x, self.update, stream=stream)
+        self.t += 1
+        return self.update
+
+    def average_bits_per_element(self, rounds: int | None = None) -> float:
+        """Transmitted bits per element and round: 32 in a full-precision round, 1 otherwise."""
+        n = self.t if rounds is None else int(rounds)
+        if n == 0:
+            return 0.0
+        full = (n + self.K - 1) // self.K                       # rounds t = 0, K, 2K, ... below n
+        return (32.0 * full + (n - full)) / n

@@ -169,3 +169,41 @@ def test_resume_from_saved_compensation_reproduces_the_run():
     marsit.marsit_ring_step_sim(grads[k], c3, u, b, wl.scale, workloads.step_seed(501, k))
     torch.cuda.synchronize()
     assert not torch.equal(b, history[k][1])
+
+
+@pytest.mark.parametrize("schedule,M,grid_x,K", [("ring", 8, 0, 10), ("torus", 16, 4, 7), ("tree", 8, 0, 1000),
+                                                ("ring", 3, 0, 1)])
+def test_marsit_sgd_follows_the_auxiliary_sequence(schedule, M, grid_x, K):
+    """Appendix B: y_t = x_t - mean_m c_t^(m) moves exactly like plain SGD with the mean gradient,
+    y_{t+1} = y_t - mean_m g_t^(m), whichever branch of Algorithm 1 a round takes.  Checked on a noisy
+    quadratic, where the loss must also go down."""
+    from paper_2204_06787_amd.sgd import MarsitSGD
+    d, T, eta_l, eta_s = 200_003, 40, 0.05, 5e-3
+    gen = torch.Generator(device="cuda").manual_seed(123)
+    target = torch.randn(d, generator=gen, device="cuda")
+    x = torch.zeros(d, dtype=torch.float32, device="cuda")
+    opt = MarsitSGD(x, M=M, K=K, eta_s=eta_s, seed=99, schedule=schedule, grid_x=grid_x)
+    y = x.double().clone()                                   # y_0 = x_0 - 0
+    loss0 = float(((x - target) ** 2).mean())
+    for t in range(T):
+        noise = torch.randn((M, d), generator=gen, device="cuda") * 0.5
+        grads = ((x - target).unsqueeze(0) + noise) * eta_l     # eta_l * grad f_m(x_t; xi)
+        grads = grads.float().contiguous()
+        opt.step(grads)
+        y -= grads.double().mean(dim=0)
+    torch.cuda.synchronize()
+    got = x.double() - opt.c.double().mean(dim=0)
+    assert float((got - y).abs().max()) <= 1e-4               # fp32 rounding of T rounds, values of order 1
+    assert bool((opt.update.abs() == np.float32(eta_s)).all()) or (T - 1) % K == 0
+    assert float(((x - target) ** 2).mean()) < 0.9 * loss0
+    full = (T + K - 1) // K
+    assert opt.average_bits_per_element() == pytest.approx((32 * full + T - full) / T)
+
+
+def test_average_bits_per_element_matches_the_printed_table():
+    """Fig. 4(b): 1.62 / 1.31 / 1.16 bits for K = 50 / 100 / 200 (one 32-bit round every K)."""
+    from paper_2204_06787_amd.sgd import MarsitSGD
+    x = torch.zeros(64, dtype=torch.float32, device="cuda")
+    for K, printed in ((50, 1.62), (100, 1.31), (200, 1.16)):
+        opt = MarsitSGD(x, M=2, K=K, eta_s=1e-3, seed=1)
+        assert round(opt.average_bits_per_element(rounds=K), 2) == printed
