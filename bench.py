@@ -215,19 +215,21 @@ def main():
         aux["marsit_hop_merge"]["note"] = f"one part of {seg} packed words ({8 * seg} B message); ALU-bound by design"
         aux["marsit_tree_step_sim"] = entry(timed(lambda: marsit.marsit_tree_step_sim(
             grads[0], c3, update, one_bits, wl.scale, args.seed, stream=stream), reps=20, warm=25), nbytes)
-        if not wl.grid_x:
-            # the ring as M workers on M streams, hop by hop (what a transport would sequence)
-            with marsit.RingPipeline(M) as pipe:
-                wsp = torch.empty(pipe.workspace_words(d), dtype=torch.int64, device="cuda")
-                ms = timed(lambda: pipe.ring_step(grads[0], c3, update, one_bits, wsp, wl.scale, args.seed,
-                                                  stream=stream), reps=5)
-                torch.cuda.synchronize()
-            aux["marsit_pipeline_ring_step"] = {
-                "ms_per_step": ms, "streams": M, "launches_per_step": M * M + M * (M - 1) + M,
-                "ms_per_hop_step": ms / (M + 1),
-                "note": "M compress+send steps, M-1 merge hops, 1 decode step; segments of "
-                        f"{8 * ((d // 64) // M)} B"}
-            del wsp
+        # the schedule as M workers on M streams, hop by hop (what a transport would sequence)
+        X = wl.grid_x or M
+        Y = M // X
+        with marsit.RingPipeline(M) as pipe:
+            wsp = torch.empty(pipe.workspace_words(d, wl.grid_x), dtype=torch.int64, device="cuda")
+            ms = timed(lambda: pipe.step(grads[0], c3, update, one_bits, wsp, wl.scale, args.seed,
+                                         grid_x=wl.grid_x, stream=stream), reps=5)
+            torch.cuda.synchronize()
+        aux["marsit_pipeline_step"] = {
+            "ms_per_step": ms, "streams": M,
+            "launches_per_step": M * X + M * (X - 1) + (M * (Y - 1) if Y > 1 else 0) + M,
+            "hop_steps": X + (Y - 1) + 1,
+            "note": f"{X} compress+send steps, {X - 1} row merge hops, {Y - 1} column merge hops, 1 decode step; "
+                    f"row segments of {8 * ((d // 64) // X)} B"}
+        del wsp
         out["other_entry_points"] = aux
         del c3, x, one_bits
 

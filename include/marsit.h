@@ -186,20 +186,28 @@ uint64_t marsit_chain_workspace_words(uint32_t M, uint64_t d, uint32_t grid_x);
  * and the release of its own send buffer.  A worker computes the signs of a part right before it
  * folds them in, so that computation overlaps the wait for the incoming segment (Algorithm 1:
  * receive in parallel with the sign step).  The gather period is simulated: the last holder of a part writes it to bits_out, which
- * every worker reads.  Ring schedule only.  Results are bit-identical to marsit_ring_step_sim.
+ * every worker reads.  marsit_pipeline_step takes grid_x as marsit_ring_step_sim does: on a torus each
+ * row runs its ring first; the row result of row-part a ends at column (a + X - 1) mod X, whose Y
+ * workers then run the column ring over the Y sub-parts of that row-part.  marsit_pipeline_ring_step
+ * is marsit_pipeline_step with grid_x = 0.  Results are bit-identical to marsit_ring_step_sim.
  *
  * marsit_pipeline_create makes the M streams (default priority) and the events; this is the only
  * call of the library that creates runtime objects, marsit_pipeline_destroy releases them (after
- * synchronising the worker streams).  marsit_pipeline_ring_step allocates nothing; it returns when
+ * synchronising the worker streams).  marsit_pipeline_step allocates nothing; it returns when
  * everything is enqueued, and `stream` is made to wait for the workers, so work enqueued on
  * `stream` afterwards sees the results.  One step at a time per pipeline object.
- *   workspace  device scratch owned by the caller, marsit_pipeline_workspace_words(M, d) 64-bit
- *              words: the M per-worker bitmaps and two send buffers per worker.
+ *   workspace  device scratch owned by the caller, marsit_pipeline_workspace_words(M, d, grid_x)
+ *              64-bit words (0 for an invalid shape): the M per-worker bitmaps and two send
+ *              buffers per worker, on a torus also the Y row results and two column-phase send
+ *              buffers per worker.
  */
 typedef struct marsit_pipeline marsit_pipeline;
 int marsit_pipeline_create(marsit_pipeline **out, uint32_t M);
 int marsit_pipeline_destroy(marsit_pipeline *p);
-uint64_t marsit_pipeline_workspace_words(uint32_t M, uint64_t d);
+uint64_t marsit_pipeline_workspace_words(uint32_t M, uint64_t d, uint32_t grid_x);
+int marsit_pipeline_step(marsit_pipeline *p, const float *g, float *c, float *update_out,
+                         uint64_t *bits_out, uint64_t *workspace, uint64_t d, uint64_t ld, float scale,
+                         uint64_t seed, uint32_t grid_x, void *stream);
 int marsit_pipeline_ring_step(marsit_pipeline *p, const float *g, float *c, float *update_out,
                               uint64_t *bits_out, uint64_t *workspace, uint64_t d, uint64_t ld,
                               float scale, uint64_t seed, void *stream);

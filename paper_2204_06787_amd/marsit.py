@@ -25,7 +25,7 @@ EXPORTS = (
     "marsit_ring_step_sim", "marsit_chain_step_sim", "marsit_chain_workspace_words",
     "marsit_full_sync", "marsit_step", "marsit_apply_update",
     "marsit_pipeline_create", "marsit_pipeline_destroy", "marsit_pipeline_workspace_words",
-    "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
+    "marsit_pipeline_step", "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
     "marsit_aggregate_sign", "marsit_majority_vote", "marsit_count_matching",
     "marsit_hop_merge_weighted", "marsit_tree_step_sim",
     "marsit_ssdm_cascade_hop", "marsit_cascade_ring_step_sim",
@@ -82,9 +82,11 @@ def load_library(path: str | None = None):
     lib.marsit_pipeline_create.restype = ci
     lib.marsit_pipeline_destroy.argtypes = [vp]
     lib.marsit_pipeline_destroy.restype = ci
-    lib.marsit_pipeline_workspace_words.argtypes = [u32, u64]
+    lib.marsit_pipeline_workspace_words.argtypes = [u32, u64, u32]
     lib.marsit_pipeline_workspace_words.restype = u64
     lib.marsit_pipeline_ring_step.argtypes = [vp, vp, vp, vp, vp, vp, u64, u64, f32, u64, vp]
+    lib.marsit_pipeline_step.argtypes = [vp, vp, vp, vp, vp, vp, u64, u64, f32, u64, u32, vp]
+    lib.marsit_pipeline_step.restype = ci
     lib.marsit_pipeline_ring_step.restype = ci
     lib.marsit_hop_merge_device_seed.argtypes = [vp, vp, vp, u64, u64, u32, u32, vp, vp]
     lib.marsit_hop_merge_device_seed.restype = ci
@@ -264,15 +266,32 @@ def marsit_chain_step_sim(g, c, update_out, bits_out, workspace, scale: float, s
 
 
 class RingPipeline:
-    """Handle of ``marsit_pipeline_*``: a ring of M workers, one HIP stream each."""
+    """Handle of ``marsit_pipeline_*``: M workers, one HIP stream each, on a ring or a torus."""
 
     def __init__(self, M: int):
         self._h = ctypes.c_void_p()
         self.M = int(M)
         _check("marsit_pipeline_create", load_library().marsit_pipeline_create(ctypes.byref(self._h), M))
 
-    def workspace_words(self, d: int) -> int:
-        return int(load_library().marsit_pipeline_workspace_words(self.M, d))
+    def workspace_words(self, d: int, grid_x: int = 0) -> int:
+        return int(load_library().marsit_pipeline_workspace_words(self.M, d, grid_x))
+
+    def step(self, g, c, update_out, bits_out, workspace, scale: float, seed: int, grid_x: int = 0,
+             d: int | None = None, stream=None):
+        M, ld = _rows(g, "g")
+        if M != self.M or _rows(c, "c") != (M, ld):
+            raise TypeError("g and c must be [M, ld] with the pipeline's M")
+        d = g.shape[1] if d is None else int(d)
+        need = self.workspace_words(d, grid_x)
+        if need == 0 and d > 0:
+            raise ValueError("grid_x must be 0 or divide M")
+        if workspace.numel() < need:
+            raise ValueError("workspace too small")
+        _check("marsit_pipeline_step", load_library().marsit_pipeline_step(
+            self._h, _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
+            _bits_ptr(bits_out, "bits_out"), _bits_ptr(workspace, "workspace"), d, ld, scale,
+            seed & 0xFFFFFFFFFFFFFFFF, grid_x, _stream(stream)))
+        return update_out, bits_out
 
     def ring_step(self, g, c, update_out, bits_out, workspace, scale: float, seed: int,
                   d: int | None = None, stream=None):

@@ -135,8 +135,13 @@ def test_other_entry_points_argument_validation(lib):
     assert lib.marsit_pipeline_create(None, 4) == marsit.EINVAL
     assert lib.marsit_pipeline_destroy(None) == marsit.EINVAL
     assert lib.marsit_pipeline_ring_step(None, FAKE, FAKE, FAKE, FAKE, FAKE, 64, 64, 1.0, 1, None) == marsit.EINVAL
-    assert lib.marsit_pipeline_workspace_words(8, 25_600_000) == 8 * 400_000 + 16 * 50_001
-    assert lib.marsit_pipeline_workspace_words(0, 100) == 0
+    assert lib.marsit_pipeline_step(None, FAKE, FAKE, FAKE, FAKE, FAKE, 64, 64, 1.0, 1, 0, None) == marsit.EINVAL
+    assert lib.marsit_pipeline_workspace_words(8, 25_600_000, 0) == 8 * 400_000 + 16 * 50_001
+    # 4 x 4 torus: own maps, row send buffers, 4 row results, column send buffers
+    assert lib.marsit_pipeline_workspace_words(16, 25_600_000, 4) == (
+        16 * 400_000 + 32 * 100_001 + 4 * 400_000 + 32 * 25_001)
+    assert lib.marsit_pipeline_workspace_words(0, 100, 0) == 0
+    assert lib.marsit_pipeline_workspace_words(6, 100, 4) == 0
 
     assert lib.marsit_aggregate_sign(FAKE, None, FAKE, 4, 64, 64, None) == marsit.EINVAL
     assert lib.marsit_majority_vote(FAKE, FAKE, FAKE, 65, 64, 64, None) == marsit.EINVAL

@@ -326,6 +326,29 @@ def test_ring_pipeline(M, d):
             assert_f32_parity(host_f32(c1), c_h, f"compensation (pipeline), step {t}")
 
 
+@pytest.mark.parametrize("M,X,d", [(8, 4, 400_000 + 21), (8, 2, 64 * 37 + 5), (16, 4, 200_003), (6, 3, 65_536),
+                                   (6, 2, 7), (4, 1, 64 * 9 + 3), (4, 4, 1000), (12, 4, 64 * 5), (9, 3, 1),
+                                   (64, 8, 70_001)])
+def test_torus_pipeline(M, X, d):
+    """Row rings, then column rings among the last holders, on one stream per worker."""
+    g_h, c_h = _inputs(M, d, seed=14)
+    g1, c1 = dev(g_h), dev(c_h)
+    g2, c2 = dev(g_h), dev(c_h)
+    u1 = torch.empty(d, dtype=torch.float32, device="cuda")
+    b1 = marsit.new_bitmap(d)
+    with marsit.RingPipeline(M) as pipe:
+        ws = torch.empty(pipe.workspace_words(d, X), dtype=torch.int64, device="cuda")
+        for t in range(3):
+            sd = workloads.step_seed(815, t)
+            pipe.step(g1, c1, u1, b1, ws, 1e-3, sd, grid_x=X)
+            torch.cuda.synchronize()
+            u2, b2 = fused_step(g2, c2, 1e-3, sd, grid_x=X)
+            want_u, want_b, _ = oracle_step(g_h, c_h, 1e-3, sd, grid_x=X)
+            assert np.array_equal(host_bits(b1), want_b) and torch.equal(b1, b2), t
+            assert np.array_equal(host_f32(u1), want_u) and torch.equal(u1, u2), t
+            assert_f32_parity(host_f32(c1), c_h, f"compensation (torus pipeline), step {t}")
+
+
 def test_ring_pipeline_orders_with_the_callers_stream():
     """Work enqueued on the caller's stream after the step sees the results without a device sync."""
     M, d = 8, 300_000
