@@ -356,6 +356,30 @@ void oracle_apply_update(float *x, const float *update, uint64_t d)
     }
 }
 
+/*
+ * Local momentum of a worker (Section 5, "Optimizers and hyper-parameters": the image runs use the
+ * Momentum optimizer; the paper prints no formula, so the common heavy-ball form is taken):
+ *     buf <- beta * buf + grad;     g <- eta_l * buf,
+ * one fp32 rounding per operation (product, sum, product), for every worker m and element e < d.
+ * g is what Algorithm 2 hands to Marsit as its (already scaled) gradient.
+ */
+int oracle_local_momentum(float *buf, const float *grad, float *g_out, uint32_t M, uint64_t d,
+                          uint64_t ld, float beta, float eta_l)
+{
+    if (ld < d)
+        return -1;
+    for (uint32_t m = 0; m < M; ++m) {
+        for (uint64_t e = 0; e < d; ++e) {
+            const size_t i = (size_t)m * ld + e;
+            const float carried = beta * buf[i];
+            const float v = carried + grad[i];
+            buf[i] = v;
+            g_out[i] = eta_l * v;
+        }
+    }
+    return 0;
+}
+
 /* ------------------------------------------------------------------------------------------
  * Diagnostics of Section 3.2.2 / Fig. 2(b): the "matching rate" of a sign vector is the share of
  * elements whose sign equals the sign of the non-compressed aggregate sum_m (g^(m) + c^(m)).

@@ -75,6 +75,8 @@ def _load():
     lib.oracle_full_sync.restype = ctypes.c_int
     lib.oracle_apply_update.argtypes = [vp, vp, u64]
     lib.oracle_apply_update.restype = None
+    lib.oracle_local_momentum.argtypes = [vp, vp, vp, u32, u64, u64, f32, f32]
+    lib.oracle_local_momentum.restype = ctypes.c_int
     lib.oracle_aggregate_sign.argtypes = [vp, vp, vp, u32, u64, u64]
     lib.oracle_aggregate_sign.restype = None
     lib.oracle_majority_vote.argtypes = [vp, vp, vp, u32, u64, u64]
@@ -264,6 +266,20 @@ def apply_update(x, update):
     assert x.shape == update.shape
     _load().oracle_apply_update(_ptr(x), _ptr(update), x.size)
     return x
+
+
+def local_momentum(buf, grad, beta, eta_l, d=None):
+    """buf <- beta*buf + grad (in place); returns g = eta_l * buf.  buf, grad: float32 [M, ld]."""
+    buf = _f32(buf, "buf")
+    grad = _f32(grad, "grad")
+    assert buf.ndim == 2 and buf.shape == grad.shape
+    M, ld = buf.shape
+    d = ld if d is None else int(d)
+    g = np.full_like(grad, 12345.0)
+    rc = _load().oracle_local_momentum(_ptr(buf), _ptr(grad), _ptr(g), M, d, ld,
+                                       beta, eta_l)
+    assert rc == 0
+    return g
 
 
 # --- diagnostics (Section 3.2.2, Fig. 2b) ------------------------------------------------------

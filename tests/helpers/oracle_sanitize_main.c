@@ -38,6 +38,7 @@ static int run_case(uint32_t M, uint64_t d, uint64_t ld, uint32_t grid_x)
     oracle_majority_vote(g, c, bits, M, d, ld);
     (void)oracle_count_matching(bits, ref, d);
     rc |= oracle_full_sync(g, c, update, M, d, ld);
+    rc |= oracle_local_momentum(c, g, g, M, d, ld, 0.9f, 0.1f);
     if (d > 0)
         oracle_apply_update(g, update, d);
     free(g); free(c); free(update); free(bits); free(maps); free(ref); free(norms);

@@ -502,6 +502,57 @@ def test_apply_update():
     assert np.array_equal(orc.apply_update(x, u), np.array([0.5, 2.5, -3.25], dtype=np.float32))
 
 
+def test_local_momentum_geometric_closed_form():
+    """Constant gradient 1, beta = 1/2: buf_t = 2 - 2^(1-t) exactly (every value is a short binary
+    fraction), g_t = eta_l * buf_t; a gradient of -3 in another worker scales the same series."""
+    buf = np.zeros((2, 5), dtype=np.float32)
+    grad = np.empty((2, 5), dtype=np.float32)
+    grad[0] = 1.0
+    grad[1] = -3.0
+    grad[:, 4] = 777.0                      # column >= d: never read, never written
+    for t in range(1, 20):
+        g = orc.local_momentum(buf, grad, 0.5, 0.25, d=4)
+        want = 2.0 - 2.0 ** (1 - t)
+        assert np.all(buf[0, :4] == np.float32(want)) and np.all(buf[1, :4] == np.float32(-3.0 * want))
+        assert np.all(g[0, :4] == np.float32(0.25 * want)) and np.all(g[1, :4] == np.float32(-0.75 * want))
+        assert np.all(buf[:, 4] == 0.0) and np.all(g[:, 4] == 12345.0)
+
+
+def test_local_momentum_special_cases():
+    """beta = 0 is plain scaling of the gradient; beta = 1 with eta_l = 1 is a running sum."""
+    rng = np.random.default_rng(77)
+    grad = rng.standard_normal((3, 1000)).astype(np.float32)
+    buf = rng.standard_normal((3, 1000)).astype(np.float32)
+    g = orc.local_momentum(buf, grad, 0.0, 0.1)
+    assert np.array_equal(buf, grad) and np.array_equal(g, np.float32(0.1) * grad)
+    total = np.zeros_like(grad)
+    acc = np.zeros_like(grad)
+    for _ in range(5):
+        step = rng.integers(-8, 9, size=grad.shape).astype(np.float32)      # integers: sums are exact
+        total += step
+        g = orc.local_momentum(acc, step, 1.0, 1.0)
+        assert np.array_equal(acc, total) and np.array_equal(g, total)
+
+
+def test_local_momentum_matches_torch_sgd_buffer():
+    """The heavy-ball buffer is the one torch.optim.SGD keeps (dampening 0): with lr = eta_l the
+    parameter moves by -g every step.  torch fuses nothing here on CPU, so agreement is to rounding."""
+    import torch
+    rng = np.random.default_rng(78)
+    x0 = rng.standard_normal(500).astype(np.float32)
+    p = torch.nn.Parameter(torch.from_numpy(x0.copy()))
+    opt = torch.optim.SGD([p], lr=0.05, momentum=0.9)
+    buf = np.zeros((1, 500), dtype=np.float32)
+    x = x0.astype(np.float64)
+    for t in range(6):
+        grad = rng.standard_normal((1, 500)).astype(np.float32)
+        p.grad = torch.from_numpy(grad[0].copy())
+        opt.step()
+        g = orc.local_momentum(buf, grad, 0.9, 0.05)
+        x = x - g[0].astype(np.float64)
+        assert np.allclose(p.detach().numpy(), x, rtol=0, atol=2e-6 * (t + 1))
+
+
 # ---------------------------------------------------------------------------------------------
 # Matching-rate diagnostics (Section 3.2.2, Fig. 2b)
 # ---------------------------------------------------------------------------------------------
