@@ -205,6 +205,11 @@ def main():
         aux["marsit_full_sync"] = entry(timed(lambda: marsit.marsit_full_sync(grads[0], c3, update, stream=stream),
                                               reps=20, warm=25), 12 * M * d + 4 * d)
         aux["marsit_apply_update"] = entry(timed(lambda: marsit.marsit_apply_update(x, update, stream=stream)), 12 * d)
+        scaled = torch.empty_like(c3)
+        aux["marsit_local_momentum"] = entry(timed(lambda: marsit.marsit_local_momentum(
+            c3, grads[0], scaled, 0.5, 0.1, stream=stream)), 16 * M * d)
+        c3.zero_()
+        del scaled
         aux["marsit_compress"] = entry(timed(lambda: marsit.marsit_compress(grads[0][0], c3[0], one_bits, stream=stream)),
                                        8 * d + d // 8)
         aux["marsit_decode_compensate"] = entry(timed(lambda: marsit.marsit_decode_compensate(

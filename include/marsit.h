@@ -278,6 +278,16 @@ int marsit_cascade_ring_step_sim(const float *g, const float *c, float *update_o
                                  float *norms_out, void *workspace, uint32_t M, uint64_t d, uint64_t ld,
                                  uint64_t seed, void *stream);
 
+/*
+ * Local momentum of the M workers before a synchronisation (Section 5, optimizers: the image runs
+ * use Momentum; heavy-ball form):  buf <- beta * buf + grad;  g_out <- eta_l * buf,  each operation
+ * rounded once in fp32.  g_out is what Algorithm 2 passes to the synchronisation as the scaled
+ * gradient.  All three arrays are [M][ld] device memory, columns >= d untouched; g_out may be the
+ * same array as grad, buf may not alias either.  beta, eta_l finite.
+ */
+int marsit_local_momentum(float *buf, const float *grad, float *g_out, uint32_t M, uint64_t d,
+                          uint64_t ld, float beta, float eta_l, void *stream);
+
 /* Algorithm 2, the model update:  x[e] <- x[e] - update[e]. */
 int marsit_apply_update(float *x, const float *update, uint64_t d, void *stream);
 

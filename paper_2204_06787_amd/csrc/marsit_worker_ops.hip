@@ -148,6 +148,31 @@ apply_update_kernel(float *__restrict__ x, const float *__restrict__ update, uin
     store4<false>(x + e, xv - uv, vec, n_valid);
 }
 
+// Local heavy-ball momentum for all workers in one launch (blockIdx.y = worker):
+// buf <- beta * buf + grad; g <- eta_l * buf.  Three separately rounded fp32 operations (the library
+// is built without contraction).  g may be the same array as grad: a lane reads its four elements
+// before it writes them.
+__global__ void __launch_bounds__(kBlock)
+local_momentum_kernel(float *__restrict__ buf, const float *grad, float *g_out, uint64_t d,
+                      uint64_t ld, float beta, float eta_l, bool aligned)
+{
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (col >= n_cols)
+        return;
+    const uint64_t e = col << 2;
+    const size_t at = static_cast<size_t>(blockIdx.y) * ld + e;
+    const bool full = e + 4 <= d;
+    const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+    const bool vec = full && aligned;
+    const f32x4 bv = load4<true>(buf + at, vec, n_valid);
+    const f32x4 gv = load4<true>(grad + at, vec, n_valid);
+    const f32x4 carried = bv * beta;
+    const f32x4 v = carried + gv;
+    store4<true>(buf + at, v, vec, n_valid);
+    store4<true>(g_out + at, v * eta_l, vec, n_valid);
+}
+
 }   // namespace marsit
 
 using namespace marsit;
@@ -383,6 +408,23 @@ int marsit_apply_update(float *x, const float *update, uint64_t d, void *stream)
     const bool aligned = aligned_to(x, 16) && aligned_to(update, 16);
     hipLaunchKernelGGL(apply_update_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock), 0,
                        static_cast<hipStream_t>(stream), x, update, d, aligned);
+    return finish_launch();
+}
+
+int marsit_local_momentum(float *buf, const float *grad, float *g_out, uint32_t M, uint64_t d,
+                          uint64_t ld, float beta, float eta_l, void *stream)
+{
+    if (buf == nullptr || grad == nullptr || g_out == nullptr || M == 0 || M > MARSIT_MAX_WORKERS ||
+        ld < d || d > kMaxElements || !std::isfinite(beta) || !std::isfinite(eta_l) || buf == grad ||
+        buf == g_out)
+        return MARSIT_EINVAL;
+    if (!aligned_to(buf, 4) || !aligned_to(grad, 4) || !aligned_to(g_out, 4))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+    const bool aligned = aligned_to(buf, 16) && aligned_to(grad, 16) && aligned_to(g_out, 16) && ld % 4 == 0;
+    hipLaunchKernelGGL(local_momentum_kernel, dim3(blocks_for((d + 3) >> 2), M), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), buf, grad, g_out, d, ld, beta, eta_l, aligned);
     return finish_launch();
 }
 

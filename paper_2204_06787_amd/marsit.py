@@ -23,7 +23,7 @@ EXPORTS = (
     "marsit_version", "marsit_last_hip_error", "marsit_status_string", "marsit_philox4x32_10",
     "marsit_split_bounds", "marsit_compress", "marsit_hop_merge", "marsit_decode_compensate",
     "marsit_ring_step_sim", "marsit_chain_step_sim", "marsit_chain_workspace_words",
-    "marsit_full_sync", "marsit_step", "marsit_apply_update",
+    "marsit_full_sync", "marsit_step", "marsit_apply_update", "marsit_local_momentum",
     "marsit_pipeline_create", "marsit_pipeline_destroy", "marsit_pipeline_workspace_words",
     "marsit_pipeline_step", "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
     "marsit_aggregate_sign", "marsit_majority_vote", "marsit_count_matching",
@@ -114,6 +114,8 @@ def load_library(path: str | None = None):
     lib.marsit_step.restype = ci
     lib.marsit_apply_update.argtypes = [vp, vp, u64, vp]
     lib.marsit_apply_update.restype = ci
+    lib.marsit_local_momentum.argtypes = [vp, vp, vp, u32, u64, u64, f32, f32, vp]
+    lib.marsit_local_momentum.restype = ci
     if path == LIB_PATH:
         _lib = lib
     return lib
@@ -348,6 +350,17 @@ def marsit_apply_update(x, update, d: int | None = None, stream=None):
     _check("marsit_apply_update", load_library().marsit_apply_update(
         _f32_ptr(x, "x"), _f32_ptr(update, "update"), d, _stream(stream)))
     return x
+
+
+def marsit_local_momentum(buf, grad, g_out, beta: float, eta_l: float, d: int | None = None, stream=None):
+    M, ld = _rows(buf, "buf")
+    if _rows(grad, "grad") != (M, ld) or _rows(g_out, "g_out") != (M, ld):
+        raise TypeError("buf, grad and g_out must have the same shape and row stride")
+    d = buf.shape[1] if d is None else int(d)
+    _check("marsit_local_momentum", load_library().marsit_local_momentum(
+        _f32_ptr(buf, "buf"), _f32_ptr(grad, "grad"), _f32_ptr(g_out, "g_out"), M, d, ld, beta, eta_l,
+        _stream(stream)))
+    return g_out
 
 
 # --- diagnostics (Section 3.2.2, Fig. 2b) --------------------------------------------------------

@@ -15,10 +15,12 @@ from . import marsit
 
 class MarsitSGD:
     def __init__(self, x: torch.Tensor, M: int, K: int, eta_s: float, seed: int,
-                 schedule: str = "ring", grid_x: int = 0):
+                 schedule: str = "ring", grid_x: int = 0, momentum: float = 0.0):
         """``x``: the model, float32 ``[d]`` in device memory, updated in place.
         ``K``: a full-precision round whenever ``t mod K == 0`` (``t`` starts at 0).
-        ``schedule``: ``"ring"`` (``grid_x`` = 0), ``"torus"`` (``grid_x`` columns) or ``"tree"``."""
+        ``schedule``: ``"ring"`` (``grid_x`` = 0), ``"torus"`` (``grid_x`` columns) or ``"tree"``.
+        ``momentum``: heavy-ball coefficient of the workers' local optimizer (Section 5 of the paper
+        trains the image models with Momentum); used by :meth:`step_from_raw_gradients`."""
         if schedule not in ("ring", "torus", "tree"):
             raise ValueError("schedule must be ring, torus or tree")
         if not (x.is_cuda and x.dtype == torch.float32 and x.dim() == 1 and x.is_contiguous()):
@@ -32,7 +34,18 @@ class MarsitSGD:
         self.c = torch.zeros((self.M, d), dtype=torch.float32, device=x.device)     # c_0 = 0
         self.update = torch.empty(d, dtype=torch.float32, device=x.device)
         self.bits = marsit.new_bitmap(d, device=x.device)
+        self.momentum = float(momentum)
+        self.buf = None                                     # [M, d] momentum buffers, made on first use
         self.t = 0
+
+    def step_from_raw_gradients(self, grads: torch.Tensor, eta_l: float, stream=None) -> torch.Tensor:
+        """One round from the workers' unscaled stochastic gradients ``[M, d]``: the local momentum
+        buffers are advanced and ``eta_l`` times the buffers goes into the synchronisation.
+        ``grads`` is overwritten with that scaled input."""
+        if self.buf is None:
+            self.buf = torch.zeros_like(self.c)
+        marsit.marsit_local_momentum(self.buf, grads, grads, self.momentum, eta_l, stream=stream)
+        return self.step(grads, stream=stream)
 
     def step(self, scaled_grads: torch.Tensor, stream=None) -> torch.Tensor:
         """One round.  ``scaled_grads``: ``[M, d]`` float32, worker m's stochastic gradient already

@@ -169,6 +169,12 @@ def test_other_entry_points_argument_validation(lib):
 
     assert lib.marsit_apply_update(None, FAKE, 64, None) == marsit.EINVAL
     assert lib.marsit_apply_update(FAKE, FAKE, 0, None) == marsit.OK
+    assert lib.marsit_local_momentum(FAKE, FAKE + 64, None, 2, 64, 64, 0.9, 0.1, None) == marsit.EINVAL
+    assert lib.marsit_local_momentum(FAKE, FAKE, FAKE + 64, 2, 64, 64, 0.9, 0.1, None) == marsit.EINVAL   # buf aliases grad
+    assert lib.marsit_local_momentum(FAKE, FAKE + 64, FAKE + 64, 2, 64, 32, 0.9, 0.1, None) == marsit.EINVAL   # ld < d
+    assert lib.marsit_local_momentum(FAKE, FAKE + 64, FAKE + 64, 2, 64, 64, float("nan"), 0.1, None) == marsit.EINVAL
+    assert lib.marsit_local_momentum(FAKE, FAKE + 62, FAKE + 64, 2, 64, 64, 0.9, 0.1, None) == marsit.EALIGN
+    assert lib.marsit_local_momentum(FAKE, FAKE + 64, FAKE + 64, 2, 0, 64, 0.9, 0.1, None) == marsit.OK
 
 
 def test_missing_library_fails_loudly(tmp_path):
