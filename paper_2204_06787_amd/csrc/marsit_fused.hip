@@ -573,15 +573,27 @@ full_sync_fast_kernel(const float *__restrict__ g, float *__restrict__ c,
 // -------------------------------------------------------------------------------------------------
 // Launch shapes
 // -------------------------------------------------------------------------------------------------
-// Dynamic LDS bytes per workgroup that leave room for exactly `waves` one-wavefront workgroups of
-// the fused kernel on a CU.  Measured on MI355X (25.6 M elements): the best count is 3 for M = 8
-// and 16, 5 for M = 4, 10 for M = 2 -- about 40 KB of loads in flight per CU, never fewer than 3.
-inline uint32_t throttle_lds_bytes(uint32_t M)
+// One-wavefront workgroups of a fused kernel that should share a CU.  Measured on MI355X at
+// 25.6 M elements, best count per shape: rings 2: 10, 3: 6-7, 4: 5, 5: 4-5, 6: 4, 7 and up: 3;
+// tori 2x2: 5, 3x2 and 2x3: 4, 4x2, 3x3, 4x4: 3 -- about 21/M, i.e. 40-50 KB of loads in flight
+// per CU, never fewer than 3.  The 2x4 torus keeps only two rows of two workers in flight and
+// takes one more (4: 79 % of HBM peak, 3: 73.5 %).
+inline uint32_t fused_waves_per_cu(uint32_t X, uint32_t Y)
 {
-    constexpr uint32_t lds_per_cu = 160u * 1024u;   // gfx950; the runtime attribute reports 64 KB
-    uint32_t waves = (20u + M / 2u) / M;
+    const uint32_t M = X * Y;
+    uint32_t waves = (21u + M / 2u) / M;
     if (waves < 3u)
         waves = 3u;
+    if (X == 2u && Y == 4u)
+        waves = 4u;
+    return waves;
+}
+
+// Dynamic LDS bytes per workgroup that leave room for exactly `waves` one-wavefront workgroups on
+// a CU: the kernels never touch it, it only limits how many of them are resident.
+inline uint32_t throttle_lds_bytes(uint32_t waves)
+{
+    constexpr uint32_t lds_per_cu = 160u * 1024u;   // gfx950; the runtime attribute reports 64 KB
     // a few per cent below an even share: with an exact share one workgroup fewer fits.  At least
     // 3 workgroups per CU keeps the request under the 64 KB a launch may ask for without opting in.
     return ((lds_per_cu / waves) * 31u / 32u) & ~511u;
@@ -604,7 +616,7 @@ void launch_sync_step(const float *g, float *c, float *update, uint32_t *bits32,
                       uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1,
                       const PartTable &parts, hipStream_t stream)
 {
-    const uint32_t lds = throttle_lds_bytes(X * Y);
+    const uint32_t lds = throttle_lds_bytes(fused_waves_per_cu(X, Y));
     const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
     hipLaunchKernelGGL((sync_step_kernel<X, Y>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,
                        update, bits32, n_cols, ld, scale_bits, key0, key1, parts);
@@ -630,7 +642,7 @@ template <int M>
 void launch_full_sync(const float *g, float *c, float *update, uint64_t n_cols, uint64_t ld,
                       hipStream_t stream)
 {
-    const uint32_t lds = throttle_lds_bytes(M);
+    const uint32_t lds = throttle_lds_bytes(fused_waves_per_cu(M, 1));
     const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
     hipLaunchKernelGGL((full_sync_fast_kernel<M>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,
                        update, n_cols, ld);
@@ -641,7 +653,7 @@ void launch_tree_step(const float *g, float *c, float *update, uint32_t *bits32,
                       uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1,
                       hipStream_t stream)
 {
-    const uint32_t lds = throttle_lds_bytes(M);
+    const uint32_t lds = throttle_lds_bytes(fused_waves_per_cu(M, 1));
     const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
     hipLaunchKernelGGL((tree_step_kernel<M>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c, update,
                        bits32, n_cols, ld, scale_bits, key0, key1);
