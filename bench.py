@@ -68,10 +68,20 @@ def cpu_baseline(wl, g_host, seed, threads):
     orc.sync_step(g8, c8, wl.scale, seed, grid_x=wl.grid_x, threads=1)
     dt1 = time.perf_counter() - t0
     bytes8 = 12 * wl.M * d8 + 4 * d8 + d8 // 8
+    cpu_model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
     return {
         "value": gbps, "unit": "GB/s", "cores": threads, "kind": "oracle",
         "sample": f"1 full step of {wl.name} (M={wl.M}, d={wl.d}) on {threads} OpenMP threads",
         "seconds": dt, "worker_elements_per_s": wl.M * wl.d / dt,
+        "cpu_model": cpu_model, "host_cores_visible": os.cpu_count(),
         "single_thread": {"value": bytes8 / dt1 / 1e9, "unit": "GB/s", "seconds": dt1,
                           "sample": f"1 step on the first {d8} columns"},
     }
