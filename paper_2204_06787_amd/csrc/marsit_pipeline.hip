@@ -10,6 +10,11 @@
 // computes the signs of a part right before it needs them, so sign computation overlaps the wait
 // for the incoming segment (Algorithm 1: receive in parallel with the sign step).  The gather period is a no-op here: the last
 // holder writes the final segment where every worker reads it.
+//
+// Torus (grid_x columns): every row runs that ring over its X workers on the X row-parts; the row
+// result of row-part a ends at the worker in column (a + X - 1) mod X.  The Y workers of that column
+// then run a ring over the Y sub-parts of row-part a, operands being the row results, and the last
+// holder of a sub-part writes it to the final bitmap.
 
 #include <hip/hip_runtime.h>
 
