@@ -768,6 +768,32 @@ def test_cascading_compression_is_unbiased_for_the_sum():
     assert np.all(np.abs(acc / n - total) <= 5 * worst / np.sqrt(n))
 
 
+@pytest.mark.parametrize("M,d", [(2, 8), (3, 8), (4, 5)])
+def test_cascading_deviation_grows_like_the_appendix_says(M, d):
+    """Appendix A compares the cascaded result s_3 with the plain mean s_1.  Because Q is unbiased
+    with E||Q(v) - v||^2 = (D - 1) ||v||^2, the expected squared error of the chain obeys
+    e_k = D e_(k-1) + (D - 1) ||S_k||^2 (S_k: sum of the first k workers of the chain), and
+    E||s_3 - s_1||^2 = e_M / M^2 -- the geometric growth in M behind the (2D)^M bound."""
+    rng = np.random.default_rng(60 + M)
+    g = rng.standard_normal((M, d)).astype(np.float32)
+    c = np.zeros_like(g)
+    order = [(M - 1 + h) % M for h in range(M)]          # the only word falls in the last part
+    e, run = 0.0, np.zeros(d)
+    for m in order:
+        run = run + g[m].astype(np.float64)
+        e = d * e + (d - 1) * float(run @ run)
+    expected = e / M ** 2
+    mean = g.astype(np.float64).sum(axis=0) / M
+    n = 8000
+    dev = np.empty(n)
+    for i in range(n):
+        upd, _, _ = orc.cascade_ring_step(g, c, 9000 + i)
+        diff = upd.astype(np.float64) - mean
+        dev[i] = diff @ diff
+    assert abs(dev.mean() - expected) <= 5 * dev.std() / np.sqrt(n)
+    assert dev.mean() <= (2 * d) ** M * max(float(r @ r) for r in g.astype(np.float64)) / M     # the printed bound
+
+
 def test_cascading_matching_rate_is_near_a_coin_flip_and_below_marsit():
     """Fig. 2(b)'s ordering on synthetic data: with a large part the l2 norm swamps every element,
     the stochastic sign is nearly a fair coin, and cascading compression matches the sign of the
