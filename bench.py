@@ -240,9 +240,9 @@ def main():
             torch.cuda.synchronize()
         aux["marsit_pipeline_step"] = {
             "ms_per_step": ms, "streams": M,
-            "launches_per_step": M * X + M * (X - 1) + (M * (Y - 1) if Y > 1 else 0) + M,
+            "launches_per_step": M + M * (X - 1) + M * (Y - 1) + M,
             "hop_steps": X + (Y - 1) + 1,
-            "note": f"{X} compress+send steps, {X - 1} row merge hops, {Y - 1} column merge hops, 1 decode step; "
+            "note": f"1 compress+send step, {X - 1} row hops (sign step fused into the merge), {Y - 1} column hops, 1 decode step; "
                     f"row segments of {8 * ((d // 64) // X)} B"}
         del wsp
         out["other_entry_points"] = aux

@@ -95,6 +95,20 @@ int marsit_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_t *out,
                      uint64_t seed, void *stream);
 
 /*
+ * The sign step and one merge in one launch, for a worker that folds its own signs of a part into
+ * the segment it received (Algorithm 1, sign step followed by the merge of the same part): the result equals
+ * marsit_compress(g, c, tmp, n) followed by marsit_hop_merge(recv, tmp, out, word_begin,
+ * ceil(n/64), fold, hop_id, seed), without storing the local bitmap.
+ *   recv  [ceil(n/64)] received segment (may be NULL when fold == 1);  out may alias recv.
+ *   g, c  [n] the worker's gradient and compensation FROM THE FIRST ELEMENT OF THE PART (element
+ *         64 * word_begin of its vector); c may be NULL.  n: elements of the part (a ragged last
+ *         word is allowed; its bits past n are written as 0).
+ */
+int marsit_compress_hop_merge(const uint64_t *recv, const float *g, const float *c, uint64_t *out,
+                              uint64_t word_begin, uint64_t n, uint32_t fold, uint32_t hop_id,
+                              uint64_t seed, void *stream);
+
+/*
  * marsit_hop_merge with the seed read from DEVICE memory (one 64-bit word, 8-byte aligned) when
  * the kernel runs, not when it is enqueued: a HIP graph that a caller captures around such launches
  * can be replayed with a new seed.  marsit_set_device_seed writes that word with a one-thread kernel on `stream`
@@ -183,9 +197,9 @@ uint64_t marsit_chain_workspace_words(uint32_t M, uint64_t d, uint32_t grid_x);
 /*
  * The ring of Section 4 / Fig. 3 with one HIP stream per worker: every hop of every part is its own
  * launch and waits only for what a real ring waits for -- the segment from the previous worker
- * and the release of its own send buffer.  A worker computes the signs of a part right before it
- * folds them in, so that computation overlaps the wait for the incoming segment (Algorithm 1:
- * receive in parallel with the sign step).  The gather period is simulated: the last holder of a part writes it to bits_out, which
+ * and the release of its own send buffer.  A worker computes the signs of the part it starts before
+ * anything arrives (Algorithm 1: receive in parallel with the sign step); every later hop is one
+ * marsit_compress_hop_merge launch.  The gather period is simulated: the last holder of a part writes it to bits_out, which
  * every worker reads.  marsit_pipeline_step takes grid_x as marsit_ring_step_sim does: on a torus each
  * row runs its ring first; the row result of row-part a ends at column (a + X - 1) mod X, whose Y
  * workers then run the column ring over the Y sub-parts of that row-part.  marsit_pipeline_ring_step

@@ -3,12 +3,15 @@
 // worker, and the previous use of its send buffer being consumed).  On one GPU the "transport" is
 // an event plus a buffer that the next worker reads; with one worker per GPU the same graph has a
 // peer copy where the event is.  Nothing here computes: it sequences marsit_compress,
-// marsit_hop_merge and marsit_decode_compensate.
+// marsit_compress_hop_merge, marsit_hop_merge and marsit_decode_compensate.
 //
 // Schedule (Section 4 of the paper, Fig. 3's reduce period): part i starts at worker i; at hop step
 // h = 1..M-1 worker w folds its own signs of part (w - h) mod M into what worker w-1 sent.  A worker
-// computes the signs of a part right before it needs them, so sign computation overlaps the wait
-// for the incoming segment (Algorithm 1: receive in parallel with the sign step).  The gather period is a no-op here: the last
+// computes the signs of the part it starts before anything arrives (Algorithm 1: the sign step runs
+// in parallel with the receive); for every later part the sign step is fused into the merge
+// (marsit_compress_hop_merge): one launch per hop, and the part's signs are never stored.  On this
+// device a part's sign step is a few microseconds of HBM time, less than a launch.  The gather
+// period is a no-op here: the last
 // holder writes the final segment where every worker reads it.
 //
 // Torus (grid_x columns): every row runs that ring over its X workers on the X row-parts; the row
@@ -214,10 +217,6 @@ int marsit_pipeline_step(marsit_pipeline *p, const float *g, float *c, float *up
                 const uint32_t a = (x + X - h) % X;                 // the row-part that reaches (y, x) now
                 const uint32_t prev = y * X + (x + X - 1) % X, next = y * X + (x + 1) % X;
                 const uint64_t lo = fine[a * Y], n = fine[(a + 1) * Y] - lo;
-                // own signs of that part: overlaps the wait for the incoming segment
-                rc = compress_part(y, x, a);
-                if (rc != MARSIT_OK)
-                    return rc;
                 // the segment from the previous worker of the row has arrived
                 if (!ok(hipStreamWaitEvent(p->worker[w], p->hop[h - 1][prev], 0)))
                     return MARSIT_EHIP;
@@ -231,8 +230,11 @@ int marsit_pipeline_step(marsit_pipeline *p, const float *g, float *c, float *up
                     uint64_t *out = (h == X - 1)
                         ? rowres + static_cast<size_t>(Y > 1 ? y : 0) * W + lo
                         : seg + (static_cast<size_t>(h & 1u) * M + w) * L.rp;
-                    rc = marsit_hop_merge(recv, maps + static_cast<size_t>(w) * W + lo, out, lo, n, h + 1,
-                                          (y << 8) | h, seed, p->worker[w]);
+                    // own signs of that part, computed in the same pass that folds them in
+                    const uint64_t e0 = lo * 64, e1 = ((lo + n) * 64 < d) ? (lo + n) * 64 : d;
+                    rc = marsit_compress_hop_merge(recv, g + static_cast<size_t>(w) * ld + e0,
+                                                   c + static_cast<size_t>(w) * ld + e0, out, lo, e1 - e0,
+                                                   h + 1, (y << 8) | h, seed, p->worker[w]);
                     if (rc != MARSIT_OK)
                         return rc;
                 }

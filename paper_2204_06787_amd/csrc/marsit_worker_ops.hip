@@ -104,6 +104,54 @@ hop_merge_kernel(const uint32_t *recv32, const uint32_t *local32, uint32_t *out3
 }
 
 // -------------------------------------------------------------------------------------------------
+// marsit_compress_hop_merge: the sign step and one merge in one pass.  lane = one column of 4
+// elements = nibble q of packed word i: the local nibble comes from the sign bits of g + c instead
+// of a stored bitmap, the rest is hop_merge_kernel.
+// -------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kBlock)
+compress_hop_merge_kernel(const uint32_t *recv32, const float *__restrict__ g,
+                          const float *__restrict__ c, uint32_t *out32, uint64_t word_begin,
+                          uint64_t n, uint32_t threshold, bool always_local, uint32_t hop_id,
+                          uint32_t key0, uint32_t key1, bool aligned)
+{
+    const uint64_t n_cols = (n + 3) >> 2;
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint64_t i = col >> 4;
+    const uint32_t q = static_cast<uint32_t>(col) & 15u;
+    const size_t half_index = 2u * static_cast<size_t>(i) + (q >> 3);
+    const uint32_t shift = (q & 7u) * 4u;
+    const uint64_t n_words = (n + 63) >> 6;
+    uint32_t nib = 0;
+
+    if (col < n_cols) {
+        const uint64_t e = col << 2;
+        const bool full = e + 4 <= n;
+        const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(n - e);
+        const bool vec = full && aligned;
+        const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+        const f32x4 sv = load4<true>(g + e, vec, n_valid) + ((c != nullptr) ? load4<true>(c + e, vec, n_valid) : zero);
+        uint32_t l = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            l |= (static_cast<uint32_t>(j) < n_valid && (f32_bits(sv[j]) >> 31) == 0u) ? (1u << j) : 0u;
+        const uint32_t r = always_local ? 0u : (recv32[half_index] >> shift) & 0xFu;
+        const uint64_t w = word_begin + i;
+        uint32_t u[4];
+        philox4x32_10(q, hop_id, static_cast<uint32_t>(w), static_cast<uint32_t>(w >> 32), key0,
+                      key1, u);
+        uint32_t t = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            t |= (always_local || u[j] < threshold) ? (1u << j) : 0u;
+        nib = (r ^ ((r ^ l) & t)) & ((1u << n_valid) - 1u);   // t ? l : r; bits past the end stay 0
+    }
+
+    const uint32_t half = half_row_or(nib << shift);
+    if (i < n_words && (q & 7u) == 0u)
+        out32[half_index] = half;
+}
+
+// -------------------------------------------------------------------------------------------------
 // marsit_decode_compensate: lane = one column of 4 elements.
 // -------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kBlock)
@@ -238,6 +286,28 @@ static int launch_hop_merge(const uint64_t *recv, const uint64_t *local, uint64_
                        reinterpret_cast<const uint32_t *>(local), reinterpret_cast<uint32_t *>(out),
                        word_begin, n_words, threshold, always_local, hop_id,
                        static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), seed_ptr);
+    return finish_launch();
+}
+
+int marsit_compress_hop_merge(const uint64_t *recv, const float *g, const float *c, uint64_t *out,
+                              uint64_t word_begin, uint64_t n, uint32_t fold, uint32_t hop_id,
+                              uint64_t seed, void *stream)
+{
+    if (g == nullptr || out == nullptr || fold == 0 || (recv == nullptr && fold != 1) ||
+        n > kMaxElements)
+        return MARSIT_EINVAL;
+    if (!aligned_to(recv, 8) || !aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(out, 8))
+        return MARSIT_EALIGN;
+    if (n == 0)
+        return MARSIT_OK;
+    const bool always_local = (fold == 1);
+    const uint32_t threshold = always_local ? 0xFFFFFFFFu : keep_threshold(fold);
+    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16);
+    const uint64_t n_words = (n + 63) / 64;
+    hipLaunchKernelGGL(compress_hop_merge_kernel, dim3(blocks_for(n_words * 16)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(recv), g, c,
+                       reinterpret_cast<uint32_t *>(out), word_begin, n, threshold, always_local, hop_id,
+                       static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), aligned);
     return finish_launch();
 }
 

@@ -25,7 +25,7 @@ EXPORTS = (
     "marsit_ring_step_sim", "marsit_chain_step_sim", "marsit_chain_workspace_words",
     "marsit_full_sync", "marsit_step", "marsit_apply_update", "marsit_local_momentum",
     "marsit_pipeline_create", "marsit_pipeline_destroy", "marsit_pipeline_workspace_words",
-    "marsit_pipeline_step", "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
+    "marsit_compress_hop_merge", "marsit_pipeline_step", "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
     "marsit_aggregate_sign", "marsit_majority_vote", "marsit_count_matching",
     "marsit_hop_merge_weighted", "marsit_tree_step_sim",
     "marsit_ssdm_cascade_hop", "marsit_cascade_ring_step_sim",
@@ -88,6 +88,8 @@ def load_library(path: str | None = None):
     lib.marsit_pipeline_step.argtypes = [vp, vp, vp, vp, vp, vp, u64, u64, f32, u64, u32, vp]
     lib.marsit_pipeline_step.restype = ci
     lib.marsit_pipeline_ring_step.restype = ci
+    lib.marsit_compress_hop_merge.argtypes = [vp, vp, vp, vp, u64, u64, u32, u32, u64, vp]
+    lib.marsit_compress_hop_merge.restype = ci
     lib.marsit_hop_merge_device_seed.argtypes = [vp, vp, vp, u64, u64, u32, u32, vp, vp]
     lib.marsit_hop_merge_device_seed.restype = ci
     lib.marsit_set_device_seed.argtypes = [vp, u64, vp]
@@ -205,6 +207,16 @@ def marsit_hop_merge(recv, local, out, word_begin: int, n_words_: int, fold: int
     _check("marsit_hop_merge", load_library().marsit_hop_merge(
         _bits_ptr(recv, "recv"), _bits_ptr(local, "local"), _bits_ptr(out, "out"), word_begin,
         n_words_, fold, hop_id, seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
+    return out
+
+
+def marsit_compress_hop_merge(recv, g, c, out, word_begin: int, fold: int, hop_id: int, seed: int,
+                              n: int | None = None, stream=None):
+    """``g``/``c``: the worker's vectors from the first element of the part (1-D views)."""
+    n = g.numel() if n is None else int(n)
+    _check("marsit_compress_hop_merge", load_library().marsit_compress_hop_merge(
+        _bits_ptr(recv, "recv", True), _f32_ptr(g, "g"), _f32_ptr(c, "c", True), _bits_ptr(out, "out"),
+        word_begin, n, fold, hop_id, seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
     return out
 
 

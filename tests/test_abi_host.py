@@ -132,6 +132,12 @@ def test_other_entry_points_argument_validation(lib):
     assert marsit.marsit_chain_workspace_words(16, 25_600_000, 4) == 20 * 400_000
     assert marsit.marsit_chain_workspace_words(6, 100, 4) == 0
 
+    assert lib.marsit_compress_hop_merge(None, FAKE, FAKE, FAKE, 0, 64, 2, 1, 1, None) == marsit.EINVAL   # recv needed
+    assert lib.marsit_compress_hop_merge(FAKE, FAKE, FAKE, FAKE, 0, 64, 0, 1, 1, None) == marsit.EINVAL   # fold 0
+    assert lib.marsit_compress_hop_merge(FAKE, None, FAKE, FAKE, 0, 64, 2, 1, 1, None) == marsit.EINVAL
+    assert lib.marsit_compress_hop_merge(FAKE + 4, FAKE, FAKE, FAKE, 0, 64, 2, 1, 1, None) == marsit.EALIGN
+    assert lib.marsit_compress_hop_merge(FAKE, FAKE, FAKE, FAKE, 0, 0, 2, 1, 1, None) == marsit.OK
+
     assert lib.marsit_pipeline_create(None, 4) == marsit.EINVAL
     assert lib.marsit_pipeline_destroy(None) == marsit.EINVAL
     assert lib.marsit_pipeline_ring_step(None, FAKE, FAKE, FAKE, FAKE, FAKE, 64, 64, 1.0, 1, None) == marsit.EINVAL

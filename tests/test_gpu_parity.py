@@ -366,6 +366,36 @@ def test_ring_pipeline_orders_with_the_callers_stream():
     assert np.array_equal(host_f32(u_copy), want_u)
 
 
+@pytest.mark.parametrize("n", [1, 3, 4, 63, 64, 65, 255, 1000, 64 * 300, 64 * 300 + 17, 1_000_003])
+@pytest.mark.parametrize("fold,offset", [(1, 0), (2, 0), (5, 0), (8, 1)])
+def test_compress_hop_merge(n, fold, offset):
+    """The sign step fused into a merge = the oracle's sign-pack followed by its hop merge, from an
+    aligned and from a misaligned base, with and without compensation, in place over recv."""
+    rng = np.random.default_rng(n * 31 + fold)
+    W = marsit.n_words(n)
+    g_h = rng.standard_normal(n).astype(np.float32)
+    c_h = (0.5 * rng.standard_normal(n)).astype(np.float32)
+    recv_h = rng.integers(0, 2**64, size=W, dtype=np.uint64)
+    if n % 64:
+        recv_h[-1] &= np.uint64((1 << (n % 64)) - 1)
+    word_begin, hop_id, seed = 123_456, (2 << 8) | 3, 0xABCDEF0123
+    for with_c in (True, False):
+        local = orc.sign_pack(orc.add_compensation(g_h, c_h if with_c else np.zeros_like(c_h)))
+        want = orc.hop_merge(recv_h, local, word_begin, fold, hop_id, seed)
+        if offset:
+            g_d = unaligned_rows(1, n, offset)[0]
+            g_d.copy_(dev(g_h))
+            c_d = unaligned_rows(1, n, offset)[0]
+            c_d.copy_(dev(c_h))
+        else:
+            g_d, c_d = dev(g_h), dev(c_h)
+        out = dev(recv_h.copy())                       # in place over the received segment
+        marsit.marsit_compress_hop_merge(out if fold > 1 else None, g_d, c_d if with_c else None, out,
+                                         word_begin, fold, hop_id, seed)
+        torch.cuda.synchronize()
+        assert np.array_equal(host_bits(out), want), (n, fold, with_c)
+
+
 def test_hop_merge_with_the_seed_in_device_memory():
     rng = np.random.default_rng(15)
     n = 3000
