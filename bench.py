@@ -214,6 +214,11 @@ def main():
         # first ~25 launches of a burst 5-8 % slower)
         aux["marsit_full_sync"] = entry(timed(lambda: marsit.marsit_full_sync(grads[0], c3, update, stream=stream),
                                               reps=20, warm=25), 12 * M * d + 4 * d)
+        # one round of Algorithm 2 in one pass (one-bit branch: t = 1, K = 2): model read and written in the fused kernel
+        aux["marsit_step_apply"] = entry(timed(lambda: marsit.marsit_step_apply(
+            1, 2, grads[0], c3, x, None, one_bits, wl.scale, args.seed, grid_x=wl.grid_x, stream=stream),
+            reps=20, warm=25), 12 * M * d + 8 * d + d // 8)
+        c3.zero_()
         aux["marsit_apply_update"] = entry(timed(lambda: marsit.marsit_apply_update(x, update, stream=stream)), 12 * d)
         scaled = torch.empty_like(c3)
         aux["marsit_local_momentum"] = entry(timed(lambda: marsit.marsit_local_momentum(

@@ -246,6 +246,19 @@ int marsit_step(uint64_t t, uint64_t K, const float *g, float *c, float *update_
                 uint64_t seed, uint32_t grid_x, void *stream);
 
 /*
+ * One round of Algorithm 2 in one pass: marsit_step and the model update x[e] <- x[e] - g_t[e] in
+ * the same kernels (x is read and written once; the separate marsit_apply_update pass and, if
+ * update_out is NULL, the write of g_t are saved).  Results equal marsit_step followed by
+ * marsit_apply_update bit for bit.
+ *   x           [d] the model, device memory, updated in place; must not alias update_out.
+ *   update_out  [d] or NULL.
+ * Other arguments as in marsit_step.
+ */
+int marsit_step_apply(uint64_t t, uint64_t K, const float *g, float *c, float *x, float *update_out,
+                      uint64_t *bits_out, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                      uint64_t seed, uint32_t grid_x, void *stream);
+
+/*
  * Diagnostics of Section 3.2.2 / Fig. 2(b).  The matching rate of a sign vector is the share of
  * elements whose sign equals the sign of the non-compressed aggregate.
  *

@@ -44,11 +44,14 @@ struct ThresholdTable {
 // then consume.  The scheduling barriers keep the compiler from sinking the loads next to their
 // uses, which would leave only two loads in flight per wavefront.
 // -------------------------------------------------------------------------------------------------
-template <int X, int Y>
+//
+// APPLY: the model update of Algorithm 2 in the same pass, x <- x - update (x is one more read and
+// one more write stream); `update` may then be NULL.  Without APPLY the kernel never looks at x.
+template <int X, int Y, bool APPLY>
 __global__ void __launch_bounds__(kSyncBlock)
 sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
                  uint32_t *__restrict__ bits32, uint64_t n_cols, uint64_t ld, uint32_t scale_bits,
-                 uint32_t key0, uint32_t key1, PartTable parts)
+                 uint32_t key0, uint32_t key1, PartTable parts, float *__restrict__ x_model)
 {
     constexpr int M = X * Y;
     const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
@@ -87,6 +90,9 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
             }
         };
         fetch_row(0);
+        f32x4 xv = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (APPLY)
+            xv = load4_stream(x_model + e);
         uint32_t pick_col[4] = {0, 0, 0, 0};
 #pragma unroll
         for (int ky = 0; ky < Y; ++ky) {
@@ -149,7 +155,10 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
             upd[j] = __uint_as_float(scale_bits ^ sign);
             nib |= (sign == 0u) ? (1u << j) : 0u;
         }
-        store4_stream(update + e, upd);
+        if (!APPLY || update != nullptr)
+            store4_stream(update + e, upd);
+        if (APPLY)
+            store4_stream(x_model + e, xv - upd);
 
         // compensation update: c <- s - update for every worker
 #pragma unroll
@@ -263,7 +272,7 @@ sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
                          float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
                          uint64_t ld, uint64_t col_begin, uint32_t scale_bits, uint32_t key0,
                          uint32_t key1, uint32_t X, uint32_t Y, bool aligned, PartTable parts,
-                         ThresholdTable thresholds)
+                         ThresholdTable thresholds, float *__restrict__ x_model)
 {
     const uint32_t M = X * Y;
     const uint64_t n_cols = (d + 3) >> 2;
@@ -340,7 +349,13 @@ sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
                 nib |= (sign == 0u) ? (1u << j) : 0u;
             }
         }
-        store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
+        if (update != nullptr)
+            store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
+        if (x_model != nullptr) {
+            // Algorithm 2, model update in the same pass
+            const f32x4 xv = load4(x_model + e, vec, n_valid);
+            store4<MARSIT_STREAMING_STORES>(x_model + e, xv - upd, vec, n_valid);
+        }
 
         if (STAGED)
             compensate_from_stage(c, stage, upd, M, ld, e, vec, n_valid);
@@ -507,7 +522,8 @@ tree_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
 // -------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kBlock)
 full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
-                 uint32_t M, uint64_t d, uint64_t ld, uint64_t col_begin, bool aligned)
+                 uint32_t M, uint64_t d, uint64_t ld, uint64_t col_begin, bool aligned,
+                 float *__restrict__ x_model)
 {
     const uint64_t n_cols = (d + 3) >> 2;
     const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -532,16 +548,22 @@ full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
 #pragma unroll
     for (int j = 0; j < 4; ++j)
         mean[j] = acc[j] / fm;
-    store4<MARSIT_STREAMING_STORES>(update + e, mean, vec, n_valid);
+    if (update != nullptr)
+        store4<MARSIT_STREAMING_STORES>(update + e, mean, vec, n_valid);
+    if (x_model != nullptr) {
+        const f32x4 xv = load4(x_model + e, vec, n_valid);
+        store4<MARSIT_STREAMING_STORES>(x_model + e, xv - mean, vec, n_valid);
+    }
 }
 
 // The same for a compile-time worker count, whole aligned columns only, launched like the fused
 // one-bit kernel (one-wavefront workgroups, all 2M loads issued up front, throttled occupancy):
 // the traffic pattern is the same 2M read streams and M+1 write streams.
-template <int M>
+template <int M, bool APPLY>
 __global__ void __launch_bounds__(kSyncBlock)
 full_sync_fast_kernel(const float *__restrict__ g, float *__restrict__ c,
-                      float *__restrict__ update, uint64_t n_cols, uint64_t ld)
+                      float *__restrict__ update, uint64_t n_cols, uint64_t ld,
+                      float *__restrict__ x_model)
 {
     const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
     if (col >= n_cols)
@@ -553,6 +575,9 @@ full_sync_fast_kernel(const float *__restrict__ g, float *__restrict__ c,
         gv[m] = load4_stream(g + static_cast<size_t>(m) * ld + e);
         cv[m] = load4_stream(c + static_cast<size_t>(m) * ld + e);
     }
+    f32x4 xv = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (APPLY)
+        xv = load4_stream(x_model + e);
     __builtin_amdgcn_sched_barrier(0);
     f32x4 acc = gv[0] + cv[0];
 #pragma unroll
@@ -563,7 +588,10 @@ full_sync_fast_kernel(const float *__restrict__ g, float *__restrict__ c,
 #pragma unroll
     for (int j = 0; j < 4; ++j)
         mean[j] = acc[j] / fm;
-    store4_stream(update + e, mean);
+    if (!APPLY || update != nullptr)
+        store4_stream(update + e, mean);
+    if (APPLY)
+        store4_stream(x_model + e, xv - mean);
     const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int m = 0; m < M; ++m)
@@ -614,16 +642,20 @@ inline uint32_t generic_lds_bytes(uint32_t M)
 template <int X, int Y>
 void launch_sync_step(const float *g, float *c, float *update, uint32_t *bits32, uint64_t n_cols,
                       uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1,
-                      const PartTable &parts, hipStream_t stream)
+                      const PartTable &parts, float *x_model, hipStream_t stream)
 {
     const uint32_t lds = throttle_lds_bytes(fused_waves_per_cu(X, Y));
     const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
-    hipLaunchKernelGGL((sync_step_kernel<X, Y>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,
-                       update, bits32, n_cols, ld, scale_bits, key0, key1, parts);
+    if (x_model == nullptr)
+        hipLaunchKernelGGL((sync_step_kernel<X, Y, false>), dim3(blocks), dim3(kSyncBlock), lds, stream,
+                           g, c, update, bits32, n_cols, ld, scale_bits, key0, key1, parts, x_model);
+    else
+        hipLaunchKernelGGL((sync_step_kernel<X, Y, true>), dim3(blocks), dim3(kSyncBlock), lds, stream,
+                           g, c, update, bits32, n_cols, ld, scale_bits, key0, key1, parts, x_model);
 }
 
 using SyncLauncher = void (*)(const float *, float *, float *, uint32_t *, uint64_t, uint64_t,
-                              uint32_t, uint32_t, uint32_t, const PartTable &, hipStream_t);
+                              uint32_t, uint32_t, uint32_t, const PartTable &, float *, hipStream_t);
 
 // Schedules with a compiled specialisation; every other shape runs the generic kernel.
 SyncLauncher find_specialisation(uint32_t X, uint32_t Y)
@@ -640,12 +672,16 @@ SyncLauncher find_specialisation(uint32_t X, uint32_t Y)
 
 template <int M>
 void launch_full_sync(const float *g, float *c, float *update, uint64_t n_cols, uint64_t ld,
-                      hipStream_t stream)
+                      float *x_model, hipStream_t stream)
 {
     const uint32_t lds = throttle_lds_bytes(fused_waves_per_cu(M, 1));
     const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
-    hipLaunchKernelGGL((full_sync_fast_kernel<M>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,
-                       update, n_cols, ld);
+    if (x_model == nullptr)
+        hipLaunchKernelGGL((full_sync_fast_kernel<M, false>), dim3(blocks), dim3(kSyncBlock), lds, stream,
+                           g, c, update, n_cols, ld, x_model);
+    else
+        hipLaunchKernelGGL((full_sync_fast_kernel<M, true>), dim3(blocks), dim3(kSyncBlock), lds, stream,
+                           g, c, update, n_cols, ld, x_model);
 }
 
 template <int M>
@@ -679,7 +715,7 @@ TreeLauncher find_tree(uint32_t M)
     }
 }
 
-using FullSyncLauncher = void (*)(const float *, float *, float *, uint64_t, uint64_t, hipStream_t);
+using FullSyncLauncher = void (*)(const float *, float *, float *, uint64_t, uint64_t, float *, hipStream_t);
 
 FullSyncLauncher find_full_sync(uint32_t M)
 {
@@ -702,13 +738,13 @@ FullSyncLauncher find_full_sync(uint32_t M)
 
 using namespace marsit;
 
-extern "C" {
-
-int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
-                         uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed,
-                         uint32_t grid_x, void *stream)
+// The one-bit pass; x_model != NULL: with the model update x <- x - update in the same kernels
+// (update_out may then be NULL).
+static int ring_step_impl(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                          float *x_model, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                          uint64_t seed, uint32_t grid_x, void *stream)
 {
-    if (g == nullptr || c == nullptr || update_out == nullptr || M == 0 ||
+    if (g == nullptr || c == nullptr || (update_out == nullptr && x_model == nullptr) || M == 0 ||
         M > MARSIT_MAX_WORKERS || ld < d || !std::isfinite(scale) || d > kMaxElements)
         return MARSIT_EINVAL;
     const uint32_t X = (grid_x == 0) ? M : grid_x;
@@ -716,7 +752,7 @@ int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *
         return MARSIT_EINVAL;
     const uint32_t Y = M / X;
     if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(update_out, 4) ||
-        !aligned_to(bits_out, 8))
+        !aligned_to(bits_out, 8) || !aligned_to(x_model, 4))
         return MARSIT_EALIGN;
     if (d == 0)
         return MARSIT_OK;
@@ -729,7 +765,7 @@ int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *
         parts.bound[k] = static_cast<uint32_t>(k <= M ? bounds[k] : n_words);
 
     const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
-                         (ld % 4 == 0);
+                         aligned_to(x_model, 16) && (ld % 4 == 0);
     const uint32_t scale_bits = float_bits_host(scale);
     const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
     uint32_t *bits32 = reinterpret_cast<uint32_t *>(bits_out);
@@ -743,7 +779,7 @@ int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *
     if (fast != nullptr) {
         const uint64_t fast_cols = (d / 64) * 16;
         if (fast_cols > 0) {
-            fast(g, c, update_out, bits32, fast_cols, ld, scale_bits, key0, key1, parts, s);
+            fast(g, c, update_out, bits32, fast_cols, ld, scale_bits, key0, key1, parts, x_model, s);
             const int rc = finish_launch();
             if (rc != MARSIT_OK)
                 return rc;
@@ -762,14 +798,58 @@ int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *
         if (M <= kMaxStagedWorkers)
             hipLaunchKernelGGL(sync_step_generic_kernel<true>, dim3(blocks), dim3(kSyncBlock),
                                generic_lds_bytes(M), s, g, c, update_out, bits32, d, ld,
-                               generic_col_begin, scale_bits, key0, key1, X, Y, aligned, parts, thresholds);
+                               generic_col_begin, scale_bits, key0, key1, X, Y, aligned, parts, thresholds,
+                               x_model);
         else
             hipLaunchKernelGGL(sync_step_generic_kernel<false>, dim3(blocks), dim3(kSyncBlock), 0, s, g, c,
                                update_out, bits32, d, ld, generic_col_begin, scale_bits, key0, key1, X, Y,
-                               aligned, parts, thresholds);
+                               aligned, parts, thresholds, x_model);
         return finish_launch();
     }
     return MARSIT_OK;
+}
+
+// The full-precision round; x_model as in ring_step_impl.
+static int full_sync_impl(const float *g, float *c, float *update_out, float *x_model, uint32_t M,
+                          uint64_t d, uint64_t ld, void *stream)
+{
+    if (g == nullptr || c == nullptr || (update_out == nullptr && x_model == nullptr) || M == 0 ||
+        M > MARSIT_MAX_WORKERS || ld < d || d > kMaxElements)
+        return MARSIT_EINVAL;
+    if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(update_out, 4) || !aligned_to(x_model, 4))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
+                         aligned_to(x_model, 16) && (ld % 4 == 0);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    uint64_t col_begin = 0;
+    const FullSyncLauncher fast = aligned ? find_full_sync(M) : nullptr;
+    if (fast != nullptr && d >= 4) {
+        col_begin = d / 4;
+        fast(g, c, update_out, col_begin, ld, x_model, s);
+        const int rc = finish_launch();
+        if (rc != MARSIT_OK)
+            return rc;
+    }
+    const uint64_t n_cols = (d + 3) >> 2;
+    if (col_begin < n_cols) {
+        hipLaunchKernelGGL(full_sync_kernel, dim3(blocks_for(n_cols - col_begin)), dim3(kBlock), 0, s,
+                           g, c, update_out, M, d, ld, col_begin, aligned, x_model);
+        return finish_launch();
+    }
+    return MARSIT_OK;
+}
+
+extern "C" {
+
+int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                         uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed,
+                         uint32_t grid_x, void *stream)
+{
+    if (update_out == nullptr)
+        return MARSIT_EINVAL;
+    return ring_step_impl(g, c, update_out, bits_out, nullptr, M, d, ld, scale, seed, grid_x, stream);
 }
 
 int marsit_tree_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
@@ -825,32 +905,9 @@ int marsit_tree_step_sim(const float *g, float *c, float *update_out, uint64_t *
 int marsit_full_sync(const float *g, float *c, float *update_out, uint32_t M, uint64_t d,
                      uint64_t ld, void *stream)
 {
-    if (g == nullptr || c == nullptr || update_out == nullptr || M == 0 ||
-        M > MARSIT_MAX_WORKERS || ld < d || d > kMaxElements)
+    if (update_out == nullptr)
         return MARSIT_EINVAL;
-    if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(update_out, 4))
-        return MARSIT_EALIGN;
-    if (d == 0)
-        return MARSIT_OK;
-    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
-                         (ld % 4 == 0);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    uint64_t col_begin = 0;
-    const FullSyncLauncher fast = aligned ? find_full_sync(M) : nullptr;
-    if (fast != nullptr && d >= 4) {
-        col_begin = d / 4;
-        fast(g, c, update_out, col_begin, ld, s);
-        const int rc = finish_launch();
-        if (rc != MARSIT_OK)
-            return rc;
-    }
-    const uint64_t n_cols = (d + 3) >> 2;
-    if (col_begin < n_cols) {
-        hipLaunchKernelGGL(full_sync_kernel, dim3(blocks_for(n_cols - col_begin)), dim3(kBlock), 0, s,
-                           g, c, update_out, M, d, ld, col_begin, aligned);
-        return finish_launch();
-    }
-    return MARSIT_OK;
+    return full_sync_impl(g, c, update_out, nullptr, M, d, ld, stream);
 }
 
 int marsit_step(uint64_t t, uint64_t K, const float *g, float *c, float *update_out,
@@ -867,6 +924,21 @@ int marsit_step(uint64_t t, uint64_t K, const float *g, float *c, float *update_
     if (!aligned_to(bits_out, 8))
         return MARSIT_EALIGN;
     return marsit_full_sync(g, c, update_out, M, d, ld, stream);
+}
+
+int marsit_step_apply(uint64_t t, uint64_t K, const float *g, float *c, float *x, float *update_out,
+                      uint64_t *bits_out, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                      uint64_t seed, uint32_t grid_x, void *stream)
+{
+    if (K == 0 || x == nullptr || x == update_out)
+        return MARSIT_EINVAL;
+    if (t % K != 0)
+        return ring_step_impl(g, c, update_out, bits_out, x, M, d, ld, scale, seed, grid_x, stream);
+    if (!std::isfinite(scale) || (grid_x != 0 && (M == 0 || M % grid_x != 0)))
+        return MARSIT_EINVAL;
+    if (!aligned_to(bits_out, 8))
+        return MARSIT_EALIGN;
+    return full_sync_impl(g, c, update_out, x, M, d, ld, stream);
 }
 
 }   // extern "C"

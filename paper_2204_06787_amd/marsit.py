@@ -23,7 +23,7 @@ EXPORTS = (
     "marsit_version", "marsit_last_hip_error", "marsit_status_string", "marsit_philox4x32_10",
     "marsit_split_bounds", "marsit_compress", "marsit_hop_merge", "marsit_decode_compensate",
     "marsit_ring_step_sim", "marsit_chain_step_sim", "marsit_chain_workspace_words",
-    "marsit_full_sync", "marsit_step", "marsit_apply_update", "marsit_local_momentum",
+    "marsit_full_sync", "marsit_step", "marsit_step_apply", "marsit_apply_update", "marsit_local_momentum",
     "marsit_pipeline_create", "marsit_pipeline_destroy", "marsit_pipeline_workspace_words",
     "marsit_compress_hop_merge", "marsit_pipeline_step", "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
     "marsit_aggregate_sign", "marsit_majority_vote", "marsit_count_matching",
@@ -114,6 +114,8 @@ def load_library(path: str | None = None):
     lib.marsit_full_sync.restype = ci
     lib.marsit_step.argtypes = [u64, u64, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
     lib.marsit_step.restype = ci
+    lib.marsit_step_apply.argtypes = [u64, u64, vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
+    lib.marsit_step_apply.restype = ci
     lib.marsit_apply_update.argtypes = [vp, vp, u64, vp]
     lib.marsit_apply_update.restype = ci
     lib.marsit_local_momentum.argtypes = [vp, vp, vp, u32, u64, u64, f32, f32, vp]
@@ -355,6 +357,22 @@ def marsit_step(t: int, K: int, g, c, update_out, bits_out, scale: float, seed: 
         _bits_ptr(bits_out, "bits_out", True), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF, grid_x,
         _stream(stream)))
     return update_out, bits_out
+
+
+def marsit_step_apply(t: int, K: int, g, c, x, update_out, bits_out, scale: float, seed: int,
+                      grid_x: int = 0, d: int | None = None, stream=None):
+    """``marsit_step`` with the model update ``x -= g_t`` in the same pass; ``update_out`` may be None."""
+    M, ld = _rows(g, "g")
+    if _rows(c, "c") != (M, ld):
+        raise TypeError("g and c must have the same shape and row stride")
+    d = g.shape[1] if d is None else int(d)
+    if x.numel() < d or (update_out is not None and update_out.numel() < d):
+        raise ValueError("x / update_out shorter than d")
+    _check("marsit_step_apply", load_library().marsit_step_apply(
+        t, K, _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(x, "x"), _f32_ptr(update_out, "update_out", True),
+        _bits_ptr(bits_out, "bits_out", True), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF, grid_x,
+        _stream(stream)))
+    return x
 
 
 def marsit_apply_update(x, update, d: int | None = None, stream=None):

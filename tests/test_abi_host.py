@@ -173,6 +173,14 @@ def test_other_entry_points_argument_validation(lib):
     assert lib.marsit_hop_merge_device_seed(FAKE, FAKE, FAKE, 0, 10, 2, 1, FAKE + 4, None) == marsit.EALIGN
     assert lib.marsit_set_device_seed(None, 5, None) == marsit.EINVAL
 
+    assert lib.marsit_step_apply(1, 4, FAKE, FAKE, None, FAKE, FAKE, 4, 64, 64, 1.0, 1, 0, None) == marsit.EINVAL   # no model
+    assert lib.marsit_step_apply(1, 0, FAKE, FAKE, FAKE, FAKE + 1024, FAKE, 4, 64, 64, 1.0, 1, 0, None) == marsit.EINVAL   # K = 0
+    assert lib.marsit_step_apply(1, 4, FAKE, FAKE, FAKE, FAKE, FAKE, 4, 64, 64, 1.0, 1, 0, None) == marsit.EINVAL   # x aliases update
+    assert lib.marsit_step_apply(1, 4, FAKE, FAKE, FAKE + 2, None, FAKE, 4, 64, 64, 1.0, 1, 0, None) == marsit.EALIGN
+    assert lib.marsit_step_apply(0, 4, FAKE, FAKE, FAKE + 2, None, FAKE, 4, 64, 64, 1.0, 1, 0, None) == marsit.EALIGN
+    assert lib.marsit_step_apply(1, 4, FAKE, FAKE, FAKE, None, FAKE, 4, 64, 64, 1.0, 1, 3, None) == marsit.EINVAL   # 3 does not divide 4
+    assert lib.marsit_step_apply(1, 4, FAKE, FAKE, FAKE, None, None, 4, 0, 64, 1.0, 1, 0, None) == marsit.OK
+    assert lib.marsit_step_apply(0, 4, FAKE, FAKE, FAKE, None, None, 4, 0, 64, 1.0, 1, 0, None) == marsit.OK
     assert lib.marsit_apply_update(None, FAKE, 64, None) == marsit.EINVAL
     assert lib.marsit_apply_update(FAKE, FAKE, 0, None) == marsit.OK
     assert lib.marsit_local_momentum(FAKE, FAKE + 64, None, 2, 64, 64, 0.9, 0.1, None) == marsit.EINVAL

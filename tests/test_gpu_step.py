@@ -133,6 +133,74 @@ def test_sgd_driver_with_local_momentum():
             assert np.array_equal(host_f32(opt.update), u_h), t
 
 
+@pytest.mark.parametrize("M,grid_x,d,ld,offset", [
+    (8, 0, 70_001, 70_004, 0), (16, 4, 33_000, 33_000, 0), (3, 0, 64 * 5, 64 * 5, 0), (9, 0, 4099, 4100, 0),
+    (6, 3, 1000, 1000, 0), (5, 0, 2000, 2001, 0), (8, 0, 777, 780, 1), (1, 0, 130, 132, 0), (48, 0, 300, 300, 0)])
+@pytest.mark.parametrize("keep_update", [True, False])
+def test_step_apply(M, grid_x, d, ld, offset, keep_update):
+    """A round with the model update in the same pass: compiled and generic schedules, ragged
+    tails, padded and misaligned rows, one-bit and full-precision rounds (K = 3, t = 0..4)."""
+    K, scale, seed0 = 3, 2e-3, 77
+    rng = np.random.default_rng(M * 100 + d)
+    x_h = rng.standard_normal(d).astype(np.float32)
+    c_h = np.zeros((M, ld), dtype=np.float32)
+    if offset:
+        c_d = unaligned_rows(M, ld, offset)
+        x_d = torch.zeros(d + 8, dtype=torch.float32, device="cuda")[offset:offset + d]
+        x_d.copy_(dev(x_h))
+    else:
+        c_d = torch.zeros((M, ld), dtype=torch.float32, device="cuda")
+        x_d = dev(x_h)
+    u_d = torch.full((d,), 7.0, dtype=torch.float32, device="cuda") if keep_update else None
+    bits = marsit.new_bitmap(d)
+    x_tol = np.zeros(d)
+    for t in range(5):
+        g_h = (0.01 * rng.standard_normal((M, ld))).astype(np.float32)
+        if offset:
+            g_d = unaligned_rows(M, ld, offset)
+            g_d.copy_(dev(g_h))
+        else:
+            g_d = dev(g_h)
+        marsit.marsit_step_apply(t, K, g_d, c_d, x_d, u_d, bits, scale, seed0 + t, grid_x=grid_x, d=d)
+        torch.cuda.synchronize()
+        u_tol = None
+        if t % K == 0:
+            s64 = g_h[:, :d].astype(np.float64) + c_h[:, :d]
+            want_u = orc.full_sync(g_h, c_h, d=d)
+            u_tol = _mean_tolerance(s64, M) + np.spacing(np.abs(want_u))
+            if keep_update:
+                assert np.all(np.abs(host_f32(u_d).astype(np.float64) - want_u) <= u_tol), t
+        else:
+            want_u, want_b, _ = orc.sync_step(g_h, c_h, scale, seed0 + t, grid_x=grid_x, d=d)
+            assert np.array_equal(host_bits(bits), want_b), t
+            if keep_update:
+                assert np.array_equal(host_f32(u_d), want_u), t
+        x_h = orc.apply_update(x_h, want_u)
+        x_tol = _advance_model_tolerance(x_tol, x_h, u_tol)
+        assert np.all(np.abs(host_f32(x_d).astype(np.float64) - x_h) <= x_tol), t
+        assert_f32_parity(host_f32(c_d)[:, :d], c_h[:, :d], f"compensation, round {t}")
+        assert np.array_equal(host_f32(c_d)[:, d:], c_h[:, d:])                     # padding untouched
+
+
+def test_step_apply_equals_step_then_apply_update_bit_for_bit():
+    """Against the two-call form on the device (both HIP): identical model, compensation, bitmap."""
+    M, d, K = 8, 300_000 + 37, 4
+    rng = np.random.default_rng(8)
+    x0 = dev(rng.standard_normal(d).astype(np.float32))
+    xa, xb = x0.clone(), x0.clone()
+    ca = torch.zeros((M, d), dtype=torch.float32, device="cuda")
+    cb = torch.zeros_like(ca)
+    ua = torch.empty(d, dtype=torch.float32, device="cuda")
+    ba, bb = marsit.new_bitmap(d).zero_(), marsit.new_bitmap(d).zero_()     # a full-precision round leaves them alone
+    for t in range(6):
+        g = dev((0.02 * rng.standard_normal((M, d))).astype(np.float32))
+        marsit.marsit_step(t, K, g, ca, ua, ba, 1e-3, 900 + t)
+        marsit.marsit_apply_update(xa, ua)
+        marsit.marsit_step_apply(t, K, g, cb, xb, None, bb, 1e-3, 900 + t)
+        torch.cuda.synchronize()
+        assert torch.equal(xa, xb) and torch.equal(ca, cb) and torch.equal(ba, bb), t
+
+
 @pytest.mark.parametrize("M,grid_x,K", [(8, 0, 4), (16, 4, 3), (3, 0, 1), (5, 0, 100)])
 def test_marsit_driven_sgd_loop(M, grid_x, K):
     """Algorithm 2 with Algorithm 1 inside: T rounds, a full-precision round whenever t mod K == 0,
