@@ -229,6 +229,8 @@ def main():
                                        8 * d + d // 8)
         aux["marsit_decode_compensate"] = entry(timed(lambda: marsit.marsit_decode_compensate(
             one_bits, grads[0][0], c3[0], wl.scale, update, c3[0], stream=stream)), 16 * d + d // 8)
+        aux["marsit_decode_compensate_apply"] = entry(timed(lambda: marsit.marsit_decode_compensate_apply(
+            one_bits, grads[0][0], c3[0], wl.scale, x, None, c3[0], stream=stream)), 20 * d + d // 8)
         seg = (d // 64) // M
         aux["marsit_hop_merge"] = entry(timed(lambda: marsit.marsit_hop_merge(
             one_bits[:seg], bits[:seg], one_bits[:seg], 0, seg, 3, 2, args.seed, stream=stream)), 24 * seg)

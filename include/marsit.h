@@ -132,6 +132,16 @@ int marsit_decode_compensate(const uint64_t *bits, const float *g, const float *
                              float *update_out, float *c_out, uint64_t d, void *stream);
 
 /*
+ * marsit_decode_compensate with the model update of Algorithm 2 in the same pass:
+ * x[e] <- x[e] - update[e].  This is what one worker runs after the gather period: its gradient,
+ * compensation and model are each read once, compensation and model written once (20 bytes per
+ * element instead of 28 for the two separate passes).  x [d] must not alias the outputs;
+ * update_out may be NULL.  Results equal marsit_decode_compensate followed by marsit_apply_update.
+ */
+int marsit_decode_compensate_apply(const uint64_t *bits, const float *g, const float *c, float scale,
+                                   float *x, float *update_out, float *c_out, uint64_t d, void *stream);
+
+/*
  * The whole one-bit pass (Algorithm 1, the branch mod(t,K) != 0) for M workers simulated inside one
  * device, fused in one kernel: compensate, sign, the M-1 merges of every part's chain, decode,
  * global compensation.  Results are bit-identical to chaining marsit_compress, marsit_hop_merge

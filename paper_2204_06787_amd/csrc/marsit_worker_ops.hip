@@ -157,7 +157,7 @@ compress_hop_merge_kernel(const uint32_t *recv32, const float *__restrict__ g,
 __global__ void __launch_bounds__(kBlock)
 decode_compensate_kernel(const uint32_t *__restrict__ bits32, const float *__restrict__ g,
                          const float *c, float *__restrict__ update, float *c_out, uint64_t d,
-                         uint32_t scale_bits, bool aligned)
+                         uint32_t scale_bits, bool aligned, float *__restrict__ x_model)
 {
     const uint64_t n_cols = (d + 3) >> 2;
     const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -177,6 +177,11 @@ decode_compensate_kernel(const uint32_t *__restrict__ bits32, const float *__res
         upd[j] = __uint_as_float(scale_bits ^ (((nib >> j) & 1u) ? 0u : 0x80000000u));
     if (update != nullptr)
         store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
+    if (x_model != nullptr) {
+        // Algorithm 2, model update in the same pass
+        const f32x4 xv = load4(x_model + e, vec, n_valid);
+        store4<MARSIT_STREAMING_STORES>(x_model + e, xv - upd, vec, n_valid);
+    }
     store4<MARSIT_STREAMING_STORES>(c_out + e, sv - upd, vec, n_valid);
 }
 
@@ -352,23 +357,37 @@ int marsit_hop_merge_weighted(const uint64_t *recv, const uint64_t *local, uint6
     return launch_hop_merge(recv, local, out, word_begin, n_words, w_recv, w_local, hop_id, seed, stream);
 }
 
-int marsit_decode_compensate(const uint64_t *bits, const float *g, const float *c, float scale,
-                             float *update_out, float *c_out, uint64_t d, void *stream)
+static int decode_impl(const uint64_t *bits, const float *g, const float *c, float scale,
+                       float *update_out, float *c_out, float *x_model, uint64_t d, void *stream)
 {
     if (bits == nullptr || g == nullptr || c_out == nullptr || !std::isfinite(scale) ||
         d > kMaxElements)
         return MARSIT_EINVAL;
     if (!aligned_to(bits, 8) || !aligned_to(g, 4) || !aligned_to(c, 4) ||
-        !aligned_to(update_out, 4) || !aligned_to(c_out, 4))
+        !aligned_to(update_out, 4) || !aligned_to(c_out, 4) || !aligned_to(x_model, 4))
         return MARSIT_EALIGN;
     if (d == 0)
         return MARSIT_OK;
     const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
-                         aligned_to(c_out, 16);
+                         aligned_to(c_out, 16) && aligned_to(x_model, 16);
     hipLaunchKernelGGL(decode_compensate_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock), 0,
                        static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(bits), g,
-                       c, update_out, c_out, d, float_bits_host(scale), aligned);
+                       c, update_out, c_out, d, float_bits_host(scale), aligned, x_model);
     return finish_launch();
+}
+
+int marsit_decode_compensate(const uint64_t *bits, const float *g, const float *c, float scale,
+                             float *update_out, float *c_out, uint64_t d, void *stream)
+{
+    return decode_impl(bits, g, c, scale, update_out, c_out, nullptr, d, stream);
+}
+
+int marsit_decode_compensate_apply(const uint64_t *bits, const float *g, const float *c, float scale,
+                                   float *x, float *update_out, float *c_out, uint64_t d, void *stream)
+{
+    if (x == nullptr || x == update_out || x == c_out)
+        return MARSIT_EINVAL;
+    return decode_impl(bits, g, c, scale, update_out, c_out, x, d, stream);
 }
 
 uint64_t marsit_chain_workspace_words(uint32_t M, uint64_t d, uint32_t grid_x)

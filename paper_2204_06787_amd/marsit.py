@@ -25,7 +25,7 @@ EXPORTS = (
     "marsit_ring_step_sim", "marsit_chain_step_sim", "marsit_chain_workspace_words",
     "marsit_full_sync", "marsit_step", "marsit_step_apply", "marsit_apply_update", "marsit_local_momentum",
     "marsit_pipeline_create", "marsit_pipeline_destroy", "marsit_pipeline_workspace_words",
-    "marsit_compress_hop_merge", "marsit_pipeline_step", "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
+    "marsit_compress_hop_merge", "marsit_decode_compensate_apply", "marsit_pipeline_step", "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
     "marsit_aggregate_sign", "marsit_majority_vote", "marsit_count_matching",
     "marsit_hop_merge_weighted", "marsit_tree_step_sim",
     "marsit_ssdm_cascade_hop", "marsit_cascade_ring_step_sim",
@@ -114,6 +114,8 @@ def load_library(path: str | None = None):
     lib.marsit_full_sync.restype = ci
     lib.marsit_step.argtypes = [u64, u64, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
     lib.marsit_step.restype = ci
+    lib.marsit_decode_compensate_apply.argtypes = [vp, vp, vp, f32, vp, vp, vp, u64, vp]
+    lib.marsit_decode_compensate_apply.restype = ci
     lib.marsit_step_apply.argtypes = [u64, u64, vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
     lib.marsit_step_apply.restype = ci
     lib.marsit_apply_update.argtypes = [vp, vp, u64, vp]
@@ -244,6 +246,18 @@ def marsit_decode_compensate(bits, g, c, scale: float, update_out, c_out, d: int
         _bits_ptr(bits, "bits"), _f32_ptr(g, "g"), _f32_ptr(c, "c", True), scale,
         _f32_ptr(update_out, "update_out", True), _f32_ptr(c_out, "c_out"), d, _stream(stream)))
     return update_out, c_out
+
+
+def marsit_decode_compensate_apply(bits, g, c, scale: float, x, update_out, c_out, d: int | None = None,
+                                   stream=None):
+    """``marsit_decode_compensate`` with the model update ``x -= update`` in the same pass."""
+    d = g.numel() if d is None else int(d)
+    if x.numel() < d:
+        raise ValueError("x shorter than d")
+    _check("marsit_decode_compensate_apply", load_library().marsit_decode_compensate_apply(
+        _bits_ptr(bits, "bits"), _f32_ptr(g, "g"), _f32_ptr(c, "c", True), scale, _f32_ptr(x, "x"),
+        _f32_ptr(update_out, "update_out", True), _f32_ptr(c_out, "c_out"), d, _stream(stream)))
+    return x, c_out
 
 
 def marsit_ring_step_sim(g, c, update_out, bits_out, scale: float, seed: int, grid_x: int = 0,

@@ -138,6 +138,11 @@ def test_other_entry_points_argument_validation(lib):
     assert lib.marsit_compress_hop_merge(FAKE + 4, FAKE, FAKE, FAKE, 0, 64, 2, 1, 1, None) == marsit.EALIGN
     assert lib.marsit_compress_hop_merge(FAKE, FAKE, FAKE, FAKE, 0, 0, 2, 1, 1, None) == marsit.OK
 
+    assert lib.marsit_decode_compensate_apply(FAKE, FAKE, FAKE, 1.0, None, FAKE, FAKE, 64, None) == marsit.EINVAL
+    assert lib.marsit_decode_compensate_apply(FAKE, FAKE, FAKE, 1.0, FAKE, FAKE, FAKE + 1024, 64, None) == marsit.EINVAL   # x aliases update
+    assert lib.marsit_decode_compensate_apply(FAKE, FAKE, FAKE, 1.0, FAKE + 2, None, FAKE, 64, None) == marsit.EALIGN
+    assert lib.marsit_decode_compensate_apply(FAKE, FAKE, FAKE, 1.0, FAKE + 1024, None, FAKE, 0, None) == marsit.OK
+
     assert lib.marsit_pipeline_create(None, 4) == marsit.EINVAL
     assert lib.marsit_pipeline_destroy(None) == marsit.EINVAL
     assert lib.marsit_pipeline_ring_step(None, FAKE, FAKE, FAKE, FAKE, FAKE, 64, 64, 1.0, 1, None) == marsit.EINVAL

@@ -139,6 +139,39 @@ def test_decode_compensate(d, offset):
     assert_f32_parity(host_f32(out), want_c0, "c_out (c = NULL)")
 
 
+@pytest.mark.parametrize("d", [1, 3, 4, 5, 63, 64, 65, 1023, 4100, 100_003])
+@pytest.mark.parametrize("offset", [0, 1])
+def test_decode_compensate_apply(d, offset):
+    """Decode, compensation update and model update in one pass = the oracle's three steps."""
+    rng = np.random.default_rng(d + 7)
+    g, c = _inputs(1, d + 1, seed=5)
+    g1 = np.ascontiguousarray(g[0, offset:offset + d])
+    c1 = np.ascontiguousarray(c[0, offset:offset + d])
+    x1 = rng.standard_normal(d).astype(np.float32)
+    bits = rng.integers(0, 2**64, size=orc.n_words(d), dtype=np.uint64)
+    scale = 2.5e-3
+    want_u = orc.decode(bits, scale, d)
+    want_c = orc.compensate(orc.add_compensation(g1, c1), want_u)
+    want_x = orc.apply_update(x1.copy(), want_u)
+
+    buf = [torch.zeros(d + 1, dtype=torch.float32, device="cuda") for _ in range(4)]
+    gv, cv, xv, uv = (b[offset:offset + d] for b in buf)
+    gv.copy_(dev(g1))
+    cv.copy_(dev(c1))
+    xv.copy_(dev(x1))
+    marsit.marsit_decode_compensate_apply(dev(bits), gv, cv, scale, xv, uv, cv, d=d)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_f32(uv).view(np.uint32), want_u.view(np.uint32))
+    assert_f32_parity(host_f32(cv), want_c, "c_out")
+    assert_f32_parity(host_f32(xv), want_x, "x")
+    # without the update output: a second application moves the model once more
+    cv.copy_(dev(c1))
+    marsit.marsit_decode_compensate_apply(dev(bits), gv, cv, scale, xv, None, cv, d=d)
+    torch.cuda.synchronize()
+    assert_f32_parity(host_f32(xv), orc.apply_update(want_x.copy(), want_u), "x (second round)")
+    assert_f32_parity(host_f32(cv), want_c, "c_out (second round)")
+
+
 # ------------------------------------------------------------------------------------------------
 # fused pass vs oracle
 # ------------------------------------------------------------------------------------------------
