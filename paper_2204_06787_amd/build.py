@@ -50,5 +50,25 @@ def build_library(force: bool = True, extra_flags=(), out: str | None = None) ->
     return out
 
 
+C_CLIENT_SRC = os.path.join(ROOT, "tests", "helpers", "abi_c_client.c")
+C_CLIENT = os.path.join(ROOT, "tests", "helpers", "abi_c_client")
+
+
+def build_c_client(rocm: str = "/opt/rocm") -> str:
+    """Compile the plain-C test client of the ABI with gcc and link it against the built library."""
+    if not os.path.exists(LIB):
+        raise RuntimeError("build the HIP library first")
+    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(rocm, "include"), "-I", os.path.join(ROOT, "include"), C_CLIENT_SRC,
+           "-o", C_CLIENT, "-L", PKG, "-lmarsit", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN/../../paper_2204_06787_amd", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    if proc.returncode != 0:
+        sys.stderr.write(proc.stdout + proc.stderr)
+        raise RuntimeError("gcc failed: " + " ".join(cmd))
+    return C_CLIENT
+
+
 if __name__ == "__main__":
     print(build_library(force=True))
+    print(build_c_client())

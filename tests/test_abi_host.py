@@ -210,3 +210,17 @@ def test_product_does_not_import_the_oracle():
                 assert "oracle" not in text.lower() or name == "workloads.py", name
     text = open(os.path.join(pkg, "workloads.py")).read()
     assert "import oracle" not in text and "from oracle" not in text
+
+
+def test_header_is_valid_c(tmp_path):
+    """include/marsit.h compiles as plain C11 (the boundary has no C++ in it)."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "marsit.h"\nint main(void) { return marsit_version() == 0; }\n')
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    proc = subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                           "-I", os.path.join(root, "include"), str(src)], capture_output=True, text=True)
+    assert proc.returncode == 0, proc.stderr
