@@ -27,8 +27,8 @@ HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, vendor figure
 # WRITE_SIZE runs scaled by a copy kernel of known size (figures and commands: profiles/).
 # None where no counter run has been made for that workload.
 MEASURED_TRAFFIC_BYTES = {
-    "resnet50": 2_563_184_321,   # profiles/sync_step_kernel_resnet50_hbm_traffic.txt
-    "torus4x4": 5_020_849_151,   # profiles/sync_step_kernel_torus4x4_hbm_traffic.txt
+    "resnet50": 2_563_238_687,   # profiles/sync_step_kernel_resnet50_hbm_traffic.txt
+    "torus4x4": 5_020_856_830,   # profiles/sync_step_kernel_torus4x4_hbm_traffic.txt
 }
 
 
