@@ -224,3 +224,16 @@ def test_header_is_valid_c(tmp_path):
     proc = subprocess.run(["gcc", "-std=c11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
                            "-I", os.path.join(root, "include"), str(src)], capture_output=True, text=True)
     assert proc.returncode == 0, proc.stderr
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py times one GPU's share; asking for more exits with a message that says so (before
+    anything touches a GPU)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    proc = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                          capture_output=True, text=True, timeout=120)
+    assert proc.returncode != 0
+    assert "ONE GPU" in proc.stderr and "--gpus must be 1" in proc.stderr
+    assert proc.stdout.strip() == ""
