@@ -187,6 +187,24 @@ def main():
         out["unfused_chain"] = {"ms_per_step": chain_ms, "value": nbytes / (chain_ms * 1e-3) / 1e9,
                                 "unit": "GB/s (same algorithmic bytes)", "steps": n_chain,
                                 "launches_per_step": 2 * wl.M + wl.M * (wl.M - 1) + wl.M}
+
+        # the same pass as ONE exchange step: M compress, one fold per part, M decodes
+        def exchange(t):
+            marsit.marsit_exchange_step_sim(grads[t % pool], c2, update, bits, ws, wl.scale,
+                                            workloads.step_seed(args.seed, t), grid_x=wl.grid_x, stream=stream)
+        for t in range(2):
+            exchange(t)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(n_chain):
+            exchange(2 + t)
+        torch.cuda.synchronize()
+        ex_ms = (time.perf_counter() - t0) * 1e3 / n_chain
+        Xb = wl.grid_x or wl.M
+        out["unfused_exchange_step"] = {
+            "ms_per_step": ex_ms, "value": nbytes / (ex_ms * 1e-3) / 1e9,
+            "unit": "GB/s (same algorithmic bytes)", "steps": n_chain,
+            "launches_per_step": 2 * wl.M + wl.M + (wl.M if wl.M // Xb > 1 else 0)}
         del ws, c2
 
     if not args.no_aux:

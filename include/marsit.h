@@ -201,6 +201,33 @@ int marsit_chain_step_sim(const float *g, float *c, float *update_out, uint64_t 
                           uint64_t *workspace, uint32_t M, uint64_t d, uint64_t ld, float scale,
                           uint64_t seed, uint32_t grid_x, void *stream);
 
+/*
+ * The whole chain of one part in one launch, for a deployment that exchanges the sign segments
+ * all-to-all instead of passing them round the ring (Section 4's reduce period collapsed into one
+ * exchange step: every worker sends the owner of a part its own signs of that part, the owner
+ * folds them, the gather period follows): out = the chain that starts with operand `first` and
+ * folds operand (first + h) mod K at hop h = 1..K-1 with fold count h + 1 and hop id hop_base | h.
+ * Bit-identical to the K - 1 marsit_hop_merge calls of that chain.
+ *   maps          operand k's segment starts at maps + k * stride_words ([n_words] each).
+ *   K             1..MARSIT_MAX_WORKERS operands;  first < K.
+ *   hop_base      low 8 bits zero: 0 for a ring, (y << 8) for row y of a torus, (1 << 16) for the
+ *                 column phase.
+ *   out           [n_words]; must not overlap the operands.
+ */
+int marsit_fold_segments(const uint64_t *maps, uint64_t stride_words, uint32_t K, uint32_t first,
+                         uint64_t *out, uint64_t word_begin, uint64_t n_words, uint32_t hop_base,
+                         uint64_t seed, void *stream);
+
+/*
+ * The one-bit pass of M simulated workers as that one exchange step: M marsit_compress, one
+ * marsit_fold_segments per part (rows, then columns on a torus), M marsit_decode_compensate, all
+ * on `stream`.  Arguments, workspace (marsit_chain_workspace_words) and results as in
+ * marsit_chain_step_sim; 3M launches on a ring instead of M*M + M.
+ */
+int marsit_exchange_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                             uint64_t *workspace, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                             uint64_t seed, uint32_t grid_x, void *stream);
+
 /* Host-side: size of the workspace of marsit_chain_step_sim in 64-bit words (0 for bad arguments). */
 uint64_t marsit_chain_workspace_words(uint32_t M, uint64_t d, uint32_t grid_x);
 

@@ -152,6 +152,57 @@ compress_hop_merge_kernel(const uint32_t *recv32, const float *__restrict__ g,
 }
 
 // -------------------------------------------------------------------------------------------------
+// marsit_fold_segments: the whole chain of a part in one launch, for the owner of the part that has
+// received the K sign segments (all-to-all exchange instead of K-1 ring hops).  lane = (packed
+// word i, nibble q) as in hop_merge_kernel.  The draws do not depend on the data: per bit, the last
+// hop whose draw succeeds names the operand whose sign survives; then each operand's nibble is
+// read once and selected.  Same draws, same result as K-1 marsit_hop_merge launches.
+// -------------------------------------------------------------------------------------------------
+struct FoldThresholds {
+    uint32_t thr[MARSIT_MAX_WORKERS + 1];     // thr[m] = floor(2^32 / m)
+};
+
+__global__ void __launch_bounds__(kBlock)
+fold_segments_kernel(const uint32_t *__restrict__ maps32, uint64_t stride_halves, uint32_t K,
+                     uint32_t first, uint32_t *__restrict__ out32, uint64_t word_begin,
+                     uint64_t n_words, uint32_t hop_base, uint32_t key0, uint32_t key1,
+                     FoldThresholds thresholds)
+{
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint64_t i = col >> 4;
+    const uint32_t q = static_cast<uint32_t>(col) & 15u;
+    const size_t half_index = 2u * static_cast<size_t>(i) + (q >> 3);
+    const uint32_t shift = (q & 7u) * 4u;
+    uint32_t nib = 0;
+
+    if (i < n_words) {
+        const uint64_t w = word_begin + i;
+        uint32_t pick[4] = {0, 0, 0, 0};
+        for (uint32_t h = 1; h < K; ++h) {
+            uint32_t u[4];
+            philox4x32_10(q, hop_base | h, static_cast<uint32_t>(w), static_cast<uint32_t>(w >> 32),
+                          key0, key1, u);
+            const uint32_t thr = thresholds.thr[h + 1];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                pick[j] = (u[j] < thr) ? h : pick[j];
+        }
+        uint32_t k = first;
+        for (uint32_t h = 0; h < K; ++h) {
+            const uint32_t v = (maps32[static_cast<size_t>(k) * stride_halves + half_index] >> shift) & 0xFu;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                nib = (pick[j] == h) ? ((nib & ~(1u << j)) | (v & (1u << j))) : nib;
+            k = (k + 1 == K) ? 0u : k + 1;
+        }
+    }
+
+    const uint32_t half = half_row_or(nib << shift);
+    if (i < n_words && (q & 7u) == 0u)
+        out32[half_index] = half;
+}
+
+// -------------------------------------------------------------------------------------------------
 // marsit_decode_compensate: lane = one column of 4 elements.
 // -------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kBlock)
@@ -388,6 +439,97 @@ int marsit_decode_compensate_apply(const uint64_t *bits, const float *g, const f
     if (x == nullptr || x == update_out || x == c_out)
         return MARSIT_EINVAL;
     return decode_impl(bits, g, c, scale, update_out, c_out, x, d, stream);
+}
+
+int marsit_fold_segments(const uint64_t *maps, uint64_t stride_words, uint32_t K, uint32_t first,
+                         uint64_t *out, uint64_t word_begin, uint64_t n_words, uint32_t hop_base,
+                         uint64_t seed, void *stream)
+{
+    if (maps == nullptr || out == nullptr || K == 0 || K > MARSIT_MAX_WORKERS || first >= K ||
+        n_words > kMaxElements / 64 || (K > 1 && stride_words < n_words) || (hop_base & 0xFFu) != 0)
+        return MARSIT_EINVAL;
+    if (!aligned_to(maps, 8) || !aligned_to(out, 8))
+        return MARSIT_EALIGN;
+    if (n_words == 0)
+        return MARSIT_OK;
+    FoldThresholds thresholds;
+    thresholds.thr[0] = 0;
+    thresholds.thr[1] = 0xFFFFFFFFu;
+    for (uint32_t m = 2; m <= MARSIT_MAX_WORKERS; ++m)
+        thresholds.thr[m] = keep_threshold(m);
+    hipLaunchKernelGGL(fold_segments_kernel, dim3(blocks_for(n_words * 16)), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(maps),
+                       2u * stride_words, K, first, reinterpret_cast<uint32_t *>(out), word_begin, n_words,
+                       hop_base, static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), thresholds);
+    return finish_launch();
+}
+
+// The one-bit pass as one exchange step: every worker computes its signs, the owner of a part gets
+// all K segments of that part (on one GPU they are simply in memory) and folds them in one launch,
+// every worker decodes.  Rows first, then columns, on a torus.  Workspace as in marsit_chain_step_sim.
+int marsit_exchange_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                             uint64_t *workspace, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                             uint64_t seed, uint32_t grid_x, void *stream)
+{
+    if (g == nullptr || c == nullptr || update_out == nullptr || bits_out == nullptr ||
+        workspace == nullptr || M == 0 || M > MARSIT_MAX_WORKERS || ld < d || !std::isfinite(scale) ||
+        d > kMaxElements)
+        return MARSIT_EINVAL;
+    const uint32_t X = (grid_x == 0) ? M : grid_x;
+    if (M % X != 0)
+        return MARSIT_EINVAL;
+    const uint32_t Y = M / X;
+    if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(update_out, 4) ||
+        !aligned_to(bits_out, 8) || !aligned_to(workspace, 8))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+
+    const uint64_t W = (d + 63) / 64;
+    uint64_t fine[MARSIT_MAX_WORKERS + 1];
+    split_bounds_host(W, M, grid_x, fine);
+    uint64_t *maps = workspace;                                  // [M][W]  every worker's own signs
+    uint64_t *rows = workspace + static_cast<size_t>(M) * W;     // [Y][W]  row results (torus)
+    int rc;
+
+    for (uint32_t m = 0; m < M; ++m) {
+        rc = marsit_compress(g + static_cast<size_t>(m) * ld, c + static_cast<size_t>(m) * ld,
+                             maps + static_cast<size_t>(m) * W, d, stream);
+        if (rc != MARSIT_OK)
+            return rc;
+    }
+    // row phase: the owner of row-part a in row y folds the X segments of its row, chain from column a
+    for (uint32_t a = 0; a < X; ++a) {
+        const uint64_t lo = fine[a * Y], n = fine[(a + 1) * Y] - lo;
+        for (uint32_t y = 0; y < Y && n > 0; ++y) {
+            uint64_t *r = (Y > 1 ? rows + static_cast<size_t>(y) * W : bits_out) + lo;
+            rc = marsit_fold_segments(maps + static_cast<size_t>(y * X) * W + lo, W, X, a, r, lo, n,
+                                      row_hop_id(y, 0), seed, stream);
+            if (rc != MARSIT_OK)
+                return rc;
+        }
+    }
+    // column phase: the owner of sub-part b of row-part a folds the Y row results, chain from row b
+    if (Y > 1) {
+        for (uint32_t f = 0; f < M; ++f) {
+            const uint64_t lo = fine[f], n = fine[f + 1] - lo;
+            if (n == 0)
+                continue;
+            rc = marsit_fold_segments(rows + lo, W, Y, f % Y, bits_out + lo, lo, n, col_hop_id(0), seed,
+                                      stream);
+            if (rc != MARSIT_OK)
+                return rc;
+        }
+    }
+    for (uint32_t m = 0; m < M; ++m) {
+        rc = marsit_decode_compensate(bits_out, g + static_cast<size_t>(m) * ld,
+                                      c + static_cast<size_t>(m) * ld, scale,
+                                      m == 0 ? update_out : nullptr, c + static_cast<size_t>(m) * ld, d,
+                                      stream);
+        if (rc != MARSIT_OK)
+            return rc;
+    }
+    return MARSIT_OK;
 }
 
 uint64_t marsit_chain_workspace_words(uint32_t M, uint64_t d, uint32_t grid_x)

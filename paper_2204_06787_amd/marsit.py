@@ -25,7 +25,8 @@ EXPORTS = (
     "marsit_ring_step_sim", "marsit_chain_step_sim", "marsit_chain_workspace_words",
     "marsit_full_sync", "marsit_step", "marsit_step_apply", "marsit_apply_update", "marsit_local_momentum",
     "marsit_pipeline_create", "marsit_pipeline_destroy", "marsit_pipeline_workspace_words",
-    "marsit_compress_hop_merge", "marsit_decode_compensate_apply", "marsit_pipeline_step", "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
+    "marsit_compress_hop_merge", "marsit_decode_compensate_apply", "marsit_fold_segments",
+    "marsit_exchange_step_sim", "marsit_pipeline_step", "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
     "marsit_aggregate_sign", "marsit_majority_vote", "marsit_count_matching",
     "marsit_hop_merge_weighted", "marsit_tree_step_sim",
     "marsit_ssdm_cascade_hop", "marsit_cascade_ring_step_sim",
@@ -116,6 +117,10 @@ def load_library(path: str | None = None):
     lib.marsit_step.restype = ci
     lib.marsit_decode_compensate_apply.argtypes = [vp, vp, vp, f32, vp, vp, vp, u64, vp]
     lib.marsit_decode_compensate_apply.restype = ci
+    lib.marsit_fold_segments.argtypes = [vp, u64, u32, u32, vp, u64, u64, u32, u64, vp]
+    lib.marsit_fold_segments.restype = ci
+    lib.marsit_exchange_step_sim.argtypes = [vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
+    lib.marsit_exchange_step_sim.restype = ci
     lib.marsit_step_apply.argtypes = [u64, u64, vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
     lib.marsit_step_apply.restype = ci
     lib.marsit_apply_update.argtypes = [vp, vp, u64, vp]
@@ -289,6 +294,38 @@ def marsit_chain_step_sim(g, c, update_out, bits_out, workspace, scale: float, s
     if workspace.numel() < marsit_chain_workspace_words(M, d, grid_x):
         raise ValueError("workspace too small")
     _check("marsit_chain_step_sim", load_library().marsit_chain_step_sim(
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
+        _bits_ptr(bits_out, "bits_out"), _bits_ptr(workspace, "workspace"), M, d, ld, scale,
+        seed & 0xFFFFFFFFFFFFFFFF, grid_x, _stream(stream)))
+    return update_out, bits_out
+
+
+def marsit_fold_segments(maps, K: int, first: int, out, word_begin: int, n_words_: int, hop_base: int,
+                         seed: int, stride_words: int | None = None, stream=None):
+    """``maps``: ``[K, stride_words]`` 64-bit tensor (or a flat one with ``stride_words`` given)
+    whose row k holds operand k's segment in its first ``n_words_`` words."""
+    if stride_words is None:
+        if maps.dim() != 2 or maps.stride(1) != 1:
+            raise TypeError("maps: need [K, words] with contiguous rows, or pass stride_words")
+        stride_words = maps.stride(0)
+    if not (isinstance(maps, torch.Tensor) and maps.is_cuda and maps.dtype in (torch.int64, torch.uint64)):
+        raise TypeError("maps: need a 64-bit integer tensor in device memory")
+    _check("marsit_fold_segments", load_library().marsit_fold_segments(
+        maps.data_ptr(), stride_words, K, first, _bits_ptr(out, "out"), word_begin, n_words_, hop_base,
+        seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
+    return out
+
+
+def marsit_exchange_step_sim(g, c, update_out, bits_out, workspace, scale: float, seed: int,
+                             grid_x: int = 0, d: int | None = None, stream=None):
+    """The pass as one exchange step: signs, one fold per part, decode.  Workspace as for the chain."""
+    M, ld = _rows(g, "g")
+    if _rows(c, "c") != (M, ld):
+        raise TypeError("g and c must have the same shape and row stride")
+    d = g.shape[1] if d is None else int(d)
+    if workspace.numel() < marsit_chain_workspace_words(M, d, grid_x):
+        raise ValueError("workspace too small")
+    _check("marsit_exchange_step_sim", load_library().marsit_exchange_step_sim(
         _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
         _bits_ptr(bits_out, "bits_out"), _bits_ptr(workspace, "workspace"), M, d, ld, scale,
         seed & 0xFFFFFFFFFFFFFFFF, grid_x, _stream(stream)))

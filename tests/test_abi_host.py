@@ -143,6 +143,17 @@ def test_other_entry_points_argument_validation(lib):
     assert lib.marsit_decode_compensate_apply(FAKE, FAKE, FAKE, 1.0, FAKE + 2, None, FAKE, 64, None) == marsit.EALIGN
     assert lib.marsit_decode_compensate_apply(FAKE, FAKE, FAKE, 1.0, FAKE + 1024, None, FAKE, 0, None) == marsit.OK
 
+    assert lib.marsit_fold_segments(None, 64, 4, 0, FAKE, 0, 64, 0, 1, None) == marsit.EINVAL
+    assert lib.marsit_fold_segments(FAKE, 64, 0, 0, FAKE, 0, 64, 0, 1, None) == marsit.EINVAL      # no operands
+    assert lib.marsit_fold_segments(FAKE, 64, 4, 4, FAKE, 0, 64, 0, 1, None) == marsit.EINVAL      # first >= K
+    assert lib.marsit_fold_segments(FAKE, 32, 4, 0, FAKE, 0, 64, 0, 1, None) == marsit.EINVAL      # operands overlap
+    assert lib.marsit_fold_segments(FAKE, 64, 4, 0, FAKE, 0, 64, 3, 1, None) == marsit.EINVAL      # hop bits in the base
+    assert lib.marsit_fold_segments(FAKE + 4, 64, 4, 0, FAKE, 0, 64, 0, 1, None) == marsit.EALIGN
+    assert lib.marsit_fold_segments(FAKE, 64, 4, 0, FAKE, 0, 0, 0, 1, None) == marsit.OK
+    assert lib.marsit_exchange_step_sim(FAKE, FAKE, FAKE, FAKE, None, 4, 64, 64, 1.0, 1, 0, None) == marsit.EINVAL
+    assert lib.marsit_exchange_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, 4, 64, 64, 1.0, 1, 3, None) == marsit.EINVAL
+    assert lib.marsit_exchange_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, 4, 0, 64, 1.0, 1, 0, None) == marsit.OK
+
     assert lib.marsit_pipeline_create(None, 4) == marsit.EINVAL
     assert lib.marsit_pipeline_destroy(None) == marsit.EINVAL
     assert lib.marsit_pipeline_ring_step(None, FAKE, FAKE, FAKE, FAKE, FAKE, 64, 64, 1.0, 1, None) == marsit.EINVAL

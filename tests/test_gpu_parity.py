@@ -334,6 +334,49 @@ def test_chain_step(M, grid_x, d):
         assert torch.equal(c1, c2)
 
 
+@pytest.mark.parametrize("K,first,n_words,hop_base", [(1, 0, 100, 0), (2, 1, 1, 0), (3, 2, 17, 0), (8, 5, 3000, 0),
+                                                      (4, 0, 999, 3 << 8), (4, 3, 64, 1 << 16), (64, 63, 130, 0),
+                                                      (16, 7, 12_501, 2 << 8)])
+def test_fold_segments(K, first, n_words, hop_base):
+    """The owner-side fold of K received segments in one launch = the oracle's chain of K - 1 hop
+    merges in the same order (start at `first`, hop h folds operand (first + h) mod K)."""
+    rng = np.random.default_rng(K * 1000 + n_words)
+    stride = n_words + 5                                           # operands need not be densely packed
+    maps_h = rng.integers(0, 2**64, size=(K, stride), dtype=np.uint64)
+    word_begin, seed = 77_000, 0x1234ABCD5678
+    want = maps_h[first, :n_words].copy()
+    for h in range(1, K):
+        want = orc.hop_merge(want, np.ascontiguousarray(maps_h[(first + h) % K, :n_words]), word_begin, h + 1,
+                             hop_base | h, seed)
+    out = torch.full((n_words + 2,), -1, dtype=torch.int64, device="cuda")
+    marsit.marsit_fold_segments(dev(maps_h), K, first, out[:n_words], word_begin, n_words, hop_base, seed)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_bits(out[:n_words]), want)
+    assert bool((out[n_words:] == -1).all())                       # nothing written past the segment
+
+
+@pytest.mark.parametrize("M,grid_x,d", [(3, 0, 65_536), (8, 0, 400_000 + 21), (16, 4, 200_003), (6, 3, 64 * 5 + 1),
+                                        (5, 0, 7), (9, 3, 33_333), (4, 1, 5000), (12, 0, 100), (64, 8, 70_001),
+                                        (1, 0, 1000)])
+def test_exchange_step(M, grid_x, d):
+    """One exchange step (signs, one fold per part, decode) against the oracle and the fused pass."""
+    g_h, c_h = _inputs(M, d, seed=16)
+    g1, c1 = dev(g_h), dev(c_h)
+    g2, c2 = dev(g_h), dev(c_h)
+    ws = torch.empty(marsit.marsit_chain_workspace_words(M, d, grid_x), dtype=torch.int64, device="cuda")
+    u1 = torch.empty(d, dtype=torch.float32, device="cuda")
+    b1 = marsit.new_bitmap(d)
+    for t in range(2):
+        sd = workloads.step_seed(606, t)
+        marsit.marsit_exchange_step_sim(g1, c1, u1, b1, ws, 1e-3, sd, grid_x=grid_x)
+        u2, b2 = fused_step(g2, c2, 1e-3, sd, grid_x=grid_x)
+        want_u, want_b, _ = oracle_step(g_h, c_h, 1e-3, sd, grid_x=grid_x)
+        assert np.array_equal(host_bits(b1), want_b) and torch.equal(b1, b2)
+        assert np.array_equal(host_f32(u1), want_u) and torch.equal(u1, u2)
+        assert_f32_parity(host_f32(c1), c_h, "compensation (exchange step)")
+        assert torch.equal(c1, c2)
+
+
 # ------------------------------------------------------------------------------------------------
 # the ring as M workers on M streams (marsit_pipeline_*) vs oracle and vs the fused kernel
 # ------------------------------------------------------------------------------------------------
