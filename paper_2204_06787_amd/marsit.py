@@ -149,17 +149,24 @@ def _stream(stream) -> int:
     return int(stream)
 
 
-def _f32_ptr(t, name, allow_none=False):
+def _f32_ptr(t, name, allow_none=False, need=0):
+    """Device pointer of a float32 tensor.  A vector (the [M, ld] operands go through ``_rows``
+    first) must be contiguous and hold at least ``need`` elements: the kernels trust these sizes."""
     if t is None:
         if allow_none:
             return None
         raise TypeError(f"{name} is required")
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32):
         raise TypeError(f"{name}: need a float32 tensor in device memory")
+    if t.dim() <= 1:
+        if t.dim() == 1 and t.numel() > 1 and t.stride(0) != 1:
+            raise TypeError(f"{name}: need a contiguous vector")
+        if t.numel() < need:
+            raise ValueError(f"{name}: {t.numel()} elements, need at least {need}")
     return t.data_ptr()
 
 
-def _bits_ptr(t, name, allow_none=False):
+def _bits_ptr(t, name, allow_none=False, need=0):
     if t is None:
         if allow_none:
             return None
@@ -167,14 +174,29 @@ def _bits_ptr(t, name, allow_none=False):
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype in (torch.int64, torch.uint64)
             and t.is_contiguous()):
         raise TypeError(f"{name}: need a contiguous 64-bit integer tensor in device memory")
+    if t.numel() < need:
+        raise ValueError(f"{name}: {t.numel()} words, need at least {need}")
     return t.data_ptr()
 
 
-def _rows(t, name):
+def _rows(t, name, d=None):
     """[M, >=d] tensor with unit inner stride -> (M, row stride in elements)."""
-    if t.dim() != 2 or t.stride(1) != 1:
+    if not isinstance(t, torch.Tensor) or t.dim() != 2 or t.stride(1) != 1:
         raise TypeError(f"{name}: need a 2-D tensor whose rows are contiguous")
+    if d is not None and t.shape[1] < d:
+        raise ValueError(f"{name}: rows of {t.shape[1]} elements, need at least {d}")
     return t.shape[0], (t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1]))
+
+
+def _matrix_args(g, c, d, names=("g", "c")):
+    """Checks the [M, ld] operand pair and returns (M, ld, d)."""
+    M, ld = _rows(g, names[0])
+    if _rows(c, names[1]) != (M, ld):
+        raise TypeError(f"{names[0]} and {names[1]} must have the same shape and row stride")
+    d = g.shape[1] if d is None else int(d)
+    if d < 0 or g.shape[1] < d or c.shape[1] < d:
+        raise ValueError(f"d = {d} exceeds the rows of {names[0]} / {names[1]}")
+    return M, ld, d
 
 
 def new_bitmap(d: int, device="cuda") -> torch.Tensor:
@@ -207,14 +229,16 @@ def marsit_split_bounds(n_words_: int, M: int, grid_x: int = 0):
 def marsit_compress(g, c, bits_out, d: int | None = None, stream=None):
     d = g.numel() if d is None else int(d)
     _check("marsit_compress", load_library().marsit_compress(
-        _f32_ptr(g, "g"), _f32_ptr(c, "c", True), _bits_ptr(bits_out, "bits_out"), d, _stream(stream)))
+        _f32_ptr(g, "g", need=d), _f32_ptr(c, "c", True, need=d), _bits_ptr(bits_out, "bits_out", need=n_words(d)),
+        d, _stream(stream)))
     return bits_out
 
 
 def marsit_hop_merge(recv, local, out, word_begin: int, n_words_: int, fold: int, hop_id: int,
                      seed: int, stream=None):
     _check("marsit_hop_merge", load_library().marsit_hop_merge(
-        _bits_ptr(recv, "recv"), _bits_ptr(local, "local"), _bits_ptr(out, "out"), word_begin,
+        _bits_ptr(recv, "recv", need=n_words_), _bits_ptr(local, "local", need=n_words_),
+        _bits_ptr(out, "out", need=n_words_), word_begin,
         n_words_, fold, hop_id, seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
     return out
 
@@ -224,7 +248,8 @@ def marsit_compress_hop_merge(recv, g, c, out, word_begin: int, fold: int, hop_i
     """``g``/``c``: the worker's vectors from the first element of the part (1-D views)."""
     n = g.numel() if n is None else int(n)
     _check("marsit_compress_hop_merge", load_library().marsit_compress_hop_merge(
-        _bits_ptr(recv, "recv", True), _f32_ptr(g, "g"), _f32_ptr(c, "c", True), _bits_ptr(out, "out"),
+        _bits_ptr(recv, "recv", True, need=n_words(n)), _f32_ptr(g, "g", need=n), _f32_ptr(c, "c", True, need=n),
+        _bits_ptr(out, "out", need=n_words(n)),
         word_begin, n, fold, hop_id, seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
     return out
 
@@ -233,14 +258,15 @@ def marsit_hop_merge_device_seed(recv, local, out, word_begin: int, n_words_: in
                                  seed_device, stream=None):
     """``seed_device``: one-element int64 tensor in device memory holding the seed."""
     _check("marsit_hop_merge_device_seed", load_library().marsit_hop_merge_device_seed(
-        _bits_ptr(recv, "recv"), _bits_ptr(local, "local"), _bits_ptr(out, "out"), word_begin,
-        n_words_, fold, hop_id, _bits_ptr(seed_device, "seed_device"), _stream(stream)))
+        _bits_ptr(recv, "recv", need=n_words_), _bits_ptr(local, "local", need=n_words_),
+        _bits_ptr(out, "out", need=n_words_), word_begin,
+        n_words_, fold, hop_id, _bits_ptr(seed_device, "seed_device", need=1), _stream(stream)))
     return out
 
 
 def marsit_set_device_seed(seed_device, seed: int, stream=None):
     _check("marsit_set_device_seed", load_library().marsit_set_device_seed(
-        _bits_ptr(seed_device, "seed_device"), seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
+        _bits_ptr(seed_device, "seed_device", need=1), seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
     return seed_device
 
 
@@ -248,8 +274,8 @@ def marsit_decode_compensate(bits, g, c, scale: float, update_out, c_out, d: int
                              stream=None):
     d = g.numel() if d is None else int(d)
     _check("marsit_decode_compensate", load_library().marsit_decode_compensate(
-        _bits_ptr(bits, "bits"), _f32_ptr(g, "g"), _f32_ptr(c, "c", True), scale,
-        _f32_ptr(update_out, "update_out", True), _f32_ptr(c_out, "c_out"), d, _stream(stream)))
+        _bits_ptr(bits, "bits", need=n_words(d)), _f32_ptr(g, "g", need=d), _f32_ptr(c, "c", True, need=d), scale,
+        _f32_ptr(update_out, "update_out", True, need=d), _f32_ptr(c_out, "c_out", need=d), d, _stream(stream)))
     return update_out, c_out
 
 
@@ -257,25 +283,20 @@ def marsit_decode_compensate_apply(bits, g, c, scale: float, x, update_out, c_ou
                                    stream=None):
     """``marsit_decode_compensate`` with the model update ``x -= update`` in the same pass."""
     d = g.numel() if d is None else int(d)
-    if x.numel() < d:
-        raise ValueError("x shorter than d")
     _check("marsit_decode_compensate_apply", load_library().marsit_decode_compensate_apply(
-        _bits_ptr(bits, "bits"), _f32_ptr(g, "g"), _f32_ptr(c, "c", True), scale, _f32_ptr(x, "x"),
-        _f32_ptr(update_out, "update_out", True), _f32_ptr(c_out, "c_out"), d, _stream(stream)))
+        _bits_ptr(bits, "bits", need=n_words(d)), _f32_ptr(g, "g", need=d), _f32_ptr(c, "c", True, need=d), scale,
+        _f32_ptr(x, "x", need=d), _f32_ptr(update_out, "update_out", True, need=d),
+        _f32_ptr(c_out, "c_out", need=d), d, _stream(stream)))
     return x, c_out
 
 
 def marsit_ring_step_sim(g, c, update_out, bits_out, scale: float, seed: int, grid_x: int = 0,
                          d: int | None = None, stream=None):
     """``g``, ``c``: ``[M, ld]`` float32 (rows contiguous); ``c`` is updated in place."""
-    M, ld = _rows(g, "g")
-    Mc, ldc = _rows(c, "c")
-    if (M, ld) != (Mc, ldc):
-        raise TypeError("g and c must have the same shape and row stride")
-    d = g.shape[1] if d is None else int(d)
+    M, ld, d = _matrix_args(g, c, d)
     _check("marsit_ring_step_sim", load_library().marsit_ring_step_sim(
-        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
-        _bits_ptr(bits_out, "bits_out", True), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF, grid_x,
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out", need=d),
+        _bits_ptr(bits_out, "bits_out", True, need=n_words(d)), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF, grid_x,
         _stream(stream)))
     return update_out, bits_out
 
@@ -287,15 +308,12 @@ def marsit_chain_workspace_words(M: int, d: int, grid_x: int = 0) -> int:
 def marsit_chain_step_sim(g, c, update_out, bits_out, workspace, scale: float, seed: int,
                           grid_x: int = 0, d: int | None = None, stream=None):
     """The pass hop by hop (un-fused).  ``workspace``: int64 tensor of ``marsit_chain_workspace_words``."""
-    M, ld = _rows(g, "g")
-    if _rows(c, "c") != (M, ld):
-        raise TypeError("g and c must have the same shape and row stride")
-    d = g.shape[1] if d is None else int(d)
+    M, ld, d = _matrix_args(g, c, d)
     if workspace.numel() < marsit_chain_workspace_words(M, d, grid_x):
         raise ValueError("workspace too small")
     _check("marsit_chain_step_sim", load_library().marsit_chain_step_sim(
-        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
-        _bits_ptr(bits_out, "bits_out"), _bits_ptr(workspace, "workspace"), M, d, ld, scale,
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out", need=d),
+        _bits_ptr(bits_out, "bits_out", need=n_words(d)), _bits_ptr(workspace, "workspace"), M, d, ld, scale,
         seed & 0xFFFFFFFFFFFFFFFF, grid_x, _stream(stream)))
     return update_out, bits_out
 
@@ -310,8 +328,14 @@ def marsit_fold_segments(maps, K: int, first: int, out, word_begin: int, n_words
         stride_words = maps.stride(0)
     if not (isinstance(maps, torch.Tensor) and maps.is_cuda and maps.dtype in (torch.int64, torch.uint64)):
         raise TypeError("maps: need a 64-bit integer tensor in device memory")
+    if K < 1 or (maps.dim() == 2 and maps.shape[0] < K) or n_words_ < 0:
+        raise ValueError("maps holds fewer than K operands")
+    reach = (K - 1) * stride_words + n_words_          # words from maps' first element to the last one read
+    have = (maps.shape[0] - 1) * maps.stride(0) + maps.shape[1] if maps.dim() == 2 else maps.numel()
+    if reach > have:
+        raise ValueError(f"maps: the K operands reach {reach} words, the tensor holds {have}")
     _check("marsit_fold_segments", load_library().marsit_fold_segments(
-        maps.data_ptr(), stride_words, K, first, _bits_ptr(out, "out"), word_begin, n_words_, hop_base,
+        maps.data_ptr(), stride_words, K, first, _bits_ptr(out, "out", need=n_words_), word_begin, n_words_, hop_base,
         seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
     return out
 
@@ -319,15 +343,12 @@ def marsit_fold_segments(maps, K: int, first: int, out, word_begin: int, n_words
 def marsit_exchange_step_sim(g, c, update_out, bits_out, workspace, scale: float, seed: int,
                              grid_x: int = 0, d: int | None = None, stream=None):
     """The pass as one exchange step: signs, one fold per part, decode.  Workspace as for the chain."""
-    M, ld = _rows(g, "g")
-    if _rows(c, "c") != (M, ld):
-        raise TypeError("g and c must have the same shape and row stride")
-    d = g.shape[1] if d is None else int(d)
+    M, ld, d = _matrix_args(g, c, d)
     if workspace.numel() < marsit_chain_workspace_words(M, d, grid_x):
         raise ValueError("workspace too small")
     _check("marsit_exchange_step_sim", load_library().marsit_exchange_step_sim(
-        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
-        _bits_ptr(bits_out, "bits_out"), _bits_ptr(workspace, "workspace"), M, d, ld, scale,
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out", need=d),
+        _bits_ptr(bits_out, "bits_out", need=n_words(d)), _bits_ptr(workspace, "workspace"), M, d, ld, scale,
         seed & 0xFFFFFFFFFFFFFFFF, grid_x, _stream(stream)))
     return update_out, bits_out
 
@@ -345,32 +366,30 @@ class RingPipeline:
 
     def step(self, g, c, update_out, bits_out, workspace, scale: float, seed: int, grid_x: int = 0,
              d: int | None = None, stream=None):
-        M, ld = _rows(g, "g")
-        if M != self.M or _rows(c, "c") != (M, ld):
+        M, ld, d = _matrix_args(g, c, d)
+        if M != self.M:
             raise TypeError("g and c must be [M, ld] with the pipeline's M")
-        d = g.shape[1] if d is None else int(d)
         need = self.workspace_words(d, grid_x)
         if need == 0 and d > 0:
             raise ValueError("grid_x must be 0 or divide M")
         if workspace.numel() < need:
             raise ValueError("workspace too small")
         _check("marsit_pipeline_step", load_library().marsit_pipeline_step(
-            self._h, _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
-            _bits_ptr(bits_out, "bits_out"), _bits_ptr(workspace, "workspace"), d, ld, scale,
+            self._h, _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out", need=d),
+            _bits_ptr(bits_out, "bits_out", need=n_words(d)), _bits_ptr(workspace, "workspace"), d, ld, scale,
             seed & 0xFFFFFFFFFFFFFFFF, grid_x, _stream(stream)))
         return update_out, bits_out
 
     def ring_step(self, g, c, update_out, bits_out, workspace, scale: float, seed: int,
                   d: int | None = None, stream=None):
-        M, ld = _rows(g, "g")
-        if M != self.M or _rows(c, "c") != (M, ld):
+        M, ld, d = _matrix_args(g, c, d)
+        if M != self.M:
             raise TypeError("g and c must be [M, ld] with the pipeline's M")
-        d = g.shape[1] if d is None else int(d)
         if workspace.numel() < self.workspace_words(d):
             raise ValueError("workspace too small")
         _check("marsit_pipeline_ring_step", load_library().marsit_pipeline_ring_step(
-            self._h, _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
-            _bits_ptr(bits_out, "bits_out"), _bits_ptr(workspace, "workspace"), d, ld, scale,
+            self._h, _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out", need=d),
+            _bits_ptr(bits_out, "bits_out", need=n_words(d)), _bits_ptr(workspace, "workspace"), d, ld, scale,
             seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
         return update_out, bits_out
 
@@ -387,25 +406,19 @@ class RingPipeline:
 
 
 def marsit_full_sync(g, c, update_out, d: int | None = None, stream=None):
-    M, ld = _rows(g, "g")
-    if _rows(c, "c") != (M, ld):
-        raise TypeError("g and c must have the same shape and row stride")
-    d = g.shape[1] if d is None else int(d)
+    M, ld, d = _matrix_args(g, c, d)
     _check("marsit_full_sync", load_library().marsit_full_sync(
-        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"), M, d, ld,
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out", need=d), M, d, ld,
         _stream(stream)))
     return update_out
 
 
 def marsit_step(t: int, K: int, g, c, update_out, bits_out, scale: float, seed: int,
                 grid_x: int = 0, d: int | None = None, stream=None):
-    M, ld = _rows(g, "g")
-    if _rows(c, "c") != (M, ld):
-        raise TypeError("g and c must have the same shape and row stride")
-    d = g.shape[1] if d is None else int(d)
+    M, ld, d = _matrix_args(g, c, d)
     _check("marsit_step", load_library().marsit_step(
-        t, K, _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
-        _bits_ptr(bits_out, "bits_out", True), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF, grid_x,
+        t, K, _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out", need=d),
+        _bits_ptr(bits_out, "bits_out", True, need=n_words(d)), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF, grid_x,
         _stream(stream)))
     return update_out, bits_out
 
@@ -413,15 +426,11 @@ def marsit_step(t: int, K: int, g, c, update_out, bits_out, scale: float, seed: 
 def marsit_step_apply(t: int, K: int, g, c, x, update_out, bits_out, scale: float, seed: int,
                       grid_x: int = 0, d: int | None = None, stream=None):
     """``marsit_step`` with the model update ``x -= g_t`` in the same pass; ``update_out`` may be None."""
-    M, ld = _rows(g, "g")
-    if _rows(c, "c") != (M, ld):
-        raise TypeError("g and c must have the same shape and row stride")
-    d = g.shape[1] if d is None else int(d)
-    if x.numel() < d or (update_out is not None and update_out.numel() < d):
-        raise ValueError("x / update_out shorter than d")
+    M, ld, d = _matrix_args(g, c, d)
     _check("marsit_step_apply", load_library().marsit_step_apply(
-        t, K, _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(x, "x"), _f32_ptr(update_out, "update_out", True),
-        _bits_ptr(bits_out, "bits_out", True), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF, grid_x,
+        t, K, _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(x, "x", need=d),
+        _f32_ptr(update_out, "update_out", True, need=d),
+        _bits_ptr(bits_out, "bits_out", True, need=n_words(d)), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF, grid_x,
         _stream(stream)))
     return x
 
@@ -429,15 +438,14 @@ def marsit_step_apply(t: int, K: int, g, c, x, update_out, bits_out, scale: floa
 def marsit_apply_update(x, update, d: int | None = None, stream=None):
     d = x.numel() if d is None else int(d)
     _check("marsit_apply_update", load_library().marsit_apply_update(
-        _f32_ptr(x, "x"), _f32_ptr(update, "update"), d, _stream(stream)))
+        _f32_ptr(x, "x", need=d), _f32_ptr(update, "update", need=d), d, _stream(stream)))
     return x
 
 
 def marsit_local_momentum(buf, grad, g_out, beta: float, eta_l: float, d: int | None = None, stream=None):
-    M, ld = _rows(buf, "buf")
-    if _rows(grad, "grad") != (M, ld) or _rows(g_out, "g_out") != (M, ld):
+    M, ld, d = _matrix_args(buf, grad, d, names=("buf", "grad"))
+    if _rows(g_out, "g_out", d) != (M, ld):
         raise TypeError("buf, grad and g_out must have the same shape and row stride")
-    d = buf.shape[1] if d is None else int(d)
     _check("marsit_local_momentum", load_library().marsit_local_momentum(
         _f32_ptr(buf, "buf"), _f32_ptr(grad, "grad"), _f32_ptr(g_out, "g_out"), M, d, ld, beta, eta_l,
         _stream(stream)))
@@ -447,12 +455,10 @@ def marsit_local_momentum(buf, grad, g_out, beta: float, eta_l: float, d: int | 
 # --- diagnostics (Section 3.2.2, Fig. 2b) --------------------------------------------------------
 
 def _vote(name, g, c, bits_out, d, stream):
-    M, ld = _rows(g, "g")
-    if _rows(c, "c") != (M, ld):
-        raise TypeError("g and c must have the same shape and row stride")
-    d = g.shape[1] if d is None else int(d)
+    M, ld, d = _matrix_args(g, c, d)
     _check(name, getattr(load_library(), name)(
-        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _bits_ptr(bits_out, "bits_out"), M, d, ld, _stream(stream)))
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _bits_ptr(bits_out, "bits_out", need=n_words(d)), M, d, ld,
+        _stream(stream)))
     return bits_out
 
 
@@ -467,7 +473,8 @@ def marsit_majority_vote(g, c, bits_out, d: int | None = None, stream=None):
 def marsit_count_matching(bits_a, bits_b, d: int, count_out, stream=None):
     """``count_out``: one-element int64 tensor in device memory (overwritten)."""
     _check("marsit_count_matching", load_library().marsit_count_matching(
-        _bits_ptr(bits_a, "bits_a"), _bits_ptr(bits_b, "bits_b"), d, _bits_ptr(count_out, "count_out"),
+        _bits_ptr(bits_a, "bits_a", need=n_words(d)), _bits_ptr(bits_b, "bits_b", need=n_words(d)), d,
+        _bits_ptr(count_out, "count_out", need=1),
         _stream(stream)))
     return count_out
 
@@ -477,7 +484,8 @@ def marsit_count_matching(bits_a, bits_b, d: int, count_out, stream=None):
 def marsit_hop_merge_weighted(recv, local, out, word_begin: int, n_words_: int, w_recv: int,
                               w_local: int, hop_id: int, seed: int, stream=None):
     _check("marsit_hop_merge_weighted", load_library().marsit_hop_merge_weighted(
-        _bits_ptr(recv, "recv"), _bits_ptr(local, "local"), _bits_ptr(out, "out"), word_begin,
+        _bits_ptr(recv, "recv", need=n_words_), _bits_ptr(local, "local", need=n_words_),
+        _bits_ptr(out, "out", need=n_words_), word_begin,
         n_words_, w_recv, w_local, hop_id, seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
     return out
 
@@ -485,13 +493,10 @@ def marsit_hop_merge_weighted(recv, local, out, word_begin: int, n_words_: int, 
 def marsit_tree_step_sim(g, c, update_out, bits_out, scale: float, seed: int, d: int | None = None,
                          stream=None):
     """The one-bit pass over a binary reduction tree; ``c`` is updated in place."""
-    M, ld = _rows(g, "g")
-    if _rows(c, "c") != (M, ld):
-        raise TypeError("g and c must have the same shape and row stride")
-    d = g.shape[1] if d is None else int(d)
+    M, ld, d = _matrix_args(g, c, d)
     _check("marsit_tree_step_sim", load_library().marsit_tree_step_sim(
-        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
-        _bits_ptr(bits_out, "bits_out", True), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF,
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out", need=d),
+        _bits_ptr(bits_out, "bits_out", True, need=n_words(d)), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF,
         _stream(stream)))
     return update_out, bits_out
 
@@ -509,23 +514,19 @@ def marsit_ssdm_cascade_hop(recv_bits, recv_norm, g, c, bits_out, norm_out, work
                             n: int, hop_id: int, seed: int, stream=None):
     """``recv_norm``/``norm_out``: one-element float32 tensors in device memory."""
     _check("marsit_ssdm_cascade_hop", load_library().marsit_ssdm_cascade_hop(
-        _bits_ptr(recv_bits, "recv_bits", True), _f32_ptr(recv_norm, "recv_norm", True), _f32_ptr(g, "g"),
-        _f32_ptr(c, "c"), _bits_ptr(bits_out, "bits_out"), _f32_ptr(norm_out, "norm_out"),
-        _bits_ptr(workspace, "workspace"), word_begin, n, hop_id, seed & 0xFFFFFFFFFFFFFFFF,
+        _bits_ptr(recv_bits, "recv_bits", True, need=n_words(n)), _f32_ptr(recv_norm, "recv_norm", True, need=1),
+        _f32_ptr(g, "g", need=n), _f32_ptr(c, "c", need=n), _bits_ptr(bits_out, "bits_out", need=n_words(n)),
+        _f32_ptr(norm_out, "norm_out", need=1),
+        _bits_ptr(workspace, "workspace", need=CASCADE_WORKSPACE_BYTES // 8), word_begin, n, hop_id, seed & 0xFFFFFFFFFFFFFFFF,
         _stream(stream)))
     return bits_out, norm_out
 
 
 def marsit_cascade_ring_step_sim(g, c, update_out, bits_out, norms_out, workspace, seed: int,
                                  d: int | None = None, stream=None):
-    M, ld = _rows(g, "g")
-    if _rows(c, "c") != (M, ld):
-        raise TypeError("g and c must have the same shape and row stride")
-    d = g.shape[1] if d is None else int(d)
-    if norms_out.numel() < M:
-        raise ValueError("norms_out needs M elements")
+    M, ld, d = _matrix_args(g, c, d)
     _check("marsit_cascade_ring_step_sim", load_library().marsit_cascade_ring_step_sim(
-        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out"),
-        _bits_ptr(bits_out, "bits_out"), _f32_ptr(norms_out, "norms_out"),
-        _bits_ptr(workspace, "workspace"), M, d, ld, seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out", need=d),
+        _bits_ptr(bits_out, "bits_out", need=n_words(d)), _f32_ptr(norms_out, "norms_out", need=M),
+        _bits_ptr(workspace, "workspace", need=CASCADE_WORKSPACE_BYTES // 8), M, d, ld, seed & 0xFFFFFFFFFFFFFFFF, _stream(stream)))
     return update_out, bits_out, norms_out

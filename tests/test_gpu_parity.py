@@ -511,3 +511,37 @@ def test_device_seed_lets_a_captured_graph_be_replayed_with_new_seeds():
         graph.replay()
         torch.cuda.synchronize()
         assert np.array_equal(host_bits(out), orc.hop_merge(recv, local, 7, 3, 2, seed)), seed
+
+
+def test_binding_rejects_short_or_strided_operands():
+    """The kernels trust the sizes they are given, so the binding checks them on the host: nothing
+    is launched for an operand that is too short or not contiguous."""
+    M, d = 4, 1000
+    g = torch.zeros((M, d), dtype=torch.float32, device="cuda")
+    c = torch.zeros((M, d), dtype=torch.float32, device="cuda")
+    u = torch.zeros(d, dtype=torch.float32, device="cuda")
+    b = marsit.new_bitmap(d)
+    with pytest.raises(ValueError):
+        marsit.marsit_ring_step_sim(g, c, u[:d - 1], b, 1e-3, 1)
+    with pytest.raises(ValueError):
+        marsit.marsit_ring_step_sim(g, c, u, b[:-1], 1e-3, 1)
+    with pytest.raises(ValueError):
+        marsit.marsit_ring_step_sim(g, c, u, b, 1e-3, 1, d=d + 1)
+    with pytest.raises(TypeError):
+        marsit.marsit_ring_step_sim(g, c[:, ::2], u, b, 1e-3, 1)
+    with pytest.raises(TypeError):
+        marsit.marsit_compress(torch.zeros(2 * d, dtype=torch.float32, device="cuda")[::2], None, b)
+    with pytest.raises(ValueError):
+        marsit.marsit_compress(g[0], c[0], b[:3])
+    with pytest.raises(ValueError):
+        marsit.marsit_decode_compensate(b, g[0], c[0], 1e-3, u, c[0][:10])
+    with pytest.raises(ValueError):
+        marsit.marsit_hop_merge(b, b, b, 0, b.numel() + 1, 2, 1, 1)
+    with pytest.raises(ValueError):
+        marsit.marsit_step_apply(1, 2, g, c, u[:5], None, b, 1e-3, 1)
+    with pytest.raises(ValueError):
+        marsit.marsit_fold_segments(torch.zeros((3, 10), dtype=torch.int64, device="cuda"), 4, 0, b, 0, 10, 0, 1)
+    with pytest.raises(TypeError):
+        marsit.marsit_apply_update(u.double(), u)
+    torch.cuda.synchronize()
+    assert not u.any() and not c.any()
