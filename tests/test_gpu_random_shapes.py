@@ -1,0 +1,87 @@
+"""Seeded random shapes through every whole-pass entry point against the oracle: worker counts
+with and without a compiled schedule, every divisor as grid width, ragged and word-aligned sizes,
+padded rows, misaligned bases, special values, odd scales."""
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import marsit_oracle as orc
+from paper_2204_06787_amd import marsit
+
+pytestmark = pytest.mark.gpu
+
+KINDS = ["ring", "apply", "tree", "pipe", "exchange", "chain"]
+SPECIAL = np.array([0.0, -0.0, np.inf, -np.inf, 1e-45, -1e-45, 3e38, -3e38], dtype=np.float32)
+
+
+def _place(a: np.ndarray, off: int) -> torch.Tensor:
+    """Device copy whose base pointer is `off` floats past an allocation boundary."""
+    base = torch.zeros(a.size + 8, dtype=torch.float32, device="cuda")
+    v = base[off:off + a.size].view(a.shape)
+    v.copy_(torch.from_numpy(a).cuda())
+    return v
+
+
+@pytest.mark.parametrize("chunk", range(8))
+def test_random_shapes(chunk):
+    rng = np.random.default_rng(20_220_414 + chunk)
+    for it in range(40):
+        M = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 12, 15, 16, 17, 24, 32, 41, 64]))
+        grid_x = int(rng.choice([0] + [x for x in range(1, M + 1) if M % x == 0]))
+        kind = str(rng.choice(KINDS))
+        if kind == "pipe" and M > 16:
+            kind = "ring"
+        d = int(rng.choice([rng.integers(1, 300), rng.integers(300, 70_000), 64 * int(rng.integers(1, 400)),
+                            256 * int(rng.integers(1, 200))]))
+        if M > 32:
+            d = min(d, 20_000)
+        ld = d + int(rng.choice([0, 0, 1, 3, 4, 8]))
+        off = int(rng.choice([0, 0, 0, 1, 2]))
+        scale = float(rng.choice([1e-3, 0.5, -2.0, 1e-30]))
+        seed = int(rng.integers(0, 2**63))
+        case = f"chunk={chunk} it={it} kind={kind} M={M} grid_x={grid_x} d={d} ld={ld} off={off} scale={scale} seed={seed}"
+        print(case, flush=True)
+
+        g_h = rng.standard_normal((M, ld)).astype(np.float32)
+        c_h = (0.3 * rng.standard_normal((M, ld))).astype(np.float32)
+        if rng.random() < 0.2:
+            k = min(d, SPECIAL.size)
+            g_h[:, :k] = SPECIAL[:k]
+            c_h[:, :k] = 0.0
+        x_h = rng.standard_normal(d).astype(np.float32)
+        g_d, c_d = _place(g_h, off), _place(c_h, off)
+        u_d = torch.full((d + 8,), 7.0, dtype=torch.float32, device="cuda")[off:off + d]
+        b_d = marsit.new_bitmap(d).fill_(-1)
+        x_d = _place(x_h, off)
+
+        c_ref = c_h.copy()
+        if kind == "tree":
+            want_u, want_b = orc.tree_step(g_h, c_ref, scale, seed, d=d)
+            marsit.marsit_tree_step_sim(g_d, c_d, u_d, b_d, scale, seed, d=d)
+        else:
+            want_u, want_b, _ = orc.sync_step(g_h, c_ref, scale, seed, grid_x=grid_x, d=d, threads=8)
+            if kind == "ring":
+                marsit.marsit_ring_step_sim(g_d, c_d, u_d, b_d, scale, seed, grid_x=grid_x, d=d)
+            elif kind == "apply":
+                marsit.marsit_step_apply(1, 2, g_d, c_d, x_d, u_d, b_d, scale, seed, grid_x=grid_x, d=d)
+            elif kind == "pipe":
+                with marsit.RingPipeline(M) as pipe:
+                    ws = torch.empty(max(1, pipe.workspace_words(d, grid_x)), dtype=torch.int64, device="cuda")
+                    pipe.step(g_d, c_d, u_d, b_d, ws, scale, seed, grid_x=grid_x, d=d)
+                    torch.cuda.synchronize()
+            else:
+                ws = torch.empty(max(1, marsit.marsit_chain_workspace_words(M, d, grid_x)), dtype=torch.int64,
+                                 device="cuda")
+                step = marsit.marsit_exchange_step_sim if kind == "exchange" else marsit.marsit_chain_step_sim
+                step(g_d, c_d, u_d, b_d, ws, scale, seed, grid_x=grid_x, d=d)
+        torch.cuda.synchronize()
+
+        assert np.array_equal(b_d.cpu().numpy().view(np.uint64), want_b), case
+        assert np.array_equal(u_d.cpu().numpy().view(np.uint32), want_u.view(np.uint32)), case
+        got_c = c_d.cpu().numpy()
+        assert np.array_equal(got_c[:, :d].view(np.uint32), c_ref[:, :d].view(np.uint32)), case
+        assert np.array_equal(got_c[:, d:].view(np.uint32), c_h[:, d:].view(np.uint32)), case     # padding untouched
+        if kind == "apply":
+            want_x = orc.apply_update(x_h.copy(), want_u)
+            assert np.array_equal(x_d.cpu().numpy().view(np.uint32), want_x.view(np.uint32)), case
