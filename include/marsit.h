@@ -268,7 +268,8 @@ int marsit_pipeline_last_hip_error(void);
 /*
  * Algorithm 1, the branch mod(t,K) == 0 (the full-precision round) for M simulated workers:
  *     update_out[e] = (1/M) * sum_m (g[m][e] + c[m][e]);   c[m][e] = 0.
- * The sum runs over m = 0..M-1 in fp32, then one division by M.
+ * Each g + c is one fp32 add; their sum (m = 0..M-1, in that order, starting from +0) and the
+ * division by M are done in double precision, and the quotient is rounded once to fp32.
  */
 int marsit_full_sync(const float *g, float *c, float *update_out, uint32_t M, uint64_t d,
                      uint64_t ld, void *stream);

@@ -534,20 +534,24 @@ full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
     const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
     const bool vec = full && aligned;
 
-    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    // the mean of the fp32 compensated gradients: summed in double in worker order, divided in
+    // double, rounded once to fp32
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
     const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll 4
     for (uint32_t m = 0; m < M; ++m) {
         const size_t off = static_cast<size_t>(m) * ld + e;
         const f32x4 sv = load4(g + off, vec, n_valid) + load4(c + off, vec, n_valid);
-        acc = (m == 0) ? sv : acc + sv;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            acc[j] += static_cast<double>(sv[j]);
         store4<MARSIT_STREAMING_STORES>(c + off, zero, vec, n_valid);
     }
-    const float fm = static_cast<float>(M);
+    const double dm = static_cast<double>(M);
     f32x4 mean;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-        mean[j] = acc[j] / fm;
+        mean[j] = static_cast<float>(acc[j] / dm);
     if (update != nullptr)
         store4<MARSIT_STREAMING_STORES>(update + e, mean, vec, n_valid);
     if (x_model != nullptr) {
@@ -579,15 +583,19 @@ full_sync_fast_kernel(const float *__restrict__ g, float *__restrict__ c,
     if (APPLY)
         xv = load4_stream(x_model + e);
     __builtin_amdgcn_sched_barrier(0);
-    f32x4 acc = gv[0] + cv[0];
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-    for (int m = 1; m < M; ++m)
-        acc = acc + (gv[m] + cv[m]);
-    const float fm = static_cast<float>(M);
+    for (int m = 0; m < M; ++m) {
+        const f32x4 sv = gv[m] + cv[m];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            acc[j] += static_cast<double>(sv[j]);
+    }
+    const double dm = static_cast<double>(M);
     f32x4 mean;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-        mean[j] = acc[j] / fm;
+        mean[j] = static_cast<float>(acc[j] / dm);
     if (!APPLY || update != nullptr)
         store4_stream(update + e, mean);
     if (APPLY)

@@ -11,7 +11,7 @@ from paper_2204_06787_amd import marsit
 
 pytestmark = pytest.mark.gpu
 
-KINDS = ["ring", "apply", "tree", "pipe", "exchange", "chain"]
+KINDS = ["ring", "apply", "tree", "pipe", "exchange", "chain", "full", "apply_full"]
 SPECIAL = np.array([0.0, -0.0, np.inf, -np.inf, 1e-45, -1e-45, 3e38, -3e38], dtype=np.float32)
 
 
@@ -56,6 +56,22 @@ def test_random_shapes(chunk):
         x_d = _place(x_h, off)
 
         c_ref = c_h.copy()
+        if kind in ("full", "apply_full"):
+            # the full-precision round: mean of the compensated gradients, compensation cleared
+            want_u = orc.full_sync(g_h, c_ref, d=d)
+            if kind == "full":
+                marsit.marsit_full_sync(g_d, c_d, u_d, d=d)
+            else:
+                marsit.marsit_step_apply(0, 3, g_d, c_d, x_d, u_d, b_d, scale, seed, grid_x=grid_x, d=d)
+            torch.cuda.synchronize()
+            assert np.array_equal(u_d.cpu().numpy().view(np.uint32), want_u.view(np.uint32)), case
+            got_c = c_d.cpu().numpy()
+            assert not got_c[:, :d].any() and np.array_equal(got_c[:, d:].view(np.uint32), c_h[:, d:].view(np.uint32)), case
+            assert bool((b_d == -1).all()), case                  # the bitmap is left alone
+            if kind == "apply_full":
+                want_x = orc.apply_update(x_h.copy(), want_u)
+                assert np.array_equal(x_d.cpu().numpy().view(np.uint32), want_x.view(np.uint32)), case
+            continue
         if kind == "tree":
             want_u, want_b = orc.tree_step(g_h, c_ref, scale, seed, d=d)
             marsit.marsit_tree_step_sim(g_d, c_d, u_d, b_d, scale, seed, d=d)

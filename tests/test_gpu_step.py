@@ -12,21 +12,6 @@ from gpu_util import assert_f32_parity, dev, host_bits, host_f32, unaligned_rows
 pytestmark = pytest.mark.gpu
 
 
-def _mean_tolerance(s64: np.ndarray, M: int) -> np.ndarray:
-    """fp32 running sum over m (M-1 roundings) and one division, against the oracle's double sum
-    rounded once: |err| <= M * 2^-24 * mean_m |s| (first order), plus one ulp of the result."""
-    return (M * 2.0 ** -24) * np.abs(s64).sum(axis=0) / M * 1.01 + 1e-45
-
-
-def _advance_model_tolerance(x_tol: np.ndarray, x_new: np.ndarray, u_tol):
-    """Bound on |x_gpu - x_oracle| after one more model update: exact while both sides subtracted
-    identical updates from identical models; once an update differed by at most u_tol, that
-    difference is carried, plus one rounding of the subtraction per round on each side."""
-    if u_tol is None and not x_tol.any():
-        return x_tol
-    return x_tol + (0 if u_tol is None else u_tol) + np.spacing(np.abs(x_new).astype(np.float32)).astype(np.float64)
-
-
 @pytest.mark.parametrize("M,d,ld,aligned", [(1, 100, 100, True), (3, 4099, 4100, True), (8, 100_000, 100_000, True),
                                              (16, 33_333, 33_336, True), (8, 5001, 5003, False), (64, 777, 780, True)])
 def test_full_sync(M, d, ld, aligned):
@@ -40,13 +25,13 @@ def test_full_sync(M, d, ld, aligned):
         g_d.copy_(dev(g_h))
         c_d.copy_(dev(c_h))
     pad_before = c_h[:, d:].copy()
-    s64 = g_h[:, :d].astype(np.float64) + c_h[:, :d]
     want = orc.full_sync(g_h, c_h, d=d)
     u = torch.empty(d, dtype=torch.float32, device="cuda")
     marsit.marsit_full_sync(g_d, c_d, u, d=d)
     torch.cuda.synchronize()
     got = host_f32(u)
-    assert np.all(np.abs(got.astype(np.float64) - want) <= _mean_tolerance(s64, M) + np.spacing(np.abs(want)))
+    # both sides add the fp32 terms in double in worker order, divide in double and round once
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
     got_c = host_f32(c_d)
     assert not got_c[:, :d].any()                                # c <- 0
     assert np.array_equal(got_c[:, d:], pad_before)              # padding untouched
@@ -111,26 +96,20 @@ def test_sgd_driver_with_local_momentum():
     c_h = np.zeros((M, d), dtype=np.float32)
     buf_h = np.zeros((M, d), dtype=np.float32)
     opt = MarsitSGD(dev(x_h), M=M, K=K, eta_s=2e-3, seed=31, momentum=0.9)
-    x_tol = np.zeros(d)
     for t in range(5):
         grad_h = rng.standard_normal((M, d)).astype(np.float32)
         opt.step_from_raw_gradients(dev(grad_h), eta_l=0.01)
         g_h = orc.local_momentum(buf_h, grad_h, 0.9, 0.01)
-        u_tol = None
         if t % K == 0:
-            s64 = g_h.astype(np.float64) + c_h
             u_h = orc.full_sync(g_h, c_h)
-            u_tol = _mean_tolerance(s64, M) + np.spacing(np.abs(u_h))
         else:
             u_h, _, _ = orc.sync_step(g_h, c_h, 2e-3, 31 + t)
         x_h = orc.apply_update(x_h, u_h)
-        x_tol = _advance_model_tolerance(x_tol, x_h, u_tol)
         torch.cuda.synchronize()
         assert_f32_parity(host_f32(opt.buf), buf_h, f"momentum buffers, round {t}")
         assert_f32_parity(host_f32(opt.c), c_h, f"compensation, round {t}")
-        assert np.all(np.abs(host_f32(opt.x).astype(np.float64) - x_h) <= x_tol), t
-        if u_tol is None:
-            assert np.array_equal(host_f32(opt.update), u_h), t
+        assert_f32_parity(host_f32(opt.update), u_h, f"update, round {t}")
+        assert_f32_parity(host_f32(opt.x), x_h, f"model, round {t}")
 
 
 @pytest.mark.parametrize("M,grid_x,d,ld,offset", [
@@ -153,7 +132,6 @@ def test_step_apply(M, grid_x, d, ld, offset, keep_update):
         x_d = dev(x_h)
     u_d = torch.full((d,), 7.0, dtype=torch.float32, device="cuda") if keep_update else None
     bits = marsit.new_bitmap(d)
-    x_tol = np.zeros(d)
     for t in range(5):
         g_h = (0.01 * rng.standard_normal((M, ld))).astype(np.float32)
         if offset:
@@ -163,21 +141,15 @@ def test_step_apply(M, grid_x, d, ld, offset, keep_update):
             g_d = dev(g_h)
         marsit.marsit_step_apply(t, K, g_d, c_d, x_d, u_d, bits, scale, seed0 + t, grid_x=grid_x, d=d)
         torch.cuda.synchronize()
-        u_tol = None
         if t % K == 0:
-            s64 = g_h[:, :d].astype(np.float64) + c_h[:, :d]
             want_u = orc.full_sync(g_h, c_h, d=d)
-            u_tol = _mean_tolerance(s64, M) + np.spacing(np.abs(want_u))
-            if keep_update:
-                assert np.all(np.abs(host_f32(u_d).astype(np.float64) - want_u) <= u_tol), t
         else:
             want_u, want_b, _ = orc.sync_step(g_h, c_h, scale, seed0 + t, grid_x=grid_x, d=d)
             assert np.array_equal(host_bits(bits), want_b), t
-            if keep_update:
-                assert np.array_equal(host_f32(u_d), want_u), t
+        if keep_update:
+            assert_f32_parity(host_f32(u_d), want_u, f"update, round {t}")
         x_h = orc.apply_update(x_h, want_u)
-        x_tol = _advance_model_tolerance(x_tol, x_h, u_tol)
-        assert np.all(np.abs(host_f32(x_d).astype(np.float64) - x_h) <= x_tol), t
+        assert_f32_parity(host_f32(x_d), x_h, f"model, round {t}")
         assert_f32_parity(host_f32(c_d)[:, :d], c_h[:, :d], f"compensation, round {t}")
         assert np.array_equal(host_f32(c_d)[:, d:], c_h[:, d:])                     # padding untouched
 
@@ -204,8 +176,7 @@ def test_step_apply_equals_step_then_apply_update_bit_for_bit():
 @pytest.mark.parametrize("M,grid_x,K", [(8, 0, 4), (16, 4, 3), (3, 0, 1), (5, 0, 100)])
 def test_marsit_driven_sgd_loop(M, grid_x, K):
     """Algorithm 2 with Algorithm 1 inside: T rounds, a full-precision round whenever t mod K == 0,
-    x <- x - g_t after every round.  One-bit rounds must match the oracle bit for bit; the
-    full-precision rounds within the fp32 summation tolerance."""
+    x <- x - g_t after every round.  Every round must match the oracle bit for bit."""
     d, T, scale, seed0 = 20_000 + 7, 9, 1e-3, 31
     wl = workloads.Workload("loop", M=M, d=d, grid_x=grid_x, steps=T, scale=scale, dist="normal", std=0.01)
     x_d = torch.zeros(d, dtype=torch.float32, device="cuda")
@@ -214,7 +185,6 @@ def test_marsit_driven_sgd_loop(M, grid_x, K):
     c_h = np.zeros((M, d), dtype=np.float32)
     u_d = torch.empty(d, dtype=torch.float32, device="cuda")
     bits = marsit.new_bitmap(d)
-    x_tol = np.zeros(d)
     for t in range(T):
         g_d = workloads.make_gradients(wl, t, seed=seed0, device="cuda")
         g_h = host_f32(g_d).copy()
@@ -228,16 +198,11 @@ def test_marsit_driven_sgd_loop(M, grid_x, K):
             assert np.array_equal(host_f32(u_d), want_u), t
             assert_f32_parity(host_f32(c_d), c_h, f"c, round {t}")
         else:
-            s64 = g_h.astype(np.float64) + c_h
             want_u = orc.full_sync(g_h, c_h)
-            got_u = host_f32(u_d)
-            assert np.all(np.abs(got_u.astype(np.float64) - want_u) <= _mean_tolerance(s64, M) + np.spacing(np.abs(want_u))), t
+            assert_f32_parity(host_f32(u_d), want_u, f"mean update, round {t}")
             assert not host_f32(c_d).any()
-        # the model: the oracle's own update on the host copy; exact unless a full-precision round
-        # (whose update may differ by the summation tolerance) has been applied
         x_h = orc.apply_update(x_h, want_u)
-        x_tol = _advance_model_tolerance(x_tol, x_h, None if t % K else _mean_tolerance(s64, M) + np.spacing(np.abs(want_u)))
-        assert np.all(np.abs(host_f32(x_d).astype(np.float64) - x_h) <= x_tol), t
+        assert_f32_parity(host_f32(x_d), x_h, f"model, round {t}")
 
 
 def test_step_can_be_captured_in_a_hip_graph():
