@@ -185,6 +185,11 @@ int marsit_tree_step_sim(const float *g, float *c, float *update_out, uint64_t *
                          uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed,
                          void *stream);
 
+/* marsit_tree_step_sim with the model update x[e] <- x[e] - g_t[e] in the same pass (as
+ * marsit_step_apply does for the ring and the torus); update_out may be NULL, x must not alias it. */
+int marsit_tree_step_apply(const float *g, float *c, float *x, float *update_out, uint64_t *bits_out,
+                           uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed, void *stream);
+
 /*
  * The same pass as marsit_ring_step_sim, hop by hop, as a real transport would run it: one
  * marsit_compress per worker, then for every part the chain of M-1 marsit_hop_merge launches over

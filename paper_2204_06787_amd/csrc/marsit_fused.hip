@@ -373,11 +373,11 @@ sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
 // k = 0, 2*2^l, ... folds the vector of worker k + 2^l into its own; each side stands for the
 // workers of its subtree.  Same lane layout and launch shape as the ring kernel.
 // -------------------------------------------------------------------------------------------------
-template <int M>
+template <int M, bool APPLY>
 __global__ void __launch_bounds__(kSyncBlock)
 tree_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
                  uint32_t *__restrict__ bits32, uint64_t n_cols, uint64_t ld, uint32_t scale_bits,
-                 uint32_t key0, uint32_t key1)
+                 uint32_t key0, uint32_t key1, float *__restrict__ x_model)
 {
     const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
     const uint32_t w = static_cast<uint32_t>(col >> 4);
@@ -392,6 +392,9 @@ tree_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
             gv[m] = load4_stream(g + static_cast<size_t>(m) * ld + e);
             cv[m] = load4_stream(c + static_cast<size_t>(m) * ld + e);
         }
+        f32x4 xv = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (APPLY)
+            xv = load4_stream(x_model + e);
         __builtin_amdgcn_sched_barrier(0);
 
         // Draws first, data later: every node of the tree carries, per bit, the index of the worker
@@ -447,7 +450,10 @@ tree_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
             upd[j] = __uint_as_float(scale_bits ^ sign);
             nib |= (sign == 0u) ? (1u << j) : 0u;
         }
-        store4_stream(update + e, upd);
+        if (!APPLY || update != nullptr)
+            store4_stream(update + e, upd);
+        if (APPLY)
+            store4_stream(x_model + e, xv - upd);
 #pragma unroll
         for (int m = 0; m < M; ++m)
             store4_stream(c + static_cast<size_t>(m) * ld + e, s[m] - upd);
@@ -467,7 +473,8 @@ __global__ void __launch_bounds__(kSyncBlock)
 tree_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
                          float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
                          uint64_t ld, uint64_t col_begin, uint32_t scale_bits, uint32_t key0,
-                         uint32_t key1, uint32_t M, uint32_t top_level, bool aligned)
+                         uint32_t key1, uint32_t M, uint32_t top_level, bool aligned,
+                         float *__restrict__ x_model)
 {
     const uint64_t n_cols = (d + 3) >> 2;
     const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
@@ -505,7 +512,12 @@ tree_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
             if (j == 0) upd.x = uval; else if (j == 1) upd.y = uval; else if (j == 2) upd.z = uval; else upd.w = uval;
             nib |= (sign == 0u) ? (1u << j) : 0u;
         }
-        store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
+        if (update != nullptr)
+            store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
+        if (x_model != nullptr) {
+            const f32x4 xv = load4(x_model + e, vec, n_valid);
+            store4<MARSIT_STREAMING_STORES>(x_model + e, xv - upd, vec, n_valid);
+        }
         if (STAGED)
             compensate_from_stage(c, stage, upd, M, ld, e, vec, n_valid);
         else
@@ -694,17 +706,21 @@ void launch_full_sync(const float *g, float *c, float *update, uint64_t n_cols, 
 
 template <int M>
 void launch_tree_step(const float *g, float *c, float *update, uint32_t *bits32, uint64_t n_cols,
-                      uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1,
+                      uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1, float *x_model,
                       hipStream_t stream)
 {
     const uint32_t lds = throttle_lds_bytes(fused_waves_per_cu(M, 1));
     const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
-    hipLaunchKernelGGL((tree_step_kernel<M>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c, update,
-                       bits32, n_cols, ld, scale_bits, key0, key1);
+    if (x_model == nullptr)
+        hipLaunchKernelGGL((tree_step_kernel<M, false>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,
+                           update, bits32, n_cols, ld, scale_bits, key0, key1, x_model);
+    else
+        hipLaunchKernelGGL((tree_step_kernel<M, true>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,
+                           update, bits32, n_cols, ld, scale_bits, key0, key1, x_model);
 }
 
 using TreeLauncher = void (*)(const float *, float *, float *, uint32_t *, uint64_t, uint64_t, uint32_t,
-                              uint32_t, uint32_t, hipStream_t);
+                              uint32_t, uint32_t, float *, hipStream_t);
 
 TreeLauncher find_tree(uint32_t M)
 {
@@ -860,19 +876,20 @@ int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *
     return ring_step_impl(g, c, update_out, bits_out, nullptr, M, d, ld, scale, seed, grid_x, stream);
 }
 
-int marsit_tree_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
-                         uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed, void *stream)
+static int tree_step_impl(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                          float *x_model, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                          uint64_t seed, void *stream)
 {
-    if (g == nullptr || c == nullptr || update_out == nullptr || M == 0 ||
+    if (g == nullptr || c == nullptr || (update_out == nullptr && x_model == nullptr) || M == 0 ||
         M > MARSIT_MAX_WORKERS || ld < d || !std::isfinite(scale) || d > kMaxElements)
         return MARSIT_EINVAL;
     if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(update_out, 4) ||
-        !aligned_to(bits_out, 8))
+        !aligned_to(bits_out, 8) || !aligned_to(x_model, 4))
         return MARSIT_EALIGN;
     if (d == 0)
         return MARSIT_OK;
     const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
-                         (ld % 4 == 0);
+                         aligned_to(x_model, 16) && (ld % 4 == 0);
     const uint32_t scale_bits = float_bits_host(scale);
     const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
     uint32_t *bits32 = reinterpret_cast<uint32_t *>(bits_out);
@@ -883,7 +900,7 @@ int marsit_tree_step_sim(const float *g, float *c, float *update_out, uint64_t *
     if (fast != nullptr) {
         const uint64_t fast_cols = (d / 64) * 16;
         if (fast_cols > 0) {
-            fast(g, c, update_out, bits32, fast_cols, ld, scale_bits, key0, key1, s);
+            fast(g, c, update_out, bits32, fast_cols, ld, scale_bits, key0, key1, x_model, s);
             const int rc = finish_launch();
             if (rc != MARSIT_OK)
                 return rc;
@@ -900,14 +917,30 @@ int marsit_tree_step_sim(const float *g, float *c, float *update_out, uint64_t *
         if (M <= kMaxStagedWorkers)
             hipLaunchKernelGGL(tree_step_generic_kernel<true>, dim3(blocks), dim3(kSyncBlock),
                                generic_lds_bytes(M), s, g, c, update_out, bits32, d, ld,
-                               generic_col_begin, scale_bits, key0, key1, M, top_level, aligned);
+                               generic_col_begin, scale_bits, key0, key1, M, top_level, aligned, x_model);
         else
             hipLaunchKernelGGL(tree_step_generic_kernel<false>, dim3(blocks), dim3(kSyncBlock), 0, s, g, c,
                                update_out, bits32, d, ld, generic_col_begin, scale_bits, key0, key1, M,
-                               top_level, aligned);
+                               top_level, aligned, x_model);
         return finish_launch();
     }
     return MARSIT_OK;
+}
+
+int marsit_tree_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                         uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed, void *stream)
+{
+    if (update_out == nullptr)
+        return MARSIT_EINVAL;
+    return tree_step_impl(g, c, update_out, bits_out, nullptr, M, d, ld, scale, seed, stream);
+}
+
+int marsit_tree_step_apply(const float *g, float *c, float *x, float *update_out, uint64_t *bits_out,
+                           uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed, void *stream)
+{
+    if (x == nullptr || x == update_out)
+        return MARSIT_EINVAL;
+    return tree_step_impl(g, c, update_out, bits_out, x, M, d, ld, scale, seed, stream);
 }
 
 int marsit_full_sync(const float *g, float *c, float *update_out, uint32_t M, uint64_t d,

@@ -3,7 +3,7 @@
 A thin driver: it owns the state Algorithm 2 carries between rounds (the model ``x``, the
 compensation vectors ``c``, the round counter) and calls the library once per round for the
 synchronisation (Algorithm 1: one-bit pass, or the full-precision round every ``K`` rounds) with the
-model update in the same pass (the tree schedule takes a second call for the model update).  All arithmetic runs in the HIP kernels.
+model update in the same pass.  All arithmetic runs in the HIP kernels.
 """
 
 from __future__ import annotations
@@ -52,11 +52,9 @@ class MarsitSGD:
         multiplied by the local step size.  Returns the global update that was applied to ``x``."""
         seed = (self.seed + self.t) & 0xFFFFFFFFFFFFFFFF
         if self.schedule == "tree" and self.t % self.K != 0:
-            marsit.marsit_tree_step_sim(scaled_grads, self.c, self.update, self.bits, self.eta_s, seed,
-                                        stream=stream)
-            marsit.marsit_apply_update(self.x, self.update, stream=stream)
+            marsit.marsit_tree_step_apply(scaled_grads, self.c, self.x, self.update, self.bits, self.eta_s,
+                                          seed, stream=stream)
         else:
-            # synchronisation and model update in one pass
             marsit.marsit_step_apply(self.t, self.K, scaled_grads, self.c, self.x, self.update, self.bits,
                                      self.eta_s, seed, grid_x=self.grid_x, stream=stream)
         self.t += 1

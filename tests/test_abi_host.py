@@ -154,6 +154,12 @@ def test_other_entry_points_argument_validation(lib):
     assert lib.marsit_exchange_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, 4, 64, 64, 1.0, 1, 3, None) == marsit.EINVAL
     assert lib.marsit_exchange_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, 4, 0, 64, 1.0, 1, 0, None) == marsit.OK
 
+    assert lib.marsit_tree_step_apply(FAKE, FAKE, None, FAKE, FAKE, 4, 64, 64, 1.0, 1, None) == marsit.EINVAL
+    assert lib.marsit_tree_step_apply(FAKE, FAKE, FAKE, FAKE, FAKE, 4, 64, 64, 1.0, 1, None) == marsit.EINVAL   # x aliases update
+    assert lib.marsit_tree_step_apply(FAKE, FAKE, FAKE + 2, None, FAKE, 4, 64, 64, 1.0, 1, None) == marsit.EALIGN
+    assert lib.marsit_tree_step_apply(FAKE, FAKE, FAKE, None, None, 4, 0, 64, 1.0, 1, None) == marsit.OK
+    assert lib.marsit_tree_step_sim(FAKE, FAKE, None, FAKE, 4, 64, 64, 1.0, 1, None) == marsit.EINVAL
+
     assert lib.marsit_pipeline_create(None, 4) == marsit.EINVAL
     assert lib.marsit_pipeline_destroy(None) == marsit.EINVAL
     assert lib.marsit_pipeline_ring_step(None, FAKE, FAKE, FAKE, FAKE, FAKE, 64, 64, 1.0, 1, None) == marsit.EINVAL
