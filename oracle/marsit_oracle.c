@@ -30,6 +30,8 @@
  *   - 2D torus, X columns by Y rows, worker (y, x) = y*X + x: rows first (ring over the X
  *     columns inside every row, parts = X row-parts of the W words), then columns (ring over
  *     the Y row results, every row-part split again in Y sub-parts).
+ *   - A torus whose last row is short (M not a multiple of X): rows as above with their own
+ *     length, the column merges weighted by the workers each side stands for.
  *   - Arithmetic type: the gradients and the compensation are fp32 vectors (Section 1 speaks
  *     of 32-bit single precision), so the compensated sum and the compensation update are one fp32 round-to-nearest-even
  *     operation each.  Build with -ffp-contract=off and without fast-math.
@@ -472,6 +474,91 @@ int oracle_hop_merge_weighted(const uint64_t *recv, const uint64_t *local, uint6
     for (uint64_t i = 0; i < n_words; ++i)
         out[i] = oracle_merge_word_weighted(recv[i], local[i], w_recv, w_local, hop_id, seed,
                                             word_begin + i);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * The one-bit pass over a torus whose last row is short (M need not be a multiple of the number
+ * of columns; Section 5 names further all-reduce layouts without detail):
+ *   X columns, Y = ceil(M / X) rows, worker (y, x) = y*X + x for y*X + x < M; row y has
+ *   X_y = X workers, except the last one with M - (Y-1)*X.
+ *   Row phase: the W words are split in X row-parts; in row y the chain of row-part a starts at
+ *   column a mod X_y and folds columns (start + h) mod X_y, h = 1..X_y-1, fold count h + 1,
+ *   hop id (y << 8) | h.  The row result stands for X_y workers.
+ *   Column phase: row-part a is split again in Y sub-parts; the chain of sub-part b starts at
+ *   row b and folds rows (b + k) mod Y, k = 1..Y-1, each side weighted by the workers it stands
+ *   for (the weighted merge), hop id (1 << 16) | k.
+ * With X dividing M every weight ratio is 1/(k+1) and this is oracle_sync_step bit for bit.
+ * ---------------------------------------------------------------------------------------- */
+int oracle_ragged_torus_step(const float *g, float *c, float *update, uint64_t *bits_final,
+                             uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed,
+                             uint32_t grid_x, int threads)
+{
+    if (M == 0 || M > ORACLE_MAX_WORKERS || ld < d || g == NULL || c == NULL || update == NULL ||
+        grid_x == 0 || grid_x > M)
+        return -1;
+    const uint32_t X = grid_x;
+    const uint32_t Y = (M + X - 1) / X;
+    const uint32_t X_last = M - (Y - 1) * X;
+    if (d == 0)
+        return 0;
+    if (threads < 1)
+        threads = 1;
+
+    uint64_t W = (d + 63u) / 64u;
+    float *s = (float *)malloc((size_t)M * d * sizeof(float));
+    uint64_t *L = (uint64_t *)malloc((size_t)M * W * sizeof(uint64_t));
+    uint64_t *B = (uint64_t *)malloc((size_t)W * sizeof(uint64_t));
+    if (s == NULL || L == NULL || B == NULL) {
+        free(s); free(L); free(B);
+        return -2;
+    }
+    for (uint32_t m = 0; m < M; ++m) {
+        oracle_add_compensation(g + (size_t)m * ld, c + (size_t)m * ld, s + (size_t)m * d, d);
+        oracle_sign_pack(s + (size_t)m * d, L + (size_t)m * W, d);
+    }
+    uint64_t row_bounds[ORACLE_MAX_WORKERS + 1];
+    oracle_split_bounds(0, W, X, row_bounds);
+
+    #pragma omp parallel for schedule(static) num_threads(threads) if (threads > 1)
+    for (uint64_t w = 0; w < W; ++w) {
+        uint32_t a = part_of(w, row_bounds, X);
+
+        uint64_t R[ORACLE_MAX_WORKERS];
+        uint32_t weight[ORACLE_MAX_WORKERS];
+        for (uint32_t y = 0; y < Y; ++y) {
+            uint32_t Xy = (y + 1 < Y) ? X : X_last;
+            uint32_t start = a % Xy;
+            uint64_t r = L[(size_t)(y * X + start) * W + w];
+            for (uint32_t h = 1; h < Xy; ++h) {
+                uint32_t col = (start + h) % Xy;
+                uint64_t local = L[(size_t)(y * X + col) * W + w];
+                r = oracle_merge_word(r, local, h + 1u, oracle_hop_id(0, y, h), seed, w);
+            }
+            R[y] = r;
+            weight[y] = Xy;
+        }
+
+        uint64_t col_bounds[ORACLE_MAX_WORKERS + 1];
+        oracle_split_bounds(row_bounds[a], row_bounds[a + 1] - row_bounds[a], Y, col_bounds);
+        uint32_t b = part_of(w, col_bounds, Y);
+        uint64_t r = R[b];
+        uint32_t gathered = weight[b];                 /* workers the running result stands for */
+        for (uint32_t k = 1; k < Y; ++k) {
+            uint32_t row = (b + k) % Y;
+            r = oracle_merge_word_weighted(r, R[row], gathered, weight[row], oracle_hop_id(1, 0, k),
+                                           seed, w);
+            gathered += weight[row];
+        }
+        B[w] = r;
+    }
+
+    oracle_decode(B, scale, update, d);
+    for (uint32_t m = 0; m < M; ++m)
+        oracle_compensate(s + (size_t)m * d, update, c + (size_t)m * ld, d);
+    if (bits_final != NULL)
+        memcpy(bits_final, B, (size_t)W * sizeof(uint64_t));
+    free(s); free(L); free(B);
     return 0;
 }
 

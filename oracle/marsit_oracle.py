@@ -71,6 +71,8 @@ def _load():
     lib.oracle_hop_id.restype = u32
     lib.oracle_sync_step.argtypes = [vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, ctypes.c_int]
     lib.oracle_sync_step.restype = ctypes.c_int
+    lib.oracle_ragged_torus_step.argtypes = [vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, ctypes.c_int]
+    lib.oracle_ragged_torus_step.restype = ctypes.c_int
     lib.oracle_full_sync.argtypes = [vp, vp, vp, u32, u64, u64]
     lib.oracle_full_sync.restype = ctypes.c_int
     lib.oracle_apply_update.argtypes = [vp, vp, u64]
@@ -244,6 +246,23 @@ def sync_step(g, c, scale: float, seed: int, grid_x: int = 0, d: int | None = No
     if rc != 0:
         raise ValueError(f"oracle_sync_step failed (rc={rc})")
     return update, bits, maps
+
+
+def ragged_torus_step(g, c, scale: float, seed: int, grid_x: int, d: int | None = None, threads: int = 1):
+    """One one-bit pass over a torus of ``grid_x`` columns whose last row may be short (any
+    ``1 <= grid_x <= M``); ``c`` is updated in place.  Returns ``(update[d], bits_final[W])``."""
+    g = _f32(g, "g")
+    c = _f32(c, "c")
+    assert g.ndim == 2 and g.shape == c.shape
+    M, ld = g.shape
+    d = ld if d is None else int(d)
+    update = np.zeros(d, dtype=np.float32)
+    bits = np.zeros(n_words(d), dtype=np.uint64)
+    rc = _load().oracle_ragged_torus_step(_ptr(g), _ptr(c), _ptr(update), _ptr(bits), M, d, ld, scale,
+                                          seed & 0xFFFFFFFFFFFFFFFF, grid_x, threads)
+    if rc != 0:
+        raise ValueError(f"oracle_ragged_torus_step failed (rc={rc})")
+    return update, bits
 
 
 def full_sync(g, c, d: int | None = None):

@@ -30,6 +30,7 @@ static int run_case(uint32_t M, uint64_t d, uint64_t ld, uint32_t grid_x)
     int rc = 0;
     rc |= oracle_sync_step(g, c, update, bits, maps, M, d, ld, 1e-3f, 42, grid_x, 1);
     rc |= oracle_sync_step(g, c, update, bits, NULL, M, d, ld, 1e-3f, 43, grid_x, 2);
+    rc |= oracle_ragged_torus_step(g, c, update, bits, M, d, ld, 1e-3f, 46, (M > 2) ? M - 1 : 1, 2);
     if (grid_x == 0) {
         rc |= oracle_tree_step(g, c, update, bits, M, d, ld, 1e-3f, 44);
         rc |= oracle_cascade_ring_step(g, c, update, bits, norms, M, d, ld, 45);

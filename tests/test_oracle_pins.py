@@ -612,6 +612,122 @@ def test_weighted_threshold_generalises_eq2():
         assert orc.merge_word_weighted(recv, local, m - 1, 1, 5, 99, 1234) == orc.merge_word(recv, local, m, 5, 99, 1234)
 
 
+# ---------------------------------------------------------------------------------------------
+# Torus whose last row is short (M not a multiple of the number of columns)
+# ---------------------------------------------------------------------------------------------
+
+def _ragged_rows(M, X):
+    Y = -(-M // X)
+    return [X] * (Y - 1) + [M - (Y - 1) * X]
+
+
+@pytest.mark.parametrize("M,X", [(3, 2), (5, 2), (5, 3), (7, 3), (5, 4), (7, 2), (4, 3)])
+def test_exact_unbiasedness_ragged_torus(M, X):
+    """Rows with fold counts 2..X_y, then columns over the row results, each weighted by the number
+    of workers it stands for: P(final = 1) = (+ workers) / M exactly, whatever the start row."""
+    rows = _ragged_rows(M, X)
+    Y = len(rows)
+    n_draws = sum(r - 1 for r in rows) + (Y - 1)
+    for b in range(Y):                                       # the column chain may start at any row
+        for bits in itertools.product((0, 1), repeat=M):
+            total = Fraction(0)
+            for draws in itertools.product((0, 1), repeat=n_draws):
+                it = iter(draws)
+                weight = Fraction(1)
+                results = []
+                for y, Xy in enumerate(rows):
+                    r = bits[y * X]
+                    for h in range(1, Xy):
+                        t = next(it)
+                        weight *= Fraction(1, h + 1) if t else Fraction(h, h + 1)
+                        l = bits[y * X + h]
+                        r = orc.odot(r, l, orc.transient_from_keep(l, t)) & 1
+                    results.append(r)
+                r, gathered = results[b], rows[b]
+                for k in range(1, Y):
+                    y = (b + k) % Y
+                    t = next(it)
+                    p = Fraction(orc.weighted_threshold(gathered, rows[y]), 1 << 32)
+                    assert abs(p - Fraction(rows[y], gathered + rows[y])) < Fraction(1, 1 << 32)
+                    p = Fraction(rows[y], gathered + rows[y])
+                    weight *= p if t else 1 - p
+                    r = orc.odot(r, results[y], orc.transient_from_keep(results[y], t)) & 1
+                    gathered += rows[y]
+                total += weight * r
+            assert total == Fraction(sum(bits), M)
+
+
+@pytest.mark.parametrize("M,X,d", [(4, 2, 64 * 9 + 5), (6, 3, 64 * 7), (8, 8, 64 * 5 + 1), (16, 4, 64 * 6), (3, 1, 64 * 4 + 9)])
+def test_ragged_torus_with_full_rows_is_the_torus(M, X, d):
+    """With X dividing M every weight ratio is 1/(k+1): the same bits as the plain schedule."""
+    rng = np.random.default_rng(300 + M)
+    g = rng.standard_normal((M, d)).astype(np.float32)
+    c = (0.3 * rng.standard_normal((M, d))).astype(np.float32)
+    c1, c2 = c.copy(), c.copy()
+    u1, b1 = orc.ragged_torus_step(g, c1, 1e-3, 77, X)
+    u2, b2, _ = orc.sync_step(g, c2, 1e-3, 77, grid_x=X)
+    assert np.array_equal(b1, b2) and np.array_equal(u1, u2) and np.array_equal(c1, c2)
+
+
+def _ragged_reservoir_bits(signs, d, M, X, seed):
+    """Second formulation, pure Python: per bit, the last successful draw of the column chain
+    names a row, the last successful draw of that row's chain names a worker."""
+    rows = _ragged_rows(M, X)
+    Y = len(rows)
+    W = (d + 63) // 64
+    row_bounds = _floor_bounds(0, W, X)
+    final = np.zeros(d, dtype=np.uint8)
+    for e in range(d):
+        w, j = divmod(e, 64)
+        a = _part(w, row_bounds)
+        col_bounds = _floor_bounds(row_bounds[a], row_bounds[a + 1] - row_bounds[a], Y)
+        b = _part(w, col_bounds)
+        pick, gathered = 0, rows[b]
+        for k in range(1, Y):
+            y = (b + k) % Y
+            if philox_ref.stream_u32(seed, (1 << 16) | k, w, j) < (rows[y] << 32) // (gathered + rows[y]):
+                pick = k
+            gathered += rows[y]
+        y = (b + pick) % Y
+        start, col = a % rows[y], 0
+        for h in range(1, rows[y]):
+            if philox_ref.stream_u32(seed, (y << 8) | h, w, j) < (1 << 32) // (h + 1):
+                col = h
+        final[e] = signs[y * X + (start + col) % rows[y]][e]
+    return final
+
+
+@pytest.mark.parametrize("M,X,d", [(5, 2, 64 * 9 + 5), (7, 3, 64 * 8), (5, 4, 64 * 6 + 63), (11, 4, 64 * 7 + 1), (3, 2, 70)])
+def test_ragged_torus_second_formulation(M, X, d):
+    rng = np.random.default_rng(400 + M)
+    g = rng.standard_normal((M, d)).astype(np.float32)
+    c = (0.3 * rng.standard_normal((M, d))).astype(np.float32)
+    seed = 0xFACE0000 + M
+    signs = (~np.signbit(g + c)).astype(np.uint8)
+    want = _ragged_reservoir_bits(signs, d, M, X, seed)
+    c_after = c.copy()
+    update, bits = orc.ragged_torus_step(g, c_after, 0.5, seed, X)
+    got = ((bits[np.arange(d) // 64] >> (np.arange(d) % 64).astype(np.uint64)) & np.uint64(1)).astype(np.uint8)
+    assert np.array_equal(got, want)
+    assert np.array_equal(update, np.where(want == 1, np.float32(0.5), np.float32(-0.5)))
+    assert np.array_equal(c_after, (g + c) - update)                 # compensation update, fp32
+
+
+@pytest.mark.parametrize("M,X,patterns", [(5, 2, list(range(32))), (7, 3, [0, 1, 64, 3, 0x38, 0x55, 0x2A, 0x7F, 0x41, 0x0F]),
+                                          (13, 4, [0x0001, 0x1000, 0x00FF, 0x1F00, 0x0F0F, 0x1555, 0x1FFF])])
+def test_ragged_torus_empirical_unbiasedness(M, X, patterns):
+    n_rep = 1 << 17
+    g = _pattern_inputs(patterns, M, n_rep)
+    c = np.zeros_like(g)
+    update, bits = orc.ragged_torus_step(g, c, 1.0, 0xABCDEF + M, X, threads=8)
+    plus = (update > 0).reshape(len(patterns), n_rep).mean(axis=1)
+    for p, pat in enumerate(patterns):
+        k = bin(pat).count("1")
+        prob = k / M
+        sigma = np.sqrt(max(prob * (1 - prob), 1e-12) / n_rep)
+        assert abs(plus[p] - prob) <= 5 * sigma + 1e-9, (pat, plus[p], prob)
+
+
 def _tree_merges(M):
     """(level, receiver, sender, w_local, w_recv) of the binary reduction tree, bottom level first."""
     out, stride, level = [], 1, 0
