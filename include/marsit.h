@@ -191,6 +191,23 @@ int marsit_tree_step_apply(const float *g, float *c, float *x, float *update_out
                            uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed, void *stream);
 
 /*
+ * The one-bit pass over a torus whose last row may be short (any 1 <= grid_x <= M; Section 5 names
+ * further all-reduce layouts without detail): X = grid_x columns, Y = ceil(M / X) rows, worker
+ * (y, x) = y*X + x; the last row has M - (Y-1)*X workers.  Row phase as in marsit_ring_step_sim
+ * with every row's own length (the chain of row-part a starts at column a mod X_y); the column
+ * merges are weighted by the number of workers each side stands for, as in
+ * marsit_hop_merge_weighted, with hop id (1 << 16) | k.  If grid_x divides M this is
+ * marsit_ring_step_sim (same results, same kernels).  Other arguments as there; the _apply form
+ * also updates the model, as marsit_step_apply does.
+ */
+int marsit_ragged_torus_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                                 uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed,
+                                 uint32_t grid_x, void *stream);
+int marsit_ragged_torus_step_apply(const float *g, float *c, float *x, float *update_out,
+                                   uint64_t *bits_out, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                                   uint64_t seed, uint32_t grid_x, void *stream);
+
+/*
  * The same pass as marsit_ring_step_sim, hop by hop, as a real transport would run it: one
  * marsit_compress per worker, then for every part the chain of M-1 marsit_hop_merge launches over
  * that part's words (row chains, then column chains on a torus), then one marsit_decode_compensate

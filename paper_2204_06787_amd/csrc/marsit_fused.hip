@@ -369,6 +369,101 @@ sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
 }
 
 // -------------------------------------------------------------------------------------------------
+// Fused pass over a torus whose last row is short (M is not a multiple of the X columns): rows of
+// X workers, the last one of X_last; the row chains run over the row's own length and the column
+// merges are weighted by the workers each side stands for.  Same structure as the generic kernel:
+// s staged in LDS, chains evaluated on the draws alone (column chain first, then the chain of the
+// row it names), one sign looked up per bit.  parts.bound[0..X] holds the X row-parts; the Y
+// sub-parts of a row-part follow the same floor rule and are found arithmetically.
+// -------------------------------------------------------------------------------------------------
+template <bool STAGED>
+__global__ void __launch_bounds__(kSyncBlock)
+sync_step_ragged_kernel(const float *__restrict__ g, float *__restrict__ c,
+                        float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
+                        uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1, uint32_t M,
+                        uint32_t X, uint32_t Y, uint32_t X_last, bool aligned, PartTable parts,
+                        ThresholdTable thresholds, float *__restrict__ x_model)
+{
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
+    const uint32_t w = static_cast<uint32_t>(col >> 4);
+    const uint32_t q = static_cast<uint32_t>(col) & 15u;
+    uint32_t nib = 0;
+
+    if (col < n_cols) {
+        const uint64_t e = col << 2;
+        const bool full = e + 4 <= d;
+        const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+        const bool vec = full && aligned;
+
+        // split step: row-part a, then sub-part b of it
+        uint32_t a = 0;
+        for (uint32_t k = 1; k < X; ++k)
+            a += (w >= parts.bound[k]) ? 1u : 0u;
+        const uint32_t lo = parts.bound[a];
+        const uint64_t n_part = parts.bound[a + 1] - lo;
+        uint32_t b = 0;
+        for (uint32_t k = 1; k < Y; ++k)
+            b += (w >= lo + static_cast<uint32_t>((k * n_part) / Y)) ? 1u : 0u;
+
+        f32x4 *stage = reinterpret_cast<f32x4 *>(marsit_dynamic_lds);
+        if (STAGED)
+            stage_sums(g, c, stage, M, ld, e, vec, n_valid);
+
+        // column chain: which row result survives, per bit (weighted draws)
+        uint32_t pick_col[4] = {0, 0, 0, 0};
+        uint32_t gathered = (b + 1u == Y) ? X_last : X;
+        for (uint32_t k = 1; k < Y; ++k) {
+            uint32_t y = b + k;
+            y = (y >= Y) ? y - Y : y;
+            const uint32_t w_local = (y + 1u == Y) ? X_last : X;
+            const uint32_t thr = weighted_threshold(gathered, w_local);
+            uint32_t u[4];
+            philox4x32_10(q, col_hop_id(k), w, 0u, key0, key1, u);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                pick_col[j] = (u[j] < thr) ? k : pick_col[j];
+            gathered += w_local;
+        }
+
+        f32x4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
+        for (uint32_t j = 0; j < n_valid; ++j) {
+            const uint32_t pc = (j == 0) ? pick_col[0] : (j == 1) ? pick_col[1] : (j == 2) ? pick_col[2] : pick_col[3];
+            uint32_t y = b + pc;
+            y = (y >= Y) ? y - Y : y;
+            const uint32_t Xy = (y + 1u == Y) ? X_last : X;
+            // the chain of row y over its own Xy workers, from column a mod Xy
+            uint32_t pick_row = 0;
+            for (uint32_t h = 1; h < Xy; ++h) {
+                uint32_t u[4];
+                philox4x32_10(q, row_hop_id(y, h), w, 0u, key0, key1, u);
+                const uint32_t uj = (j == 0) ? u[0] : (j == 1) ? u[1] : (j == 2) ? u[2] : u[3];
+                pick_row = (uj < thresholds.thr[h + 1]) ? h : pick_row;
+            }
+            const uint32_t column = (a % Xy + pick_row) % Xy;
+            const uint32_t sign = picked_sign<STAGED>(stage, g, c, y * X + column, ld, e, static_cast<int>(j));
+            const float uval = __uint_as_float(scale_bits ^ sign);
+            if (j == 0) upd.x = uval; else if (j == 1) upd.y = uval; else if (j == 2) upd.z = uval; else upd.w = uval;
+            nib |= (sign == 0u) ? (1u << j) : 0u;
+        }
+        if (update != nullptr)
+            store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
+        if (x_model != nullptr) {
+            const f32x4 xv = load4(x_model + e, vec, n_valid);
+            store4<MARSIT_STREAMING_STORES>(x_model + e, xv - upd, vec, n_valid);
+        }
+        if (STAGED)
+            compensate_from_stage(c, stage, upd, M, ld, e, vec, n_valid);
+        else
+            compensate_from_memory(g, c, upd, M, ld, e, vec, n_valid);
+    }
+
+    const uint32_t half = gather_half_word(nib, q);
+    if (bits32 != nullptr && (q & 7u) == 0u && static_cast<uint64_t>(w) * 64u < d)
+        bits32[2u * static_cast<size_t>(w) + (q >> 3)] = half;
+}
+
+// -------------------------------------------------------------------------------------------------
 // Fused pass over a binary reduction tree (whole vectors, no parts): at level l worker
 // k = 0, 2*2^l, ... folds the vector of worker k + 2^l into its own; each side stands for the
 // workers of its subtree.  Same lane layout and launch shape as the ring kernel.
@@ -833,6 +928,57 @@ static int ring_step_impl(const float *g, float *c, float *update_out, uint64_t 
     return MARSIT_OK;
 }
 
+// The one-bit pass over a torus of grid_x columns whose last row may be short.  A grid that divides
+// M is the plain torus (or the ring) and goes to ring_step_impl.
+static int ragged_torus_impl(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                             float *x_model, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                             uint64_t seed, uint32_t grid_x, void *stream)
+{
+    if (M == 0 || M > MARSIT_MAX_WORKERS || grid_x == 0 || grid_x > M)
+        return MARSIT_EINVAL;
+    if (M % grid_x == 0)
+        return ring_step_impl(g, c, update_out, bits_out, x_model, M, d, ld, scale, seed, grid_x, stream);
+    if (g == nullptr || c == nullptr || (update_out == nullptr && x_model == nullptr) || ld < d ||
+        !std::isfinite(scale) || d > kMaxElements)
+        return MARSIT_EINVAL;
+    if (!aligned_to(g, 4) || !aligned_to(c, 4) || !aligned_to(update_out, 4) ||
+        !aligned_to(bits_out, 8) || !aligned_to(x_model, 4))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+
+    const uint32_t X = grid_x, Y = (M + X - 1) / X, X_last = M - (Y - 1) * X;
+    const uint64_t n_words = (d + 63) / 64;
+    uint64_t row_bounds[MARSIT_MAX_WORKERS + 1];
+    split_bounds_host(n_words, X, 0, row_bounds);          // the X row-parts (a ring split in X)
+    PartTable parts;
+    for (uint32_t k = 0; k <= MARSIT_MAX_WORKERS; ++k)
+        parts.bound[k] = static_cast<uint32_t>(k <= X ? row_bounds[k] : n_words);
+    ThresholdTable thresholds;
+    thresholds.thr[0] = 0;
+    thresholds.thr[1] = 0xFFFFFFFFu;
+    for (uint32_t m = 2; m <= MARSIT_MAX_WORKERS; ++m)
+        thresholds.thr[m] = keep_threshold(m);
+
+    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
+                         aligned_to(x_model, 16) && (ld % 4 == 0);
+    const uint32_t scale_bits = float_bits_host(scale);
+    const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
+    uint32_t *bits32 = reinterpret_cast<uint32_t *>(bits_out);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
+    if (M <= kMaxStagedWorkers)
+        hipLaunchKernelGGL(sync_step_ragged_kernel<true>, dim3(blocks), dim3(kSyncBlock),
+                           generic_lds_bytes(M), s, g, c, update_out, bits32, d, ld, scale_bits, key0, key1,
+                           M, X, Y, X_last, aligned, parts, thresholds, x_model);
+    else
+        hipLaunchKernelGGL(sync_step_ragged_kernel<false>, dim3(blocks), dim3(kSyncBlock), 0, s, g, c,
+                           update_out, bits32, d, ld, scale_bits, key0, key1, M, X, Y, X_last, aligned,
+                           parts, thresholds, x_model);
+    return finish_launch();
+}
+
 // The full-precision round; x_model as in ring_step_impl.
 static int full_sync_impl(const float *g, float *c, float *update_out, float *x_model, uint32_t M,
                           uint64_t d, uint64_t ld, void *stream)
@@ -941,6 +1087,24 @@ int marsit_tree_step_apply(const float *g, float *c, float *x, float *update_out
     if (x == nullptr || x == update_out)
         return MARSIT_EINVAL;
     return tree_step_impl(g, c, update_out, bits_out, x, M, d, ld, scale, seed, stream);
+}
+
+int marsit_ragged_torus_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                                 uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed,
+                                 uint32_t grid_x, void *stream)
+{
+    if (update_out == nullptr)
+        return MARSIT_EINVAL;
+    return ragged_torus_impl(g, c, update_out, bits_out, nullptr, M, d, ld, scale, seed, grid_x, stream);
+}
+
+int marsit_ragged_torus_step_apply(const float *g, float *c, float *x, float *update_out,
+                                   uint64_t *bits_out, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                                   uint64_t seed, uint32_t grid_x, void *stream)
+{
+    if (x == nullptr || x == update_out)
+        return MARSIT_EINVAL;
+    return ragged_torus_impl(g, c, update_out, bits_out, x, M, d, ld, scale, seed, grid_x, stream);
 }
 
 int marsit_full_sync(const float *g, float *c, float *update_out, uint32_t M, uint64_t d,

@@ -29,6 +29,7 @@ EXPORTS = (
     "marsit_exchange_step_sim", "marsit_pipeline_step", "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
     "marsit_aggregate_sign", "marsit_majority_vote", "marsit_count_matching",
     "marsit_hop_merge_weighted", "marsit_tree_step_sim", "marsit_tree_step_apply",
+    "marsit_ragged_torus_step_sim", "marsit_ragged_torus_step_apply",
     "marsit_ssdm_cascade_hop", "marsit_cascade_ring_step_sim",
     "marsit_hop_merge_device_seed", "marsit_set_device_seed",
 )
@@ -123,6 +124,10 @@ def load_library(path: str | None = None):
     lib.marsit_exchange_step_sim.restype = ci
     lib.marsit_tree_step_apply.argtypes = [vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, vp]
     lib.marsit_tree_step_apply.restype = ci
+    lib.marsit_ragged_torus_step_sim.argtypes = [vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
+    lib.marsit_ragged_torus_step_sim.restype = ci
+    lib.marsit_ragged_torus_step_apply.argtypes = [vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
+    lib.marsit_ragged_torus_step_apply.restype = ci
     lib.marsit_step_apply.argtypes = [u64, u64, vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
     lib.marsit_step_apply.restype = ci
     lib.marsit_apply_update.argtypes = [vp, vp, u64, vp]
@@ -512,6 +517,28 @@ def marsit_tree_step_apply(g, c, x, update_out, bits_out, scale: float, seed: in
         _f32_ptr(update_out, "update_out", True, need=d),
         _bits_ptr(bits_out, "bits_out", True, need=n_words(d)), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF,
         _stream(stream)))
+    return x
+
+
+def marsit_ragged_torus_step_sim(g, c, update_out, bits_out, scale: float, seed: int, grid_x: int,
+                                 d: int | None = None, stream=None):
+    """The one-bit pass over a torus of ``grid_x`` columns whose last row may be short."""
+    M, ld, d = _matrix_args(g, c, d)
+    _check("marsit_ragged_torus_step_sim", load_library().marsit_ragged_torus_step_sim(
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out", need=d),
+        _bits_ptr(bits_out, "bits_out", True, need=n_words(d)), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF,
+        grid_x, _stream(stream)))
+    return update_out, bits_out
+
+
+def marsit_ragged_torus_step_apply(g, c, x, update_out, bits_out, scale: float, seed: int, grid_x: int,
+                                   d: int | None = None, stream=None):
+    M, ld, d = _matrix_args(g, c, d)
+    _check("marsit_ragged_torus_step_apply", load_library().marsit_ragged_torus_step_apply(
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(x, "x", need=d),
+        _f32_ptr(update_out, "update_out", True, need=d),
+        _bits_ptr(bits_out, "bits_out", True, need=n_words(d)), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF,
+        grid_x, _stream(stream)))
     return x
 
 

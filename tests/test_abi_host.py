@@ -160,6 +160,15 @@ def test_other_entry_points_argument_validation(lib):
     assert lib.marsit_tree_step_apply(FAKE, FAKE, FAKE, None, None, 4, 0, 64, 1.0, 1, None) == marsit.OK
     assert lib.marsit_tree_step_sim(FAKE, FAKE, None, FAKE, 4, 64, 64, 1.0, 1, None) == marsit.EINVAL
 
+    assert lib.marsit_ragged_torus_step_sim(FAKE, FAKE, FAKE, FAKE, 5, 64, 64, 1.0, 1, 0, None) == marsit.EINVAL    # grid_x = 0
+    assert lib.marsit_ragged_torus_step_sim(FAKE, FAKE, FAKE, FAKE, 5, 64, 64, 1.0, 1, 6, None) == marsit.EINVAL    # grid_x > M
+    assert lib.marsit_ragged_torus_step_sim(FAKE, FAKE, None, FAKE, 5, 64, 64, 1.0, 1, 2, None) == marsit.EINVAL
+    assert lib.marsit_ragged_torus_step_sim(FAKE, FAKE, FAKE, FAKE, 5, 64, 32, 1.0, 1, 2, None) == marsit.EINVAL    # ld < d
+    assert lib.marsit_ragged_torus_step_sim(FAKE, FAKE, FAKE + 2, FAKE, 5, 64, 64, 1.0, 1, 2, None) == marsit.EALIGN
+    assert lib.marsit_ragged_torus_step_sim(FAKE, FAKE, FAKE, FAKE, 5, 0, 64, 1.0, 1, 2, None) == marsit.OK
+    assert lib.marsit_ragged_torus_step_apply(FAKE, FAKE, None, FAKE, FAKE, 5, 64, 64, 1.0, 1, 2, None) == marsit.EINVAL
+    assert lib.marsit_ragged_torus_step_apply(FAKE, FAKE, FAKE, None, None, 5, 0, 64, 1.0, 1, 2, None) == marsit.OK
+
     assert lib.marsit_pipeline_create(None, 4) == marsit.EINVAL
     assert lib.marsit_pipeline_destroy(None) == marsit.EINVAL
     assert lib.marsit_pipeline_ring_step(None, FAKE, FAKE, FAKE, FAKE, FAKE, 64, 64, 1.0, 1, None) == marsit.EINVAL

@@ -11,7 +11,8 @@ from paper_2204_06787_amd import marsit
 
 pytestmark = pytest.mark.gpu
 
-KINDS = ["ring", "apply", "tree", "tree_apply", "pipe", "exchange", "chain", "full", "apply_full"]
+KINDS = ["ring", "apply", "tree", "tree_apply", "pipe", "exchange", "chain", "full", "apply_full",
+         "ragged", "ragged_apply"]
 SPECIAL = np.array([0.0, -0.0, np.inf, -np.inf, 1e-45, -1e-45, 3e38, -3e38], dtype=np.float32)
 
 
@@ -72,7 +73,15 @@ def test_random_shapes(chunk):
                 want_x = orc.apply_update(x_h.copy(), want_u)
                 assert np.array_equal(x_d.cpu().numpy().view(np.uint32), want_x.view(np.uint32)), case
             continue
-        if kind in ("tree", "tree_apply"):
+        if kind in ("ragged", "ragged_apply"):
+            grid_x = int(rng.integers(1, M + 1))                       # any width, dividing or not
+            case += f" ragged_grid_x={grid_x}"
+            want_u, want_b = orc.ragged_torus_step(g_h, c_ref, scale, seed, grid_x, d=d, threads=8)
+            if kind == "ragged":
+                marsit.marsit_ragged_torus_step_sim(g_d, c_d, u_d, b_d, scale, seed, grid_x, d=d)
+            else:
+                marsit.marsit_ragged_torus_step_apply(g_d, c_d, x_d, u_d, b_d, scale, seed, grid_x, d=d)
+        elif kind in ("tree", "tree_apply"):
             want_u, want_b = orc.tree_step(g_h, c_ref, scale, seed, d=d)
             if kind == "tree":
                 marsit.marsit_tree_step_sim(g_d, c_d, u_d, b_d, scale, seed, d=d)
@@ -101,6 +110,6 @@ def test_random_shapes(chunk):
         got_c = c_d.cpu().numpy()
         assert np.array_equal(got_c[:, :d].view(np.uint32), c_ref[:, :d].view(np.uint32)), case
         assert np.array_equal(got_c[:, d:].view(np.uint32), c_h[:, d:].view(np.uint32)), case     # padding untouched
-        if kind in ("apply", "tree_apply"):
+        if kind in ("apply", "tree_apply", "ragged_apply"):
             want_x = orc.apply_update(x_h.copy(), want_u)
             assert np.array_equal(x_d.cpu().numpy().view(np.uint32), want_x.view(np.uint32)), case

@@ -84,3 +84,45 @@ def test_tree_step_full_size_headline_shape():
     assert np.array_equal(host_bits(b), want_b)
     assert np.array_equal(host_f32(u), want_u)
     assert_f32_parity(host_f32(c), c_h, "compensation (tree, full size)")
+
+
+# ------------------------------------------------------------------------------------------------
+# torus whose last row is short (M not a multiple of the number of columns)
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,grid_x", [(3, 2), (5, 2), (5, 3), (7, 3), (5, 4), (11, 4), (13, 5), (23, 6), (41, 7),
+                                      (64, 9), (63, 8), (6, 3), (8, 8), (4, 1)])
+@pytest.mark.parametrize("d,ld,offset", [(7, 7, 0), (64 * 40, 64 * 40, 0), (33_333, 33_336, 0), (5001, 5003, 1)])
+def test_ragged_torus_step(M, grid_x, d, ld, offset):
+    """Short last row, weighted column merges; staged (M <= 40) and re-reading (M > 40) kernels,
+    ragged sizes, padded and misaligned rows, two steps with the compensation carried over; the
+    dividing shapes take the plain torus kernels and must agree with the same oracle routine."""
+    rng = np.random.default_rng(M * 100 + grid_x + d)
+    c_h = np.zeros((M, ld), dtype=np.float32)
+    if offset:
+        c_d = unaligned_rows(M, ld, offset)
+    else:
+        c_d = torch.zeros((M, ld), dtype=torch.float32, device="cuda")
+    x_h = rng.standard_normal(d).astype(np.float32)
+    x_d = dev(x_h)
+    u_d = torch.empty(d, dtype=torch.float32, device="cuda")
+    bits = marsit.new_bitmap(d)
+    for t in range(2):
+        g_h = rng.standard_normal((M, ld)).astype(np.float32)
+        if offset:
+            g_d = unaligned_rows(M, ld, offset)
+            g_d.copy_(dev(g_h))
+        else:
+            g_d = dev(g_h)
+        want_u, want_b = orc.ragged_torus_step(g_h, c_h, 1e-3, 500 + t, grid_x, d=d, threads=8)
+        if t == 0:
+            marsit.marsit_ragged_torus_step_sim(g_d, c_d, u_d, bits, 1e-3, 500 + t, grid_x, d=d)
+        else:
+            marsit.marsit_ragged_torus_step_apply(g_d, c_d, x_d, u_d, bits, 1e-3, 500 + t, grid_x, d=d)
+            x_h = orc.apply_update(x_h, want_u)
+        torch.cuda.synchronize()
+        assert np.array_equal(host_bits(bits), want_b), t
+        assert np.array_equal(host_f32(u_d).view(np.uint32), want_u.view(np.uint32)), t
+        assert_f32_parity(host_f32(c_d)[:, :d], c_h[:, :d], f"compensation, step {t}")
+        assert np.array_equal(host_f32(c_d)[:, d:], c_h[:, d:])
+        assert_f32_parity(host_f32(x_d), x_h, f"model, step {t}")
