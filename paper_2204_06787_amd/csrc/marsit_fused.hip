@@ -754,6 +754,18 @@ inline uint32_t generic_lds_bytes(uint32_t M)
     return need > 20u * 1024u ? need : 20u * 1024u;
 }
 
+// The same for the short-last-row kernel, whose lanes spend more of their time on per-bit draws:
+// it wants more wavefronts at small M (measured at 12.8 M elements: M = 5: 8 KB per wavefront,
+// 71 % of HBM peak against 59 % with 20 KB; M = 7: 12 KB; M = 13: 20 KB).
+inline uint32_t ragged_lds_bytes(uint32_t M)
+{
+    const uint32_t need = M * static_cast<uint32_t>(kSyncBlock) * 16u;
+    uint32_t want = ((need * 8u / 5u) + 511u) & ~511u;
+    if (want > 20u * 1024u)
+        want = 20u * 1024u;
+    return need > want ? need : want;
+}
+
 template <int X, int Y>
 void launch_sync_step(const float *g, float *c, float *update, uint32_t *bits32, uint64_t n_cols,
                       uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1,
@@ -970,7 +982,7 @@ static int ragged_torus_impl(const float *g, float *c, float *update_out, uint64
     const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
     if (M <= kMaxStagedWorkers)
         hipLaunchKernelGGL(sync_step_ragged_kernel<true>, dim3(blocks), dim3(kSyncBlock),
-                           generic_lds_bytes(M), s, g, c, update_out, bits32, d, ld, scale_bits, key0, key1,
+                           ragged_lds_bytes(M), s, g, c, update_out, bits32, d, ld, scale_bits, key0, key1,
                            M, X, Y, X_last, aligned, parts, thresholds, x_model);
     else
         hipLaunchKernelGGL(sync_step_ragged_kernel<false>, dim3(blocks), dim3(kSyncBlock), 0, s, g, c,
