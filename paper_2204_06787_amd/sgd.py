@@ -18,7 +18,8 @@ class MarsitSGD:
                  schedule: str = "ring", grid_x: int = 0, momentum: float = 0.0):
         """``x``: the model, float32 ``[d]`` in device memory, updated in place.
         ``K``: a full-precision round whenever ``t mod K == 0`` (``t`` starts at 0).
-        ``schedule``: ``"ring"`` (``grid_x`` = 0), ``"torus"`` (``grid_x`` columns) or ``"tree"``.
+        ``schedule``: ``"ring"`` (``grid_x`` = 0), ``"torus"`` (``grid_x`` columns; if they do not divide
+        ``M`` the last row is short) or ``"tree"``.
         ``momentum``: heavy-ball coefficient of the workers' local optimizer (Section 5 of the paper
         trains the image models with Momentum); used by :meth:`step_from_raw_gradients`."""
         if schedule not in ("ring", "torus", "tree"):
@@ -30,6 +31,8 @@ class MarsitSGD:
         self.x, self.M, self.K, self.eta_s, self.seed = x, int(M), int(K), float(eta_s), int(seed)
         self.schedule = schedule
         self.grid_x = int(grid_x) if schedule == "torus" else 0
+        if schedule == "torus" and not 1 <= self.grid_x <= self.M:
+            raise ValueError("torus: grid_x must be in 1..M")
         d = x.numel()
         self.c = torch.zeros((self.M, d), dtype=torch.float32, device=x.device)     # c_0 = 0
         self.update = torch.empty(d, dtype=torch.float32, device=x.device)
@@ -51,9 +54,18 @@ class MarsitSGD:
         """One round.  ``scaled_grads``: ``[M, d]`` float32, worker m's stochastic gradient already
         multiplied by the local step size.  Returns the global update that was applied to ``x``."""
         seed = (self.seed + self.t) & 0xFFFFFFFFFFFFFFFF
-        if self.schedule == "tree" and self.t % self.K != 0:
+        one_bit = self.t % self.K != 0
+        ragged = self.grid_x != 0 and self.M % self.grid_x != 0          # torus with a short last row
+        if self.schedule == "tree" and one_bit:
             marsit.marsit_tree_step_apply(scaled_grads, self.c, self.x, self.update, self.bits, self.eta_s,
                                           seed, stream=stream)
+        elif ragged and one_bit:
+            marsit.marsit_ragged_torus_step_apply(scaled_grads, self.c, self.x, self.update, self.bits,
+                                                  self.eta_s, seed, self.grid_x, stream=stream)
+        elif ragged:
+            # the full-precision round does not depend on the schedule
+            marsit.marsit_step_apply(self.t, self.K, scaled_grads, self.c, self.x, self.update, self.bits,
+                                     self.eta_s, seed, grid_x=0, stream=stream)
         else:
             marsit.marsit_step_apply(self.t, self.K, scaled_grads, self.c, self.x, self.update, self.bits,
                                      self.eta_s, seed, grid_x=self.grid_x, stream=stream)

@@ -274,7 +274,7 @@ def test_resume_from_saved_compensation_reproduces_the_run():
     assert not torch.equal(b, history[k][1])
 
 
-@pytest.mark.parametrize("schedule,M,grid_x,K", [("ring", 8, 0, 10), ("torus", 16, 4, 7), ("tree", 8, 0, 1000),
+@pytest.mark.parametrize("schedule,M,grid_x,K", [("ring", 8, 0, 10), ("torus", 16, 4, 7), ("tree", 8, 0, 1000), ("torus", 7, 3, 6),
                                                 ("ring", 3, 0, 1)])
 def test_marsit_sgd_follows_the_auxiliary_sequence(schedule, M, grid_x, K):
     """Appendix B: y_t = x_t - mean_m c_t^(m) moves exactly like plain SGD with the mean gradient,
