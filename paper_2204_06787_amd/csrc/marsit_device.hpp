@@ -81,16 +81,21 @@ __device__ __forceinline__ uint32_t f32_bits(float x) { return __float_as_uint(x
 
 // ---- 128-bit / guarded accesses ---------------------------------------------------------------
 
-// Four consecutive floats at p.  `vec`: p is 16-byte aligned and all four are inside the vector.
-// Otherwise the first n_valid (0..4) are read one by one, the rest are +0.  STREAMING marks data
-// that is read once (non-temporal hint).
+// 128-bit accesses are made through a vector type that promises dword alignment only: gfx950
+// global memory instructions take any dword-aligned address for a four-dword access, so rows that
+// do not start on a 16-byte boundary (odd row strides, offset bases) use the same instructions.
+typedef f32x4 f32x4_dw __attribute__((aligned(4)));
+
+// Four consecutive floats at p.  `vec`: all four are inside the vector (p is 4-byte aligned, as
+// every fp32 pointer of the library must be).  Otherwise the first n_valid (0..4) are read one by
+// one, the rest are +0.  STREAMING marks data that is read once (non-temporal hint).
 template <bool STREAMING = true>
 __device__ __forceinline__ f32x4 load4(const float *p, bool vec, uint32_t n_valid)
 {
     if (vec) {
         if (STREAMING)
-            return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
-        return *reinterpret_cast<const f32x4 *>(p);
+            return __builtin_nontemporal_load(reinterpret_cast<const f32x4_dw *>(p));
+        return *reinterpret_cast<const f32x4_dw *>(p);
     }
     f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
     if (n_valid > 0) v.x = p[0];
@@ -105,9 +110,9 @@ __device__ __forceinline__ void store4(float *p, f32x4 v, bool vec, uint32_t n_v
 {
     if (vec) {
         if (STREAMING)
-            __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(p));
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4_dw *>(p));
         else
-            *reinterpret_cast<f32x4 *>(p) = v;
+            *reinterpret_cast<f32x4_dw *>(p) = v;
         return;
     }
     if (n_valid > 0) p[0] = v.x;
@@ -116,17 +121,17 @@ __device__ __forceinline__ void store4(float *p, f32x4 v, bool vec, uint32_t n_v
     if (n_valid > 3) p[3] = v.w;
 }
 
-// Aligned, streaming (read-once / write-once) 128-bit accesses: the non-temporal hint keeps
+// Streaming (read-once / write-once) 128-bit accesses of whole columns: the non-temporal hint keeps
 // the lines from displacing each other in L2 and the memory-side cache; with 2M+ concurrent
 // streams it is worth about 10 % of bandwidth on MI355X.
 __device__ __forceinline__ f32x4 load4_stream(const float *p)
 {
-    return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+    return __builtin_nontemporal_load(reinterpret_cast<const f32x4_dw *>(p));
 }
 
 __device__ __forceinline__ void store4_stream(float *p, f32x4 v)
 {
-    __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(p));
+    __builtin_nontemporal_store(v, reinterpret_cast<f32x4_dw *>(p));
 }
 
 // ---- DPP: OR over the 8 lanes of a half row ------------------------------------------------------

@@ -16,7 +16,7 @@ enum VoteMode { kAggregateSign = 0, kMajorityVote = 1 };
 template <int MODE>
 __global__ void __launch_bounds__(kBlock)
 vote_kernel(const float *__restrict__ g, const float *__restrict__ c, uint32_t *__restrict__ bits32,
-            uint32_t M, uint64_t d, uint64_t ld, bool aligned)
+            uint32_t M, uint64_t d, uint64_t ld)
 {
     const uint64_t n_cols = (d + 3) >> 2;
     const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -27,7 +27,7 @@ vote_kernel(const float *__restrict__ g, const float *__restrict__ c, uint32_t *
         const uint64_t e = col << 2;
         const bool full = e + 4 <= d;
         const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
-        const bool vec = full && aligned;
+        const bool vec = full;
         double acc[4] = {0.0, 0.0, 0.0, 0.0};   // aggregate in double, in worker order
         uint32_t plus[4] = {0, 0, 0, 0};        // workers with a + sign
 #pragma unroll 4
@@ -107,7 +107,7 @@ __device__ __forceinline__ f32x4 cascade_value(const uint32_t *recv32, const flo
 
 __global__ void __launch_bounds__(kBlock)
 cascade_norm_partial_kernel(const uint32_t *recv32, const float *recv_norm, const float *g,
-                            const float *c, uint64_t n, bool aligned, double *partial)
+                            const float *c, uint64_t n, double *partial)
 {
     __shared__ double wave_sum[kBlock / 64];
     const uint64_t n_cols = (n + 3) >> 2;
@@ -117,7 +117,7 @@ cascade_norm_partial_kernel(const uint32_t *recv32, const float *recv_norm, cons
         const uint64_t e = col << 2;
         const bool full = e + 4 <= n;
         const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(n - e);
-        const f32x4 t = cascade_value(recv32, recv_norm, g, c, col, full && aligned, n_valid);
+        const f32x4 t = cascade_value(recv32, recv_norm, g, c, col, full, n_valid);
 #pragma unroll
         for (int j = 0; j < 4; ++j)
             if (static_cast<uint32_t>(j) < n_valid)
@@ -152,7 +152,7 @@ __global__ void cascade_norm_final_kernel(const double *partial, uint32_t n_part
 __global__ void __launch_bounds__(kBlock)
 cascade_sign_kernel(const uint32_t *recv32, const float *recv_norm, const float *g, const float *c,
                     const float *norm_ptr, uint32_t *out32, uint64_t n, uint64_t word_begin,
-                    uint32_t hop_id, uint32_t key0, uint32_t key1, bool aligned)
+                    uint32_t hop_id, uint32_t key0, uint32_t key1)
 {
     const uint64_t n_cols = (n + 3) >> 2;
     const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -163,7 +163,7 @@ cascade_sign_kernel(const uint32_t *recv32, const float *recv_norm, const float 
         const uint64_t e = col << 2;
         const bool full = e + 4 <= n;
         const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(n - e);
-        const f32x4 t = cascade_value(recv32, recv_norm, g, c, col, full && aligned, n_valid);
+        const f32x4 t = cascade_value(recv32, recv_norm, g, c, col, full, n_valid);
         const float norm = *norm_ptr;
         const uint64_t w = word_begin + wl;
         uint32_t u[4];
@@ -210,14 +210,13 @@ static int launch_vote(int mode, const float *g, const float *c, uint64_t *bits_
         return MARSIT_EALIGN;
     if (d == 0)
         return MARSIT_OK;
-    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && (ld % 4 == 0);
     const dim3 grid(blocks_for((d + 3) >> 2)), block(kBlock);
     uint32_t *bits32 = reinterpret_cast<uint32_t *>(bits_out);
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (mode == kAggregateSign)
-        hipLaunchKernelGGL(vote_kernel<kAggregateSign>, grid, block, 0, s, g, c, bits32, M, d, ld, aligned);
+        hipLaunchKernelGGL(vote_kernel<kAggregateSign>, grid, block, 0, s, g, c, bits32, M, d, ld);
     else
-        hipLaunchKernelGGL(vote_kernel<kMajorityVote>, grid, block, 0, s, g, c, bits32, M, d, ld, aligned);
+        hipLaunchKernelGGL(vote_kernel<kMajorityVote>, grid, block, 0, s, g, c, bits32, M, d, ld);
     return finish_launch();
 }
 
@@ -268,7 +267,6 @@ int marsit_ssdm_cascade_hop(const uint64_t *recv_bits, const float *recv_norm, c
     if (n == 0)
         return MARSIT_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16);
     const uint64_t n_cols = (n + 3) >> 2;
     uint32_t n_partials = blocks_for(n_cols);
     if (n_partials > kCascadeMaxPartials)
@@ -276,7 +274,7 @@ int marsit_ssdm_cascade_hop(const uint64_t *recv_bits, const float *recv_norm, c
     double *partial = static_cast<double *>(workspace);
     const uint32_t *recv32 = reinterpret_cast<const uint32_t *>(recv_bits);
     hipLaunchKernelGGL(cascade_norm_partial_kernel, dim3(n_partials), dim3(kBlock), 0, s, recv32,
-                       recv_norm, g, c, n, aligned, partial);
+                       recv_norm, g, c, n, partial);
     int rc = finish_launch();
     if (rc != MARSIT_OK)
         return rc;
@@ -287,7 +285,7 @@ int marsit_ssdm_cascade_hop(const uint64_t *recv_bits, const float *recv_norm, c
         return rc;
     hipLaunchKernelGGL(cascade_sign_kernel, dim3(blocks_for(n_cols)), dim3(kBlock), 0, s, recv32, recv_norm,
                        g, c, norm_out, reinterpret_cast<uint32_t *>(bits_out), n, word_begin, hop_id,
-                       static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), aligned);
+                       static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32));
     return finish_launch();
 }
 

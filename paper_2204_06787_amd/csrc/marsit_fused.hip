@@ -271,7 +271,7 @@ __global__ void __launch_bounds__(kSyncBlock)
 sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
                          float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
                          uint64_t ld, uint64_t col_begin, uint32_t scale_bits, uint32_t key0,
-                         uint32_t key1, uint32_t X, uint32_t Y, bool aligned, PartTable parts,
+                         uint32_t key1, uint32_t X, uint32_t Y, PartTable parts,
                          ThresholdTable thresholds, float *__restrict__ x_model)
 {
     const uint32_t M = X * Y;
@@ -285,7 +285,7 @@ sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
         const uint64_t e = col << 2;
         const bool full = e + 4 <= d;
         const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
-        const bool vec = full && aligned;
+        const bool vec = full;
 
         uint32_t f = 0;
         for (uint32_t k = 1; k < M; ++k)
@@ -381,7 +381,7 @@ __global__ void __launch_bounds__(kSyncBlock)
 sync_step_ragged_kernel(const float *__restrict__ g, float *__restrict__ c,
                         float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
                         uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1, uint32_t M,
-                        uint32_t X, uint32_t Y, uint32_t X_last, bool aligned, PartTable parts,
+                        uint32_t X, uint32_t Y, uint32_t X_last, PartTable parts,
                         ThresholdTable thresholds, float *__restrict__ x_model)
 {
     const uint64_t n_cols = (d + 3) >> 2;
@@ -394,7 +394,7 @@ sync_step_ragged_kernel(const float *__restrict__ g, float *__restrict__ c,
         const uint64_t e = col << 2;
         const bool full = e + 4 <= d;
         const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
-        const bool vec = full && aligned;
+        const bool vec = full;
 
         // split step: row-part a, then sub-part b of it
         uint32_t a = 0;
@@ -568,7 +568,7 @@ __global__ void __launch_bounds__(kSyncBlock)
 tree_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
                          float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
                          uint64_t ld, uint64_t col_begin, uint32_t scale_bits, uint32_t key0,
-                         uint32_t key1, uint32_t M, uint32_t top_level, bool aligned,
+                         uint32_t key1, uint32_t M, uint32_t top_level,
                          float *__restrict__ x_model)
 {
     const uint64_t n_cols = (d + 3) >> 2;
@@ -581,7 +581,7 @@ tree_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
         const uint64_t e = col << 2;
         const bool full = e + 4 <= d;
         const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
-        const bool vec = full && aligned;
+        const bool vec = full;
 
         f32x4 *stage = reinterpret_cast<f32x4 *>(marsit_dynamic_lds);
         if (STAGED)
@@ -629,7 +629,7 @@ tree_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
 // -------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kBlock)
 full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
-                 uint32_t M, uint64_t d, uint64_t ld, uint64_t col_begin, bool aligned,
+                 uint32_t M, uint64_t d, uint64_t ld, uint64_t col_begin,
                  float *__restrict__ x_model)
 {
     const uint64_t n_cols = (d + 3) >> 2;
@@ -639,7 +639,7 @@ full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
     const uint64_t e = col << 2;
     const bool full = e + 4 <= d;
     const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
-    const bool vec = full && aligned;
+    const bool vec = full;
 
     // the mean of the fp32 compensated gradients: summed in double in worker order, divided in
     // double, rounded once to fp32
@@ -895,17 +895,15 @@ static int ring_step_impl(const float *g, float *c, float *update_out, uint64_t 
     for (uint32_t k = 0; k <= MARSIT_MAX_WORKERS; ++k)
         parts.bound[k] = static_cast<uint32_t>(k <= M ? bounds[k] : n_words);
 
-    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
-                         aligned_to(x_model, 16) && (ld % 4 == 0);
     const uint32_t scale_bits = float_bits_host(scale);
     const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
     uint32_t *bits32 = reinterpret_cast<uint32_t *>(bits_out);
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    // Whole packed words of an aligned input go to the kernel compiled for this schedule, the
-    // ragged last word (and every input without a compiled schedule or with odd alignment) to the
-    // generic kernel.  The two write disjoint outputs.
-    const SyncLauncher fast = aligned ? find_specialisation(X, Y) : nullptr;
+    // Whole packed words go to the kernel compiled for this schedule, the ragged last word (and
+    // every input without a compiled schedule) to the generic kernel.  The two write disjoint
+    // outputs.
+    const SyncLauncher fast = find_specialisation(X, Y);
     uint64_t generic_col_begin = 0;
     if (fast != nullptr) {
         const uint64_t fast_cols = (d / 64) * 16;
@@ -929,12 +927,12 @@ static int ring_step_impl(const float *g, float *c, float *update_out, uint64_t 
         if (M <= kMaxStagedWorkers)
             hipLaunchKernelGGL(sync_step_generic_kernel<true>, dim3(blocks), dim3(kSyncBlock),
                                generic_lds_bytes(M), s, g, c, update_out, bits32, d, ld,
-                               generic_col_begin, scale_bits, key0, key1, X, Y, aligned, parts, thresholds,
+                               generic_col_begin, scale_bits, key0, key1, X, Y, parts, thresholds,
                                x_model);
         else
             hipLaunchKernelGGL(sync_step_generic_kernel<false>, dim3(blocks), dim3(kSyncBlock), 0, s, g, c,
                                update_out, bits32, d, ld, generic_col_begin, scale_bits, key0, key1, X, Y,
-                               aligned, parts, thresholds, x_model);
+                               parts, thresholds, x_model);
         return finish_launch();
     }
     return MARSIT_OK;
@@ -972,8 +970,6 @@ static int ragged_torus_impl(const float *g, float *c, float *update_out, uint64
     for (uint32_t m = 2; m <= MARSIT_MAX_WORKERS; ++m)
         thresholds.thr[m] = keep_threshold(m);
 
-    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
-                         aligned_to(x_model, 16) && (ld % 4 == 0);
     const uint32_t scale_bits = float_bits_host(scale);
     const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
     uint32_t *bits32 = reinterpret_cast<uint32_t *>(bits_out);
@@ -983,10 +979,10 @@ static int ragged_torus_impl(const float *g, float *c, float *update_out, uint64
     if (M <= kMaxStagedWorkers)
         hipLaunchKernelGGL(sync_step_ragged_kernel<true>, dim3(blocks), dim3(kSyncBlock),
                            ragged_lds_bytes(M), s, g, c, update_out, bits32, d, ld, scale_bits, key0, key1,
-                           M, X, Y, X_last, aligned, parts, thresholds, x_model);
+                           M, X, Y, X_last, parts, thresholds, x_model);
     else
         hipLaunchKernelGGL(sync_step_ragged_kernel<false>, dim3(blocks), dim3(kSyncBlock), 0, s, g, c,
-                           update_out, bits32, d, ld, scale_bits, key0, key1, M, X, Y, X_last, aligned,
+                           update_out, bits32, d, ld, scale_bits, key0, key1, M, X, Y, X_last,
                            parts, thresholds, x_model);
     return finish_launch();
 }
@@ -1002,11 +998,9 @@ static int full_sync_impl(const float *g, float *c, float *update_out, float *x_
         return MARSIT_EALIGN;
     if (d == 0)
         return MARSIT_OK;
-    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
-                         aligned_to(x_model, 16) && (ld % 4 == 0);
     hipStream_t s = static_cast<hipStream_t>(stream);
     uint64_t col_begin = 0;
-    const FullSyncLauncher fast = aligned ? find_full_sync(M) : nullptr;
+    const FullSyncLauncher fast = find_full_sync(M);
     if (fast != nullptr && d >= 4) {
         col_begin = d / 4;
         fast(g, c, update_out, col_begin, ld, x_model, s);
@@ -1017,7 +1011,7 @@ static int full_sync_impl(const float *g, float *c, float *update_out, float *x_
     const uint64_t n_cols = (d + 3) >> 2;
     if (col_begin < n_cols) {
         hipLaunchKernelGGL(full_sync_kernel, dim3(blocks_for(n_cols - col_begin)), dim3(kBlock), 0, s,
-                           g, c, update_out, M, d, ld, col_begin, aligned, x_model);
+                           g, c, update_out, M, d, ld, col_begin, x_model);
         return finish_launch();
     }
     return MARSIT_OK;
@@ -1046,14 +1040,12 @@ static int tree_step_impl(const float *g, float *c, float *update_out, uint64_t 
         return MARSIT_EALIGN;
     if (d == 0)
         return MARSIT_OK;
-    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
-                         aligned_to(x_model, 16) && (ld % 4 == 0);
     const uint32_t scale_bits = float_bits_host(scale);
     const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
     uint32_t *bits32 = reinterpret_cast<uint32_t *>(bits_out);
     hipStream_t s = static_cast<hipStream_t>(stream);
 
-    const TreeLauncher fast = aligned ? find_tree(M) : nullptr;
+    const TreeLauncher fast = find_tree(M);
     uint64_t generic_col_begin = 0;
     if (fast != nullptr) {
         const uint64_t fast_cols = (d / 64) * 16;
@@ -1075,11 +1067,11 @@ static int tree_step_impl(const float *g, float *c, float *update_out, uint64_t 
         if (M <= kMaxStagedWorkers)
             hipLaunchKernelGGL(tree_step_generic_kernel<true>, dim3(blocks), dim3(kSyncBlock),
                                generic_lds_bytes(M), s, g, c, update_out, bits32, d, ld,
-                               generic_col_begin, scale_bits, key0, key1, M, top_level, aligned, x_model);
+                               generic_col_begin, scale_bits, key0, key1, M, top_level, x_model);
         else
             hipLaunchKernelGGL(tree_step_generic_kernel<false>, dim3(blocks), dim3(kSyncBlock), 0, s, g, c,
                                update_out, bits32, d, ld, generic_col_begin, scale_bits, key0, key1, M,
-                               top_level, aligned, x_model);
+                               top_level, x_model);
         return finish_launch();
     }
     return MARSIT_OK;

@@ -112,7 +112,7 @@ __global__ void __launch_bounds__(kBlock)
 compress_hop_merge_kernel(const uint32_t *recv32, const float *__restrict__ g,
                           const float *__restrict__ c, uint32_t *out32, uint64_t word_begin,
                           uint64_t n, uint32_t threshold, bool always_local, uint32_t hop_id,
-                          uint32_t key0, uint32_t key1, bool aligned)
+                          uint32_t key0, uint32_t key1)
 {
     const uint64_t n_cols = (n + 3) >> 2;
     const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -127,7 +127,7 @@ compress_hop_merge_kernel(const uint32_t *recv32, const float *__restrict__ g,
         const uint64_t e = col << 2;
         const bool full = e + 4 <= n;
         const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(n - e);
-        const bool vec = full && aligned;
+        const bool vec = full;
         const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
         const f32x4 sv = load4<true>(g + e, vec, n_valid) + ((c != nullptr) ? load4<true>(c + e, vec, n_valid) : zero);
         uint32_t l = 0;
@@ -208,7 +208,7 @@ fold_segments_kernel(const uint32_t *__restrict__ maps32, uint64_t stride_halves
 __global__ void __launch_bounds__(kBlock)
 decode_compensate_kernel(const uint32_t *__restrict__ bits32, const float *__restrict__ g,
                          const float *c, float *__restrict__ update, float *c_out, uint64_t d,
-                         uint32_t scale_bits, bool aligned, float *__restrict__ x_model)
+                         uint32_t scale_bits, float *__restrict__ x_model)
 {
     const uint64_t n_cols = (d + 3) >> 2;
     const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -217,7 +217,7 @@ decode_compensate_kernel(const uint32_t *__restrict__ bits32, const float *__res
     const uint64_t e = col << 2;
     const bool full = e + 4 <= d;
     const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
-    const bool vec = full && aligned;
+    const bool vec = full;
 
     const uint32_t nib = (bits32[col >> 3] >> ((static_cast<uint32_t>(col) & 7u) * 4u)) & 0xFu;
     const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -237,7 +237,7 @@ decode_compensate_kernel(const uint32_t *__restrict__ bits32, const float *__res
 }
 
 __global__ void __launch_bounds__(kBlock)
-apply_update_kernel(float *__restrict__ x, const float *__restrict__ update, uint64_t d, bool aligned)
+apply_update_kernel(float *__restrict__ x, const float *__restrict__ update, uint64_t d)
 {
     const uint64_t n_cols = (d + 3) >> 2;
     const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -246,7 +246,7 @@ apply_update_kernel(float *__restrict__ x, const float *__restrict__ update, uin
     const uint64_t e = col << 2;
     const bool full = e + 4 <= d;
     const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
-    const bool vec = full && aligned;
+    const bool vec = full;
     const f32x4 xv = load4<false>(x + e, vec, n_valid);
     const f32x4 uv = load4<true>(update + e, vec, n_valid);
     store4<false>(x + e, xv - uv, vec, n_valid);
@@ -258,7 +258,7 @@ apply_update_kernel(float *__restrict__ x, const float *__restrict__ update, uin
 // before it writes them.
 __global__ void __launch_bounds__(kBlock)
 local_momentum_kernel(float *__restrict__ buf, const float *grad, float *g_out, uint64_t d,
-                      uint64_t ld, float beta, float eta_l, bool aligned)
+                      uint64_t ld, float beta, float eta_l)
 {
     const uint64_t n_cols = (d + 3) >> 2;
     const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
@@ -268,7 +268,7 @@ local_momentum_kernel(float *__restrict__ buf, const float *grad, float *g_out, 
     const size_t at = static_cast<size_t>(blockIdx.y) * ld + e;
     const bool full = e + 4 <= d;
     const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
-    const bool vec = full && aligned;
+    const bool vec = full;
     const f32x4 bv = load4<true>(buf + at, vec, n_valid);
     const f32x4 gv = load4<true>(grad + at, vec, n_valid);
     const f32x4 carried = bv * beta;
@@ -358,12 +358,11 @@ int marsit_compress_hop_merge(const uint64_t *recv, const float *g, const float 
         return MARSIT_OK;
     const bool always_local = (fold == 1);
     const uint32_t threshold = always_local ? 0xFFFFFFFFu : keep_threshold(fold);
-    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16);
     const uint64_t n_words = (n + 63) / 64;
     hipLaunchKernelGGL(compress_hop_merge_kernel, dim3(blocks_for(n_words * 16)), dim3(kBlock), 0,
                        static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(recv), g, c,
                        reinterpret_cast<uint32_t *>(out), word_begin, n, threshold, always_local, hop_id,
-                       static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32), aligned);
+                       static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32));
     return finish_launch();
 }
 
@@ -419,11 +418,9 @@ static int decode_impl(const uint64_t *bits, const float *g, const float *c, flo
         return MARSIT_EALIGN;
     if (d == 0)
         return MARSIT_OK;
-    const bool aligned = aligned_to(g, 16) && aligned_to(c, 16) && aligned_to(update_out, 16) &&
-                         aligned_to(c_out, 16) && aligned_to(x_model, 16);
     hipLaunchKernelGGL(decode_compensate_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock), 0,
                        static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(bits), g,
-                       c, update_out, c_out, d, float_bits_host(scale), aligned, x_model);
+                       c, update_out, c_out, d, float_bits_host(scale), x_model);
     return finish_launch();
 }
 
@@ -636,9 +633,8 @@ int marsit_apply_update(float *x, const float *update, uint64_t d, void *stream)
         return MARSIT_EALIGN;
     if (d == 0)
         return MARSIT_OK;
-    const bool aligned = aligned_to(x, 16) && aligned_to(update, 16);
     hipLaunchKernelGGL(apply_update_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock), 0,
-                       static_cast<hipStream_t>(stream), x, update, d, aligned);
+                       static_cast<hipStream_t>(stream), x, update, d);
     return finish_launch();
 }
 
@@ -653,9 +649,8 @@ int marsit_local_momentum(float *buf, const float *grad, float *g_out, uint32_t 
         return MARSIT_EALIGN;
     if (d == 0)
         return MARSIT_OK;
-    const bool aligned = aligned_to(buf, 16) && aligned_to(grad, 16) && aligned_to(g_out, 16) && ld % 4 == 0;
     hipLaunchKernelGGL(local_momentum_kernel, dim3(blocks_for((d + 3) >> 2), M), dim3(kBlock), 0,
-                       static_cast<hipStream_t>(stream), buf, grad, g_out, d, ld, beta, eta_l, aligned);
+                       static_cast<hipStream_t>(stream), buf, grad, g_out, d, ld, beta, eta_l);
     return finish_launch();
 }
 
