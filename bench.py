@@ -165,6 +165,7 @@ def main():
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
                      "kernel": "sync_step_kernel", "avg_launch_ms": avg_kernel_ms,
+                     "median_launch_ms": sorted(per_launch_ms)[K // 2],
                      "min_launch_ms": min(per_launch_ms), "max_launch_ms": max(per_launch_ms)},
     }
 
