@@ -41,7 +41,9 @@ typedef enum marsit_status {
     MARSIT_EINVAL = -1,   /* NULL required pointer, M == 0, M > MARSIT_MAX_WORKERS, fold == 0, ld < d,
                              grid_x does not divide M, non-finite scale, K == 0, size too large */
     MARSIT_EALIGN = -2,   /* a pointer is not aligned to its element size */
-    MARSIT_EHIP = -3      /* a HIP call failed; marsit_last_hip_error() has the raw hipError_t */
+    MARSIT_EHIP = -3,     /* a HIP call failed; marsit_last_hip_error() has the raw hipError_t */
+    MARSIT_ESCRATCH = -4  /* marsit_exchange_step_sim_static only: the input needs more workspace than
+                             MARSIT_STATIC_SCRATCH_WORDS */
 } marsit_status;
 
 /* Library version: major * 10000 + minor * 100 + patch. */
@@ -253,6 +255,27 @@ int marsit_exchange_step_sim(const float *g, float *c, float *update_out, uint64
 
 /* Host-side: size of the workspace of marsit_chain_step_sim in 64-bit words (0 for bad arguments). */
 uint64_t marsit_chain_workspace_words(uint32_t M, uint64_t d, uint32_t grid_x);
+
+/*
+ * marsit_exchange_step_sim for callers that cannot allocate device memory or carry a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The call
+ * allocates nothing and frees nothing; its workspace is a static device array inside the library of
+ * MARSIT_STATIC_SCRATCH_WORDS 64-bit words (32 MiB, held by every GPU the library is used on until
+ * the process ends).  Inputs, outputs and results exactly as marsit_exchange_step_sim.
+ *   - Inputs with marsit_chain_workspace_words(M, d, grid_x) > MARSIT_STATIC_SCRATCH_WORDS are
+ *     rejected with MARSIT_ESCRATCH before anything is launched (ring of M workers: M * ceil(d/64)
+ *     words, so d <= 33 554 432 at M = 8; the 25.6 M-element, 8-worker workload fits).
+ *   - The first call on a device looks the array's device address up (hipGetSymbolAddress, no
+ *     allocation); make that first call outside a graph capture.
+ *   - Every call on one GPU uses that GPU's one array.  Nothing in it has to start at zero (each
+ *     word that is read was written earlier in the same call), so earlier calls leave no trace in
+ *     the results; but two calls that overlap in time on one GPU (different streams, or graphs
+ *     replayed concurrently) race on it and must be ordered by the caller.
+ */
+#define MARSIT_STATIC_SCRATCH_WORDS 4194304u
+int marsit_exchange_step_sim_static(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                                    uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed,
+                                    uint32_t grid_x, void *stream);
 
 /*
  * The ring of Section 4 / Fig. 3 with one HIP stream per worker: every hop of every part is its own

@@ -5,9 +5,45 @@
 #include "marsit_device.hpp"
 #include "marsit_host.hpp"
 
+#include <atomic>
+
 namespace marsit {
 
 thread_local int tls_last_hip_error = 0;
+
+// Workspace of marsit_exchange_step_sim_static.  Every GPU the library runs on holds its own copy
+// of this array, at its own address, until the process ends.  In host code the name is only a
+// handle for hipGetSymbolAddress; kernels get the address that call returns.
+__device__ __align__(256) uint64_t scratch[MARSIT_STATIC_SCRATCH_WORDS];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<uint64_t *> scratch_address[kMaxDevices];
+
+// Device address of `scratch` on the current device; resolved on the first call per device.
+static int static_scratch_address(uint64_t **out)
+{
+    int device = -1;
+    hipError_t err = hipGetDevice(&device);
+    if (err != hipSuccess) {
+        tls_last_hip_error = static_cast<int>(err);
+        return MARSIT_EHIP;
+    }
+    if (device < 0 || device >= kMaxDevices)
+        return MARSIT_EINVAL;
+    uint64_t *ptr = scratch_address[device].load(std::memory_order_acquire);
+    if (ptr == nullptr) {
+        void *resolved = nullptr;
+        err = hipGetSymbolAddress(&resolved, HIP_SYMBOL(scratch));
+        if (err != hipSuccess || resolved == nullptr) {
+            tls_last_hip_error = static_cast<int>(err);
+            return MARSIT_EHIP;
+        }
+        ptr = static_cast<uint64_t *>(resolved);
+        scratch_address[device].store(ptr, std::memory_order_release);   // same value from any thread
+    }
+    *out = ptr;
+    return MARSIT_OK;
+}
 
 int split_bounds_host(uint64_t n_words, uint32_t M, uint32_t grid_x, uint64_t *bounds)
 {
@@ -294,6 +330,7 @@ const char *marsit_status_string(int status)
     case MARSIT_EINVAL: return "invalid argument";
     case MARSIT_EALIGN: return "pointer not aligned to its element size";
     case MARSIT_EHIP: return "HIP call failed (see marsit_last_hip_error)";
+    case MARSIT_ESCRATCH: return "input needs more workspace than the library's static scratch array holds";
     default: return "unknown status";
     }
 }
@@ -463,10 +500,12 @@ int marsit_fold_segments(const uint64_t *maps, uint64_t stride_words, uint32_t K
 
 // The one-bit pass as one exchange step: every worker computes its signs, the owner of a part gets
 // all K segments of that part (on one GPU they are simply in memory) and folds them in one launch,
-// every worker decodes.  Rows first, then columns, on a torus.  Workspace as in marsit_chain_step_sim.
-int marsit_exchange_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
-                             uint64_t *workspace, uint32_t M, uint64_t d, uint64_t ld, float scale,
-                             uint64_t seed, uint32_t grid_x, void *stream)
+// every worker decodes.  Rows first, then columns, on a torus.  Workspace as in marsit_chain_step_sim:
+// every word of it that is read has been written earlier in the same call (the M bitmaps by the
+// compress launches, the row results by the row folds), so its previous contents do not matter.
+static int exchange_step_impl(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                              uint64_t *workspace, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                              uint64_t seed, uint32_t grid_x, void *stream)
 {
     if (g == nullptr || c == nullptr || update_out == nullptr || bits_out == nullptr ||
         workspace == nullptr || M == 0 || M > MARSIT_MAX_WORKERS || ld < d || !std::isfinite(scale) ||
@@ -527,6 +566,33 @@ int marsit_exchange_step_sim(const float *g, float *c, float *update_out, uint64
             return rc;
     }
     return MARSIT_OK;
+}
+
+int marsit_exchange_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                             uint64_t *workspace, uint32_t M, uint64_t d, uint64_t ld, float scale,
+                             uint64_t seed, uint32_t grid_x, void *stream)
+{
+    return exchange_step_impl(g, c, update_out, bits_out, workspace, M, d, ld, scale, seed, grid_x, stream);
+}
+
+// marsit_exchange_step_sim for callers that cannot allocate: the workspace is the library's own
+// static array.  Its device address is looked up once per device (the first call there) and kept.
+int marsit_exchange_step_sim_static(const float *g, float *c, float *update_out, uint64_t *bits_out,
+                                    uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed,
+                                    uint32_t grid_x, void *stream)
+{
+    // argument errors first, so that they read the same as marsit_exchange_step_sim's
+    if (g == nullptr || c == nullptr || update_out == nullptr || bits_out == nullptr || M == 0 ||
+        M > MARSIT_MAX_WORKERS || ld < d || !std::isfinite(scale) || d > kMaxElements ||
+        (grid_x != 0 && M % grid_x != 0))
+        return MARSIT_EINVAL;
+    if (marsit_chain_workspace_words(M, d, grid_x) > MARSIT_STATIC_SCRATCH_WORDS)
+        return MARSIT_ESCRATCH;
+    uint64_t *workspace = nullptr;
+    const int rc = static_scratch_address(&workspace);
+    if (rc != MARSIT_OK)
+        return rc;
+    return exchange_step_impl(g, c, update_out, bits_out, workspace, M, d, ld, scale, seed, grid_x, stream);
 }
 
 uint64_t marsit_chain_workspace_words(uint32_t M, uint64_t d, uint32_t grid_x)

@@ -16,7 +16,8 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libmarsit.so")
 
 MAX_WORKERS = 64
-OK, EINVAL, EALIGN, EHIP = 0, -1, -2, -3
+OK, EINVAL, EALIGN, EHIP, ESCRATCH = 0, -1, -2, -3, -4
+STATIC_SCRATCH_WORDS = 4194304
 
 # every symbol include/marsit.h declares
 EXPORTS = (
@@ -32,6 +33,7 @@ EXPORTS = (
     "marsit_ragged_torus_step_sim", "marsit_ragged_torus_step_apply",
     "marsit_ssdm_cascade_hop", "marsit_cascade_ring_step_sim",
     "marsit_hop_merge_device_seed", "marsit_set_device_seed",
+    "marsit_exchange_step_sim_static",
 )
 
 _lib = None
@@ -122,6 +124,8 @@ def load_library(path: str | None = None):
     lib.marsit_fold_segments.restype = ci
     lib.marsit_exchange_step_sim.argtypes = [vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
     lib.marsit_exchange_step_sim.restype = ci
+    lib.marsit_exchange_step_sim_static.argtypes = [vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
+    lib.marsit_exchange_step_sim_static.restype = ci
     lib.marsit_tree_step_apply.argtypes = [vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, vp]
     lib.marsit_tree_step_apply.restype = ci
     lib.marsit_ragged_torus_step_sim.argtypes = [vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
@@ -356,6 +360,17 @@ def marsit_exchange_step_sim(g, c, update_out, bits_out, workspace, scale: float
     _check("marsit_exchange_step_sim", load_library().marsit_exchange_step_sim(
         _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out", need=d),
         _bits_ptr(bits_out, "bits_out", need=n_words(d)), _bits_ptr(workspace, "workspace"), M, d, ld, scale,
+        seed & 0xFFFFFFFFFFFFFFFF, grid_x, _stream(stream)))
+    return update_out, bits_out
+
+
+def marsit_exchange_step_sim_static(g, c, update_out, bits_out, scale: float, seed: int, grid_x: int = 0,
+                                    d: int | None = None, stream=None):
+    """``marsit_exchange_step_sim`` on the library's own static workspace: the call allocates nothing."""
+    M, ld, d = _matrix_args(g, c, d)
+    _check("marsit_exchange_step_sim_static", load_library().marsit_exchange_step_sim_static(
+        _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(update_out, "update_out", need=d),
+        _bits_ptr(bits_out, "bits_out", need=n_words(d)), M, d, ld, scale,
         seed & 0xFFFFFFFFFFFFFFFF, grid_x, _stream(stream)))
     return update_out, bits_out
 
