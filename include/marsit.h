@@ -36,10 +36,17 @@ extern "C" {
 
 #define MARSIT_MAX_WORKERS 64u
 
+/* Largest number of elements per vector (d, n) any entry point takes: 2^34 - 1024.  Every kernel
+ * covers its vector with one launch, at most one work-item per 4 elements in whole workgroups of
+ * 256, and a launch must stay below 2^32 work-items.  Larger sizes return MARSIT_EINVAL; split the
+ * vector (the random stream is keyed by the global word index, see word_begin). */
+#define MARSIT_MAX_ELEMENTS 17179868160ull
+
 typedef enum marsit_status {
     MARSIT_OK = 0,
     MARSIT_EINVAL = -1,   /* NULL required pointer, M == 0, M > MARSIT_MAX_WORKERS, fold == 0, ld < d,
-                             grid_x does not divide M, non-finite scale, K == 0, size too large */
+                             grid_x does not divide M, non-finite scale, K == 0, more than
+                             MARSIT_MAX_ELEMENTS elements */
     MARSIT_EALIGN = -2,   /* a pointer is not aligned to its element size */
     MARSIT_EHIP = -3,     /* a HIP call failed; marsit_last_hip_error() has the raw hipError_t */
     MARSIT_ESCRATCH = -4  /* marsit_exchange_step_sim_static only: the input needs more workspace than
@@ -54,6 +61,11 @@ int marsit_last_hip_error(void);
 
 /* Static, NUL-terminated description of a status code. */
 const char *marsit_status_string(int status);
+
+/* Host-side.  Work-items in x of the widest launch any entry point makes for a vector of d elements
+ * (columns of 4 elements in whole workgroups of 256); 0 if d is 0 or exceeds MARSIT_MAX_ELEMENTS.
+ * Always below 2^32, the most one launch may have. */
+uint64_t marsit_grid_work_items(uint64_t d);
 
 /*
  * Host-side Philox4x32-10 (Salmon et al., SC'11), the generator behind the merge masks.
@@ -322,7 +334,9 @@ int marsit_full_sync(const float *g, float *c, float *update_out, uint32_t M, ui
 
 /*
  * Algorithm 1 as a whole: the one-bit pass when t mod K != 0, the full-precision round when
- * t mod K == 0.  K == 0 is MARSIT_EINVAL; pass K > t_max for "never".  bits_out is left
+ * t mod K == 0.  K == 0 is MARSIT_EINVAL.  Round t = 0 satisfies t mod K == 0 for every K, so it is
+ * always a full-precision round (and leaves bits_out unwritten): a run of one-bit rounds only
+ * starts at t >= 1 with K > t_max, or calls marsit_ring_step_sim directly.  bits_out is left
  * untouched by a full-precision round.  Other arguments as in marsit_ring_step_sim.
  */
 int marsit_step(uint64_t t, uint64_t K, const float *g, float *c, float *update_out,
@@ -341,6 +355,30 @@ int marsit_step(uint64_t t, uint64_t K, const float *g, float *c, float *update_
 int marsit_step_apply(uint64_t t, uint64_t K, const float *g, float *c, float *x, float *update_out,
                       uint64_t *bits_out, uint32_t M, uint64_t d, uint64_t ld, float scale,
                       uint64_t seed, uint32_t grid_x, void *stream);
+
+/*
+ * One round of Algorithm 1 with the schedule as an argument, and of Algorithm 2 when the model is
+ * given: the whole decision "which branch, which schedule" is taken here, so a training loop makes
+ * this one call per round.
+ *   t mod K == 0 : the full-precision round (the same for every schedule; bits_out untouched);
+ *   otherwise    : the one-bit pass over `schedule`:
+ *     MARSIT_SCHEDULE_RING   grid_x must be 0 (or M);                 as marsit_ring_step_sim
+ *     MARSIT_SCHEDULE_TORUS  1 <= grid_x <= M columns; the last row is short when grid_x does not
+ *                            divide M;                                as marsit_ragged_torus_step_sim
+ *     MARSIT_SCHEDULE_TREE   grid_x must be 0;                        as marsit_tree_step_sim
+ *   x           [d] the model, updated in place (x <- x - g_t) in the same pass, or NULL for the
+ *               synchronisation alone; must not alias update_out.
+ *   update_out  [d] the global update g_t, or NULL when x is given.
+ * Results equal the entry points named above (followed by marsit_apply_update) bit for bit.
+ */
+typedef enum marsit_schedule {
+    MARSIT_SCHEDULE_RING = 0,
+    MARSIT_SCHEDULE_TORUS = 1,
+    MARSIT_SCHEDULE_TREE = 2
+} marsit_schedule;
+int marsit_round(uint64_t t, uint64_t K, int schedule, uint32_t grid_x, const float *g, float *c,
+                 float *x, float *update_out, uint64_t *bits_out, uint32_t M, uint64_t d, uint64_t ld,
+                 float scale, uint64_t seed, void *stream);
 
 /*
  * Diagnostics of Section 3.2.2 / Fig. 2(b).  The matching rate of a sign vector is the share of

@@ -186,12 +186,16 @@ __global__ void __launch_bounds__(kBlock)
 cascade_decode_kernel(const uint32_t *bits32, const float *norm_ptr, float *update, uint64_t n,
                       float workers)
 {
-    const uint64_t e = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    // lane = one column of 4 elements (nibble col % 8 of 32-bit half col / 8)
+    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint64_t e = col << 2;
     if (e >= n)
         return;
     const float norm = *norm_ptr;
-    const uint32_t bit = (bits32[e >> 5] >> (static_cast<uint32_t>(e) & 31u)) & 1u;
-    update[e] = (bit ? norm : -norm) / workers;
+    const uint32_t nib = (bits32[col >> 3] >> ((static_cast<uint32_t>(col) & 7u) * 4u)) & 0xFu;
+    const uint32_t n_valid = (e + 4 <= n) ? 4u : static_cast<uint32_t>(n - e);
+    for (uint32_t j = 0; j < n_valid; ++j)
+        update[e + j] = (((nib >> j) & 1u) ? norm : -norm) / workers;
 }
 
 }   // namespace marsit
@@ -326,7 +330,7 @@ int marsit_cascade_ring_step_sim(const float *g, const float *c, float *update_o
             if (rc != MARSIT_OK)
                 return rc;
         }
-        hipLaunchKernelGGL(cascade_decode_kernel, dim3(blocks_for(n)), dim3(kBlock), 0, s,
+        hipLaunchKernelGGL(cascade_decode_kernel, dim3(blocks_for((n + 3) >> 2)), dim3(kBlock), 0, s,
                            reinterpret_cast<const uint32_t *>(bits), norms_out + i, update_out + e0, n,
                            static_cast<float>(M));
         const int rc = finish_launch();

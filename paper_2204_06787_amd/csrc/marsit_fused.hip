@@ -32,8 +32,8 @@ struct ThresholdTable {
 // One lane = one column of 4 elements of all M workers.  Workers are loaded in chain order
 // (row (b+ky) mod Y, column (a+kx) mod X for part a*Y+b), so register indices are static and only
 // the addresses depend on the part.  Handles whole packed words only (n_cols is a multiple of 16,
-// every column has its 4 elements, every pointer is 16-byte aligned); a ragged tail goes to the
-// generic kernel.
+// every column has its 4 elements); pointers and row strides need dword alignment only, the
+// 128-bit accesses take any dword-aligned address.  A ragged tail goes to the generic kernel.
 //
 // Occupancy is throttled from the host (dynamic LDS that the kernel never touches): with 25
 // concurrent streams HBM delivers most when each CU keeps only about 40-50 KB of reads in flight;
@@ -1148,6 +1148,45 @@ int marsit_step_apply(uint64_t t, uint64_t K, const float *g, float *c, float *x
     if (!aligned_to(bits_out, 8))
         return MARSIT_EALIGN;
     return full_sync_impl(g, c, update_out, x, M, d, ld, stream);
+}
+
+// Algorithm 1 as a whole with the schedule as an argument (and Algorithm 2's model update when x
+// is given): the caller holds no "t mod K" test and no choice between entry points.
+int marsit_round(uint64_t t, uint64_t K, int schedule, uint32_t grid_x, const float *g, float *c,
+                 float *x, float *update_out, uint64_t *bits_out, uint32_t M, uint64_t d, uint64_t ld,
+                 float scale, uint64_t seed, void *stream)
+{
+    if (K == 0 || M == 0 || M > MARSIT_MAX_WORKERS || (x == nullptr && update_out == nullptr) ||
+        (x != nullptr && x == update_out) || !std::isfinite(scale))
+        return MARSIT_EINVAL;
+    switch (schedule) {
+    case MARSIT_SCHEDULE_RING:
+        if (grid_x != 0 && grid_x != M)
+            return MARSIT_EINVAL;
+        grid_x = 0;
+        break;
+    case MARSIT_SCHEDULE_TORUS:
+        if (grid_x == 0 || grid_x > M)
+            return MARSIT_EINVAL;
+        break;
+    case MARSIT_SCHEDULE_TREE:
+        if (grid_x != 0)
+            return MARSIT_EINVAL;
+        break;
+    default:
+        return MARSIT_EINVAL;
+    }
+    if (t % K == 0) {
+        // the full-precision round is the same for every schedule; bits_out is only checked
+        if (!aligned_to(bits_out, 8))
+            return MARSIT_EALIGN;
+        return full_sync_impl(g, c, update_out, x, M, d, ld, stream);
+    }
+    if (schedule == MARSIT_SCHEDULE_TREE)
+        return tree_step_impl(g, c, update_out, bits_out, x, M, d, ld, scale, seed, stream);
+    if (schedule == MARSIT_SCHEDULE_TORUS)
+        return ragged_torus_impl(g, c, update_out, bits_out, x, M, d, ld, scale, seed, grid_x, stream);
+    return ring_step_impl(g, c, update_out, bits_out, x, M, d, ld, scale, seed, 0, stream);
 }
 
 }   // extern "C"

@@ -17,7 +17,14 @@ namespace marsit {
 
 constexpr int kBlock = 256;       // every kernel but the fused ones
 constexpr int kSyncBlock = 64;    // fused kernels: one wavefront per workgroup
-constexpr uint64_t kMaxElements = static_cast<uint64_t>(1) << 37;   // word index stays below 2^31
+// Largest vector any entry point takes.  The widest launches use one work-item per column of 4
+// elements, rounded up to whole workgroups of kBlock, and a launch may not reach 2^32 work-items
+// in x: ceil(d / 4) rounded up to 256 stays below 2^32 exactly when d <= 2^34 - 1024.
+constexpr uint64_t kMaxElements = MARSIT_MAX_ELEMENTS;
+static_assert(((kMaxElements + 3) / 4 + 255) / 256 * 256 < (static_cast<uint64_t>(1) << 32),
+              "a launch over MARSIT_MAX_ELEMENTS elements must stay below 2^32 work-items");
+static_assert((((kMaxElements + 1) + 3) / 4 + 255) / 256 * 256 >= (static_cast<uint64_t>(1) << 32),
+              "MARSIT_MAX_ELEMENTS is the largest size one launch covers");
 
 // hipError_t of the last failed HIP call of this thread (marsit_last_hip_error)
 extern thread_local int tls_last_hip_error;

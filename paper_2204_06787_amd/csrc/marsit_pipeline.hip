@@ -122,7 +122,7 @@ struct PipelineLayout {
 
 static bool pipeline_layout(uint32_t M, uint64_t d, uint32_t grid_x, PipelineLayout *L)
 {
-    if (M == 0 || M > MARSIT_MAX_WORKERS || d > (static_cast<uint64_t>(1) << 37))
+    if (M == 0 || M > MARSIT_MAX_WORKERS || d > MARSIT_MAX_ELEMENTS)
         return false;
     L->X = (grid_x == 0) ? M : grid_x;
     if (L->X == 0 || M % L->X != 0)

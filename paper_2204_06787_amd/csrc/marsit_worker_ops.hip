@@ -335,6 +335,13 @@ const char *marsit_status_string(int status)
     }
 }
 
+uint64_t marsit_grid_work_items(uint64_t d)
+{
+    if (d == 0 || d > kMaxElements)
+        return 0;
+    return static_cast<uint64_t>(blocks_for((d + 3) >> 2)) * kBlock;
+}
+
 void marsit_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
 {
     philox4x32_10(ctr[0], ctr[1], ctr[2], ctr[3], key[0], key[1], out);

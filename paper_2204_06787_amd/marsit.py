@@ -16,6 +16,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libmarsit.so")
 
 MAX_WORKERS = 64
+MAX_ELEMENTS = (1 << 34) - 1024
 OK, EINVAL, EALIGN, EHIP, ESCRATCH = 0, -1, -2, -3, -4
 STATIC_SCRATCH_WORDS = 4194304
 
@@ -33,7 +34,7 @@ EXPORTS = (
     "marsit_ragged_torus_step_sim", "marsit_ragged_torus_step_apply",
     "marsit_ssdm_cascade_hop", "marsit_cascade_ring_step_sim",
     "marsit_hop_merge_device_seed", "marsit_set_device_seed",
-    "marsit_exchange_step_sim_static",
+    "marsit_exchange_step_sim_static", "marsit_grid_work_items", "marsit_round",
 )
 
 _lib = None
@@ -66,6 +67,8 @@ def load_library(path: str | None = None):
     lib.marsit_last_hip_error.restype = ci
     lib.marsit_status_string.argtypes = [ci]
     lib.marsit_status_string.restype = ctypes.c_char_p
+    lib.marsit_grid_work_items.argtypes = [u64]
+    lib.marsit_grid_work_items.restype = u64
     lib.marsit_philox4x32_10.argtypes = [vp, vp, vp]
     lib.marsit_philox4x32_10.restype = None
     lib.marsit_split_bounds.argtypes = [u64, u32, u32, vp]
@@ -134,6 +137,8 @@ def load_library(path: str | None = None):
     lib.marsit_ragged_torus_step_apply.restype = ci
     lib.marsit_step_apply.argtypes = [u64, u64, vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
     lib.marsit_step_apply.restype = ci
+    lib.marsit_round.argtypes = [u64, u64, ci, u32, vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, vp]
+    lib.marsit_round.restype = ci
     lib.marsit_apply_update.argtypes = [vp, vp, u64, vp]
     lib.marsit_apply_update.restype = ci
     lib.marsit_local_momentum.argtypes = [vp, vp, vp, u32, u64, u64, f32, f32, vp]
@@ -455,6 +460,21 @@ def marsit_step_apply(t: int, K: int, g, c, x, update_out, bits_out, scale: floa
         _bits_ptr(bits_out, "bits_out", True, need=n_words(d)), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF, grid_x,
         _stream(stream)))
     return x
+
+
+SCHEDULE_RING, SCHEDULE_TORUS, SCHEDULE_TREE = 0, 1, 2
+
+
+def marsit_round(t: int, K: int, schedule: int, grid_x: int, g, c, x, update_out, bits_out, scale: float,
+                 seed: int, d: int | None = None, stream=None):
+    """One round of Algorithm 1 (and of Algorithm 2 when ``x`` is given) over the named schedule."""
+    M, ld, d = _matrix_args(g, c, d)
+    _check("marsit_round", load_library().marsit_round(
+        t, K, schedule, grid_x, _f32_ptr(g, "g"), _f32_ptr(c, "c"), _f32_ptr(x, "x", True, need=d),
+        _f32_ptr(update_out, "update_out", True, need=d),
+        _bits_ptr(bits_out, "bits_out", True, need=n_words(d)), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF,
+        _stream(stream)))
+    return update_out
 
 
 def marsit_apply_update(x, update, d: int | None = None, stream=None):

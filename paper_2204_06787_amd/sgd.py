@@ -1,9 +1,10 @@
 """Marsit-driven SGD (Algorithm 2 of the paper) for M workers simulated on one GPU.
 
 A thin driver: it owns the state Algorithm 2 carries between rounds (the model ``x``, the
-compensation vectors ``c``, the round counter) and calls the library once per round for the
-synchronisation (Algorithm 1: one-bit pass, or the full-precision round every ``K`` rounds) with the
-model update in the same pass.  All arithmetic runs in the HIP kernels.
+compensation vectors ``c``, the round counter) and makes one library call per round
+(``marsit_round``: Algorithm 1 over the chosen schedule -- the one-bit pass, or the full-precision
+round every ``K`` rounds, decided inside the library -- with the model update in the same pass).
+All arithmetic and every decision of the method run in the library.
 """
 
 from __future__ import annotations
@@ -30,6 +31,8 @@ class MarsitSGD:
             raise ValueError("K must be at least 1")
         self.x, self.M, self.K, self.eta_s, self.seed = x, int(M), int(K), float(eta_s), int(seed)
         self.schedule = schedule
+        self._schedule_id = {"ring": marsit.SCHEDULE_RING, "torus": marsit.SCHEDULE_TORUS,
+                             "tree": marsit.SCHEDULE_TREE}[schedule]
         self.grid_x = int(grid_x) if schedule == "torus" else 0
         if schedule == "torus" and not 1 <= self.grid_x <= self.M:
             raise ValueError("torus: grid_x must be in 1..M")
@@ -54,28 +57,7 @@ class MarsitSGD:
         """One round.  ``scaled_grads``: ``[M, d]`` float32, worker m's stochastic gradient already
         multiplied by the local step size.  Returns the global update that was applied to ``x``."""
         seed = (self.seed + self.t) & 0xFFFFFFFFFFFFFFFF
-        one_bit = self.t % self.K != 0
-        ragged = self.grid_x != 0 and self.M % self.grid_x != 0          # torus with a short last row
-        if self.schedule == "tree" and one_bit:
-            marsit.marsit_tree_step_apply(scaled_grads, self.c, self.x, self.update, self.bits, self.eta_s,
-                                          seed, stream=stream)
-        elif ragged and one_bit:
-            marsit.marsit_ragged_torus_step_apply(scaled_grads, self.c, self.x, self.update, self.bits,
-                                                  self.eta_s, seed, self.grid_x, stream=stream)
-        elif ragged:
-            # the full-precision round does not depend on the schedule
-            marsit.marsit_step_apply(self.t, self.K, scaled_grads, self.c, self.x, self.update, self.bits,
-                                     self.eta_s, seed, grid_x=0, stream=stream)
-        else:
-            marsit.marsit_step_apply(self.t, self.K, scaled_grads, self.c, self.x, self.update, self.bits,
-                                     self.eta_s, seed, grid_x=self.grid_x, stream=stream)
+        marsit.marsit_round(self.t, self.K, self._schedule_id, self.grid_x, scaled_grads, self.c, self.x,
+                            self.update, self.bits, self.eta_s, seed, stream=stream)
         self.t += 1
         return self.update
-
-    def average_bits_per_element(self, rounds: int | None = None) -> float:
-        """Transmitted bits per element and round: 32 in a full-precision round, 1 otherwise."""
-        n = self.t if rounds is None else int(rounds)
-        if n == 0:
-            return 0.0
-        full = (n + self.K - 1) // self.K                       # rounds t = 0, K, 2K, ... below n
-        return (32.0 * full + (n - full)) / n

@@ -92,10 +92,65 @@ def test_ring_step_argument_validation(lib):
     assert call(gx=3) == marsit.EINVAL
     assert call(scale=float("inf")) == marsit.EINVAL
     assert call(scale=float("nan")) == marsit.EINVAL
-    assert call(d=(1 << 37) + 1, ld=(1 << 37) + 1) == marsit.EINVAL
+    assert call(d=marsit.MAX_ELEMENTS + 1, ld=marsit.MAX_ELEMENTS + 1) == marsit.EINVAL
     assert call(g=FAKE + 2) == marsit.EALIGN
     assert call(b=FAKE + 4) == marsit.EALIGN
     assert call(d=0) == marsit.OK            # empty input: success, nothing launched
+
+
+def test_size_limit_is_what_one_launch_can_cover(lib):
+    """Every kernel covers its vector with one launch of at most one work-item per 4 elements in
+    whole workgroups of 256, and a launch must stay below 2^32 work-items in x.  The limit in the
+    header is exactly the largest d for which that holds; larger sizes are refused as invalid
+    arguments by every entry point, before anything is launched."""
+    header = open(os.path.join(ROOT, "include", "marsit.h")).read()
+    limit = int(re.search(r"#define\s+MARSIT_MAX_ELEMENTS\s+(\d+)ull", header).group(1))
+    assert limit == marsit.MAX_ELEMENTS == (1 << 34) - 1024
+
+    def work_items(d, block):          # the launch geometry, recomputed here
+        cols = (d + 3) // 4
+        return (cols + block - 1) // block * block
+    for d in (1, 4, 5, 1023, 1024, 1025, 25_600_000, (1 << 32) + 197, (1 << 34) - 1028, limit - 4, limit - 1, limit):
+        assert lib.marsit_grid_work_items(d) == work_items(d, 256), d
+        assert work_items(d, 256) < (1 << 32) and work_items(d, 64) < (1 << 32), d
+        # the per-word kernels: 16 work-items per packed word, 64 per 4 words in marsit_compress
+        words = (d + 63) // 64
+        assert (words * 16 + 255) // 256 * 256 < (1 << 32)
+        assert ((words + 3) // 4 * 64 + 255) // 256 * 256 < (1 << 32)
+    assert work_items(limit + 1, 256) == (1 << 32)                   # the first size one launch cannot cover
+    for d in (limit + 1, 1 << 34, (1 << 34) + 4, 1 << 37, (1 << 37) + 1, (1 << 64) - 1):
+        assert lib.marsit_grid_work_items(d) == 0, d
+    assert lib.marsit_grid_work_items(0) == 0
+
+    for d in (limit + 1, 1 << 34, 1 << 37):
+        E = marsit.EINVAL
+        assert lib.marsit_ring_step_sim(FAKE, FAKE, FAKE, None, 1, d, d, 1e-3, 1, 0, None) == E
+        assert lib.marsit_tree_step_sim(FAKE, FAKE, FAKE, None, 1, d, d, 1e-3, 1, None) == E
+        assert lib.marsit_ragged_torus_step_sim(FAKE, FAKE, FAKE, None, 3, d, d, 1e-3, 1, 2, None) == E
+        assert lib.marsit_full_sync(FAKE, FAKE, FAKE, 1, d, d, None) == E
+        assert lib.marsit_step(1, 2, FAKE, FAKE, FAKE, None, 1, d, d, 1e-3, 1, 0, None) == E
+        assert lib.marsit_step_apply(1, 2, FAKE, FAKE, FAKE, None, None, 1, d, d, 1e-3, 1, 0, None) == E
+        assert lib.marsit_round(1, 2, 0, 0, FAKE, FAKE, FAKE, None, None, 1, d, d, 1e-3, 1, None) == E
+        assert lib.marsit_round(0, 2, 2, 0, FAKE, FAKE, FAKE, None, None, 1, d, d, 1e-3, 1, None) == E
+        assert lib.marsit_compress(FAKE, None, FAKE, d, None) == E
+        assert lib.marsit_decode_compensate(FAKE, FAKE, None, 1.0, None, FAKE, d, None) == E
+        assert lib.marsit_decode_compensate_apply(FAKE, FAKE, None, 1.0, FAKE + 64, None, FAKE, d, None) == E
+        assert lib.marsit_compress_hop_merge(FAKE, FAKE, None, FAKE, 0, d, 2, 1, 1, None) == E
+        assert lib.marsit_hop_merge(FAKE, FAKE, FAKE, 0, d // 64 + 1, 2, 1, 5, None) == E
+        assert lib.marsit_hop_merge_weighted(FAKE, FAKE, FAKE, 0, d // 64 + 1, 2, 1, 1, 5, None) == E
+        assert lib.marsit_fold_segments(FAKE, d, 2, 0, FAKE, 0, d // 64 + 1, 0, 5, None) == E
+        assert lib.marsit_apply_update(FAKE, FAKE, d, None) == E
+        assert lib.marsit_local_momentum(FAKE, FAKE + 64, FAKE + 64, 1, d, d, 0.5, 0.1, None) == E
+        assert lib.marsit_chain_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, 1, d, d, 1.0, 1, 0, None) == E
+        assert lib.marsit_exchange_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, 1, d, d, 1.0, 1, 0, None) == E
+        assert lib.marsit_exchange_step_sim_static(FAKE, FAKE, FAKE, FAKE, 1, d, d, 1.0, 1, 0, None) == E
+        assert lib.marsit_aggregate_sign(FAKE, FAKE, FAKE, 1, d, d, None) == E
+        assert lib.marsit_majority_vote(FAKE, FAKE, FAKE, 1, d, d, None) == E
+        assert lib.marsit_count_matching(FAKE, FAKE, d, FAKE, None) == E
+        assert lib.marsit_ssdm_cascade_hop(None, None, FAKE, FAKE, FAKE, FAKE, FAKE, 0, d, 1, 1, None) == E
+        assert lib.marsit_cascade_ring_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, FAKE, 1, d, d, 1, None) == E
+        assert marsit.marsit_chain_workspace_words(1, d, 0) == 0
+        assert lib.marsit_pipeline_workspace_words(1, d, 0) == 0
 
 
 def test_other_entry_points_argument_validation(lib):

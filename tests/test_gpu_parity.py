@@ -545,3 +545,65 @@ def test_binding_rejects_short_or_strided_operands():
         marsit.marsit_apply_update(u.double(), u)
     torch.cuda.synchronize()
     assert not u.any() and not c.any()
+
+
+# ------------------------------------------------------------------------------------------------
+# NaN inputs: outside the bit-for-bit contract at the NaN's own position, but they must not leak
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("M,grid_x,d", [(8, 0, 64 * 40 + 17), (16, 4, 64 * 33), (9, 0, 64 * 21 + 5), (7, 3, 64 * 19 + 63)])
+def test_nan_elements_leave_their_neighbours_bit_exact(M, grid_x, d):
+    """A NaN in one worker's element e can only change position e of the outputs (the sign of a NaN
+    that an add produces is machine-dependent, so position e itself is outside the bit-for-bit
+    contract).  Everything else -- the other 63 bits of the word, the other elements of every
+    vector -- equals the oracle bit for bit, and position e still decodes to +-scale."""
+    scale, seed = 2e-3, 4242
+    rng = np.random.default_rng(d + M)
+    g = rng.standard_normal((M, d)).astype(np.float32)
+    c = (0.3 * rng.standard_normal((M, d))).astype(np.float32)
+    planted = sorted(set(int(e) for e in rng.integers(0, d, size=12)) | {0, 63, 64, d - 1})
+    for n, e in enumerate(planted):
+        m = n % M
+        if n % 3 == 0:
+            g[m, e] = np.nan                                  # a NaN that is passed through
+        elif n % 3 == 1:
+            g[m, e], c[m, e] = np.inf, -np.inf                # a NaN that the add produces
+        else:
+            g[:, e] = np.nan                                  # NaN in every worker
+    ragged = grid_x != 0 and M % grid_x != 0
+    c_h = c.copy()
+    with np.errstate(invalid="ignore"):
+        if ragged:
+            want_u, want_b, _ = orc.ragged_torus_step(g, c_h, scale, seed, grid_x)
+        else:
+            want_u, want_b, _ = oracle_step(g, c_h, scale, seed, grid_x=grid_x)
+    g_d, c_d = dev(g), dev(c)
+    update = torch.empty(d, dtype=torch.float32, device="cuda")
+    bits = marsit.new_bitmap(d)
+    if ragged:
+        marsit.marsit_ragged_torus_step_sim(g_d, c_d, update, bits, scale, seed, grid_x)
+    else:
+        marsit.marsit_ring_step_sim(g_d, c_d, update, bits, scale, seed, grid_x=grid_x)
+    torch.cuda.synchronize()
+    got_u, got_b, got_c = host_f32(update), host_bits(bits), host_f32(c_d)
+
+    clean = np.ones(d, dtype=bool)
+    clean[planted] = False
+    assert np.array_equal(got_u.view(np.uint32)[clean], want_u.view(np.uint32)[clean])
+    assert np.array_equal(got_c.view(np.uint32)[:, clean], c_h.view(np.uint32)[:, clean])
+    mask = np.zeros(orc.n_words(d), dtype=np.uint64)                 # bit positions that are planted
+    for e in planted:
+        mask[e // 64] |= np.uint64(1) << np.uint64(e % 64)
+    assert np.array_equal(got_b & ~mask, want_b & ~mask)
+    # the planted positions: still a valid decode, consistent with the bitmap and the compensation
+    with np.errstate(invalid="ignore"):
+        s = g + c
+    for e in planted:
+        assert abs(got_u[e]) == np.float32(scale)
+        bit = (int(got_b[e // 64]) >> (e % 64)) & 1
+        assert (got_u[e] > 0) == bool(bit)
+        for m in range(M):
+            if np.isnan(s[m, e]):
+                assert np.isnan(got_c[m, e])
+            else:
+                assert got_c[m, e] == np.float32(s[m, e] - got_u[e])
