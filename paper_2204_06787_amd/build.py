@@ -27,6 +27,17 @@ HIPCC_FLAGS = [
 ]
 
 
+def fused_sources_digest() -> str:
+    """First 16 hex digits of the SHA-256 of the sources that define the fused kernels.  Counter
+    summaries of those kernels record it, so a reader can tell whether they describe this tree."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("marsit_fused.hip", "marsit_device.hpp", "marsit_host.hpp"):
+        with open(os.path.join(PKG, "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def hipcc() -> str:
     exe = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     if not os.path.exists(exe):

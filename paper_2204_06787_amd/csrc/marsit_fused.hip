@@ -174,107 +174,330 @@ sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
         bits32[2u * static_cast<size_t>(w) + (q >> 3)] = half;
 }
 
-// Staging area of the generic kernels: s = g + c of every worker for the wavefront's 64 columns,
-// [M][64] 128-bit entries in dynamic LDS (M KB per one-wavefront workgroup).  A lane only ever
-// touches its own entries, so no barrier is needed.  With it g and c are read once and c is
-// written once, whatever M is.
+// -------------------------------------------------------------------------------------------------
+// Fused pass for any number of workers, any schedule (ring, torus, torus with a short last row,
+// tree), any alignment, ragged tails.  The draws of Eq. 2 do not depend on the data and only the
+// last successful draw of a chain decides a bit, so a lane evaluates the chains of its four bits
+// on the draws alone and ends with the index of the one worker whose sign each bit takes
+// (pick_workers_*).  Two kernels use that:
+//
+//   staged_step_kernel (M <= kMaxStagedWorkers): s = g + c of every worker is staged in LDS,
+//     [M][64] 128-bit entries per one-wavefront workgroup.  The first batch of loads is issued
+//     before the draws, which run while it is in flight; the picked workers' signs are looked up in
+//     LDS and the compensation is written from LDS.  g and c are read once.
+//   sweep_step_kernel (more workers than LDS can stage at a useful occupancy): "draws first,
+//     gather, one sweep" -- fetch just the (at most four) picked elements of g and c, form the
+//     update, then stream over the M workers once, kSweepBatch at a time.  Nothing is staged; the
+//     lines the gather touched are fetched again by the sweep when they have left the L2 by then
+//     (measured at M = 64: 1.25 x the algorithmic reads).
+//
+// Both cover columns col_begin .. ceil(d/4)-1 (col_begin is a multiple of 16).
+// -------------------------------------------------------------------------------------------------
+constexpr int kSweepBatch = 8;   // workers whose loads are issued back to back (sweep, full-precision round)
+
+enum SweepSchedule { kSweepTorus = 0, kSweepRaggedTorus = 1, kSweepTree = 2 };
+
+struct SweepShape {
+    uint32_t M;           // workers
+    uint32_t X, Y;        // torus: columns, rows (ring: X = M, Y = 1)
+    uint32_t X_last;      // ragged torus: workers of the last row
+    uint32_t top_level;   // tree: ceil(log2 M)
+};
+
+__device__ __forceinline__ uint32_t pick4(const uint32_t v[4], uint32_t j)
+{
+    return (j == 0) ? v[0] : (j == 1) ? v[1] : (j == 2) ? v[2] : v[3];
+}
+
+// Ring or torus whose rows are all X long: worker picked by each of the lane's four bits.
+// Column chain first (which row result survives, per bit), then the chain of that row.  With up
+// to four rows every row's chain is evaluated once and serves all four bits (Y*(X-1) calls);
+// with more rows each bit evaluates the chain of its own row (4*(X-1) calls).
+__device__ __forceinline__ void pick_workers_torus(uint32_t w, uint32_t q, uint32_t key0, uint32_t key1,
+                                                   const SweepShape &shape, const PartTable &parts,
+                                                   const ThresholdTable &thresholds, uint32_t worker[4])
+{
+    const uint32_t X = shape.X, Y = shape.Y, M = shape.M;
+    uint32_t f = 0;                                   // Algorithm 1, split step
+    for (uint32_t k = 1; k < M; ++k)
+        f += (w >= parts.bound[k]) ? 1u : 0u;
+    const uint32_t a = f / Y;
+    const uint32_t b = f % Y;
+
+    uint32_t pick_col[4] = {0, 0, 0, 0};
+    for (uint32_t ky = 1; ky < Y; ++ky) {
+        uint32_t u[4];
+        philox4x32_10(q, col_hop_id(ky), w, 0u, key0, key1, u);
+        const uint32_t thr = thresholds.thr[ky + 1];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            pick_col[j] = (u[j] < thr) ? ky : pick_col[j];
+    }
+    if (Y <= 4) {
+        for (uint32_t ky = 0; ky < Y; ++ky) {
+            uint32_t y = b + ky;
+            y = (y >= Y) ? y - Y : y;
+            uint32_t pick_row[4] = {0, 0, 0, 0};
+            for (uint32_t kx = 1; kx < X; ++kx) {
+                uint32_t u[4];
+                philox4x32_10(q, row_hop_id(y, kx), w, 0u, key0, key1, u);
+                const uint32_t thr = thresholds.thr[kx + 1];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    pick_row[j] = (u[j] < thr) ? kx : pick_row[j];
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t x = a + pick_row[j];
+                x = (x >= X) ? x - X : x;
+                worker[j] = (pick_col[j] == ky) ? y * X + x : worker[j];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t y = b + pick_col[j];
+            y = (y >= Y) ? y - Y : y;
+            uint32_t pick_row = 0;
+            for (uint32_t kx = 1; kx < X; ++kx) {
+                uint32_t u[4];
+                philox4x32_10(q, row_hop_id(y, kx), w, 0u, key0, key1, u);
+                pick_row = (u[j] < thresholds.thr[kx + 1]) ? kx : pick_row;
+            }
+            uint32_t x = a + pick_row;
+            x = (x >= X) ? x - X : x;
+            worker[j] = y * X + x;
+        }
+    }
+}
+
+// Torus whose last row is short (M is not a multiple of the X columns): rows of X workers, the
+// last one of X_last; the row chains run over the row's own length from column a mod X_y, and the
+// column merges are weighted by the workers each side stands for.  parts.bound[0..X] holds the X
+// row-parts; the Y sub-parts of a row-part follow the same floor rule and are found arithmetically.
+__device__ __forceinline__ void pick_workers_ragged(uint32_t w, uint32_t q, uint32_t key0, uint32_t key1,
+                                                    const SweepShape &shape, const PartTable &parts,
+                                                    const ThresholdTable &thresholds, uint32_t worker[4])
+{
+    const uint32_t X = shape.X, Y = shape.Y, X_last = shape.X_last;
+    uint32_t a = 0;                                   // split step: row-part a, then sub-part b of it
+    for (uint32_t k = 1; k < X; ++k)
+        a += (w >= parts.bound[k]) ? 1u : 0u;
+    const uint32_t lo = parts.bound[a];
+    const uint64_t n_part = parts.bound[a + 1] - lo;
+    uint32_t b = 0;
+    for (uint32_t k = 1; k < Y; ++k)
+        b += (w >= lo + static_cast<uint32_t>((k * n_part) / Y)) ? 1u : 0u;
+
+    // column chain: which row result survives, per bit (weighted draws)
+    uint32_t pick_col[4] = {0, 0, 0, 0};
+    uint32_t gathered = (b + 1u == Y) ? X_last : X;
+    for (uint32_t k = 1; k < Y; ++k) {
+        uint32_t y = b + k;
+        y = (y >= Y) ? y - Y : y;
+        const uint32_t w_local = (y + 1u == Y) ? X_last : X;
+        const uint32_t thr = weighted_threshold(gathered, w_local);
+        uint32_t u[4];
+        philox4x32_10(q, col_hop_id(k), w, 0u, key0, key1, u);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            pick_col[j] = (u[j] < thr) ? k : pick_col[j];
+        gathered += w_local;
+    }
+    if (Y <= 4) {
+        for (uint32_t k = 0; k < Y; ++k) {
+            uint32_t y = b + k;
+            y = (y >= Y) ? y - Y : y;
+            const uint32_t Xy = (y + 1u == Y) ? X_last : X;
+            uint32_t pick_row[4] = {0, 0, 0, 0};
+            for (uint32_t h = 1; h < Xy; ++h) {
+                uint32_t u[4];
+                philox4x32_10(q, row_hop_id(y, h), w, 0u, key0, key1, u);
+                const uint32_t thr = thresholds.thr[h + 1];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    pick_row[j] = (u[j] < thr) ? h : pick_row[j];
+            }
+            const uint32_t a_y = a % Xy;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                uint32_t x = a_y + pick_row[j];
+                x = (x >= Xy) ? x - Xy : x;
+                worker[j] = (pick_col[j] == k) ? y * X + x : worker[j];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            uint32_t y = b + pick_col[j];
+            y = (y >= Y) ? y - Y : y;
+            const uint32_t Xy = (y + 1u == Y) ? X_last : X;
+            uint32_t pick_row = 0;
+            for (uint32_t h = 1; h < Xy; ++h) {
+                uint32_t u[4];
+                philox4x32_10(q, row_hop_id(y, h), w, 0u, key0, key1, u);
+                pick_row = (u[j] < thresholds.thr[h + 1]) ? h : pick_row;
+            }
+            uint32_t x = a % Xy + pick_row;
+            x = (x >= Xy) ? x - Xy : x;
+            worker[j] = y * X + x;
+        }
+    }
+}
+
+// Binary reduction tree: only the merges on the way from the root to the chosen leaf decide a bit
+// (all draws are independent), so every bit walks down the tree with at most ceil(log2 M) draws.
+// The merge at the root is the same for the four bits and is drawn once.
+__device__ __forceinline__ void pick_workers_tree(uint32_t w, uint32_t q, uint32_t key0, uint32_t key1,
+                                                  const SweepShape &shape, uint32_t worker[4])
+{
+    const uint32_t M = shape.M;
+    uint32_t level = shape.top_level;
+    uint32_t k4[4] = {0, 0, 0, 0};
+    if (level > 0) {
+        --level;
+        const uint32_t stride = 1u << level;          // stride < M by the definition of top_level
+        const uint32_t w_recv = (M - stride < stride) ? (M - stride) : stride;
+        const uint32_t thr = (w_recv == stride) ? 0x80000000u : weighted_threshold(w_recv, stride);
+        uint32_t u[4];
+        philox4x32_10(q, tree_hop_id(level, 0u), w, 0u, key0, key1, u);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            k4[j] = (u[j] < thr) ? 0u : stride;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        uint32_t k = k4[j];
+        for (uint32_t l = level; l-- > 0;) {
+            const uint32_t stride = 1u << l;
+            const uint32_t src = k + stride;
+            if (src >= M)
+                continue;
+            const uint32_t w_recv = (M - src < stride) ? (M - src) : stride;
+            const uint32_t thr = (w_recv == stride) ? 0x80000000u : weighted_threshold(w_recv, stride);
+            uint32_t u[4];
+            philox4x32_10(q, tree_hop_id(l, k), w, 0u, key0, key1, u);
+            k = (u[j] < thr) ? k : src;
+        }
+        worker[j] = k;
+    }
+}
+
 extern __shared__ __align__(16) unsigned char marsit_dynamic_lds[];
 
-constexpr int kSweepBatch = 8;   // workers whose loads are issued back to back
-
-// Compensated gradient of Algorithm 1 for a run-time number of workers: s -> LDS.
-__device__ __forceinline__ void stage_sums(const float *__restrict__ g, const float *c, f32x4 *stage,
-                                           uint32_t M, uint64_t ld, uint64_t e, bool vec,
-                                           uint32_t n_valid)
-{
-    for (uint32_t m0 = 0; m0 < M; m0 += kSweepBatch) {
-        f32x4 gv[kSweepBatch], cv[kSweepBatch];
-#pragma unroll
-        for (int i = 0; i < kSweepBatch; ++i) {
-            if (m0 + i < M) {
-                const size_t off = static_cast<size_t>(m0 + i) * ld + e;
-                gv[i] = load4(g + off, vec, n_valid);
-                cv[i] = load4(c + off, vec, n_valid);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < kSweepBatch; ++i)
-            if (m0 + i < M)
-                stage[static_cast<size_t>(m0 + i) * kSyncBlock + threadIdx.x] = gv[i] + cv[i];
-    }
-}
-
-// Compensation update of Algorithm 1 for a run-time number of workers: c <- s - update, s from LDS.
-__device__ __forceinline__ void compensate_from_stage(float *c, const f32x4 *stage, f32x4 upd,
-                                                      uint32_t M, uint64_t ld, uint64_t e, bool vec,
-                                                      uint32_t n_valid)
-{
-#pragma unroll 4
-    for (uint32_t m = 0; m < M; ++m) {
-        const f32x4 sv = stage[static_cast<size_t>(m) * kSyncBlock + threadIdx.x];
-        store4<MARSIT_STREAMING_STORES>(c + static_cast<size_t>(m) * ld + e, sv - upd, vec, n_valid);
-    }
-}
-
-// The same without the staging area (for M so large that the area would leave too few wavefronts
-// per CU): g and c are read again.
-__device__ __forceinline__ void compensate_from_memory(const float *__restrict__ g, float *c, f32x4 upd,
-                                                       uint32_t M, uint64_t ld, uint64_t e, bool vec,
-                                                       uint32_t n_valid)
-{
-    for (uint32_t m0 = 0; m0 < M; m0 += kSweepBatch) {
-        f32x4 gv[kSweepBatch], cv[kSweepBatch];
-#pragma unroll
-        for (int i = 0; i < kSweepBatch; ++i) {
-            if (m0 + i < M) {
-                const size_t off = static_cast<size_t>(m0 + i) * ld + e;
-                gv[i] = load4(g + off, vec, n_valid);
-                cv[i] = load4(c + off, vec, n_valid);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < kSweepBatch; ++i) {
-            if (m0 + i < M) {
-                const size_t off = static_cast<size_t>(m0 + i) * ld + e;
-                store4<MARSIT_STREAMING_STORES>(c + off, (gv[i] + cv[i]) - upd, vec, n_valid);
-            }
-        }
-    }
-}
-
-// Sign word of element j of worker `worker`: from the staging area, or straight from memory.
-template <bool STAGED>
-__device__ __forceinline__ uint32_t picked_sign(const f32x4 *stage, const float *__restrict__ g,
-                                                const float *c, uint32_t worker, uint64_t ld,
-                                                uint64_t e, int j)
-{
-    if (STAGED) {
-        const f32x4 sv = stage[static_cast<size_t>(worker) * kSyncBlock + threadIdx.x];
-        const float v = (j == 0) ? sv.x : (j == 1) ? sv.y : (j == 2) ? sv.z : sv.w;
-        return f32_bits(v) & 0x80000000u;
-    }
-    const size_t at = static_cast<size_t>(worker) * ld + e + static_cast<uint32_t>(j);
-    return f32_bits(g[at] + c[at]) & 0x80000000u;
-}
-
-// -------------------------------------------------------------------------------------------------
-// Fused pass, any schedule (X, Y at run time), any alignment, ragged tails.  Covers columns
-// col_begin .. ceil(d/4)-1 (col_begin is a multiple of 16).  s of every worker is staged in LDS,
-// the chains are evaluated on the draws alone (which worker does each bit end up taking), that
-// worker's sign is looked up in LDS, and the compensation is written from LDS: 12*M + 4 bytes per
-// element, like the compiled schedules.
-// -------------------------------------------------------------------------------------------------
-template <bool STAGED>
+template <int SCHED, int BATCH>
 __global__ void __launch_bounds__(kSyncBlock)
-sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
-                         float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
-                         uint64_t ld, uint64_t col_begin, uint32_t scale_bits, uint32_t key0,
-                         uint32_t key1, uint32_t X, uint32_t Y, PartTable parts,
-                         ThresholdTable thresholds, float *__restrict__ x_model)
+staged_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
+                   uint32_t *__restrict__ bits32, uint64_t d, uint64_t ld, uint64_t col_begin,
+                   uint32_t scale_bits, uint32_t key0, uint32_t key1, SweepShape shape, PartTable parts,
+                   ThresholdTable thresholds, float *__restrict__ x_model)
 {
-    const uint32_t M = X * Y;
+    const uint32_t M = shape.M;
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
+    const uint32_t w = static_cast<uint32_t>(col >> 4);
+    const uint32_t q = static_cast<uint32_t>(col) & 15u;
+    uint32_t nib = 0;
+
+    if (col < n_cols) {
+        const uint64_t e = col << 2;
+        const bool full = e + 4 <= d;
+        const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+        const bool vec = full;
+        // a lane only ever touches its own entries of the staging area, so no barrier is needed
+        f32x4 *stage = reinterpret_cast<f32x4 *>(marsit_dynamic_lds) + threadIdx.x;
+
+        // the first batch of loads goes out before the draws, which run while it is in flight.
+        // A batch is straight-line code: past the last worker it loads and stages the last worker
+        // again (same lines, same values) instead of branching.
+        f32x4 gv[BATCH], cv[BATCH];
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+            {
+                const uint32_t mm = (static_cast<uint32_t>(i) < M) ? static_cast<uint32_t>(i) : M - 1u;
+                const size_t off = static_cast<size_t>(mm) * ld + e;
+                gv[i] = load4(g + off, vec, n_valid);
+                cv[i] = load4(c + off, vec, n_valid);
+            }
+        }
+        f32x4 xv = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (x_model != nullptr)
+            xv = load4(x_model + e, vec, n_valid);
+        __builtin_amdgcn_sched_barrier(0);
+
+        uint32_t worker[4] = {0, 0, 0, 0};
+        if (SCHED == kSweepTorus)
+            pick_workers_torus(w, q, key0, key1, shape, parts, thresholds, worker);
+        else if (SCHED == kSweepRaggedTorus)
+            pick_workers_ragged(w, q, key0, key1, shape, parts, thresholds, worker);
+        else
+            pick_workers_tree(w, q, key0, key1, shape, worker);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // compensated gradient of every worker into LDS (Algorithm 1, first step)
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i)
+            {
+                const uint32_t mm = (static_cast<uint32_t>(i) < M) ? static_cast<uint32_t>(i) : M - 1u;
+                stage[static_cast<size_t>(mm) * kSyncBlock] = gv[i] + cv[i];
+            }
+#pragma unroll 1
+        for (uint32_t m0 = BATCH; m0 < M; m0 += BATCH) {
+#pragma unroll
+            for (int i = 0; i < BATCH; ++i) {
+                {
+                    const uint32_t mm = (m0 + i < M) ? m0 + i : M - 1u;
+                    const size_t off = static_cast<size_t>(mm) * ld + e;
+                    gv[i] = load4(g + off, vec, n_valid);
+                    cv[i] = load4(c + off, vec, n_valid);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < BATCH; ++i)
+                {
+                    const uint32_t mm = (m0 + i < M) ? m0 + i : M - 1u;
+                    stage[static_cast<size_t>(mm) * kSyncBlock] = gv[i] + cv[i];
+                }
+        }
+
+        // global update from the picked workers' signs
+        f32x4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            if (static_cast<uint32_t>(j) < n_valid) {
+                const f32x4 sv = stage[static_cast<size_t>(worker[j]) * kSyncBlock];
+                const uint32_t sign = f32_bits(sv[j]) & 0x80000000u;
+                upd[j] = __uint_as_float(scale_bits ^ sign);
+                nib |= (sign == 0u) ? (1u << j) : 0u;
+            }
+        }
+        if (update != nullptr)
+            store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
+        if (x_model != nullptr)       // Algorithm 2, model update in the same pass
+            store4<MARSIT_STREAMING_STORES>(x_model + e, xv - upd, vec, n_valid);
+
+        // compensation update c <- s - update, s from LDS
+#pragma unroll 4
+        for (uint32_t m = 0; m < M; ++m) {
+            const f32x4 sv = stage[static_cast<size_t>(m) * kSyncBlock];
+            store4<MARSIT_STREAMING_STORES>(c + static_cast<size_t>(m) * ld + e, sv - upd, vec, n_valid);
+        }
+    }
+
+    const uint32_t half = gather_half_word(nib, q);
+    if (bits32 != nullptr && (q & 7u) == 0u && static_cast<uint64_t>(w) * 64u < d)
+        bits32[2u * static_cast<size_t>(w) + (q >> 3)] = half;
+}
+
+template <int SCHED>
+__global__ void __launch_bounds__(kSyncBlock)
+sweep_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
+                  uint32_t *__restrict__ bits32, uint64_t d, uint64_t ld, uint64_t col_begin,
+                  uint32_t scale_bits, uint32_t key0, uint32_t key1, SweepShape shape, PartTable parts,
+                  ThresholdTable thresholds, float *__restrict__ x_model)
+{
+    const uint32_t M = shape.M;
     const uint64_t n_cols = (d + 3) >> 2;
     const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
     const uint32_t w = static_cast<uint32_t>(col >> 4);
@@ -287,175 +510,76 @@ sync_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
         const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
         const bool vec = full;
 
-        uint32_t f = 0;
-        for (uint32_t k = 1; k < M; ++k)
-            f += (w >= parts.bound[k]) ? 1u : 0u;
-        const uint32_t a = f / Y;
-        const uint32_t b = f % Y;
+        // (1) the draws: which worker does each bit end up taking
+        uint32_t worker[4] = {0, 0, 0, 0};
+        if (SCHED == kSweepTorus)
+            pick_workers_torus(w, q, key0, key1, shape, parts, thresholds, worker);
+        else if (SCHED == kSweepRaggedTorus)
+            pick_workers_ragged(w, q, key0, key1, shape, parts, thresholds, worker);
+        else
+            pick_workers_tree(w, q, key0, key1, shape, worker);
 
-        // compensated gradient of every worker into LDS
-        f32x4 *stage = reinterpret_cast<f32x4 *>(marsit_dynamic_lds);
-        if (STAGED)
-            stage_sums(g, c, stage, M, ld, e, vec, n_valid);
-
-        // The draws do not depend on the data, and only the last successful draw of a chain
-        // matters: find the picked worker of every bit, then look its sign up.
-        // Column chain (shared by the lane's four bits): which row result survives.
-        uint32_t pick_col[4] = {0, 0, 0, 0};
-        for (uint32_t ky = 1; ky < Y; ++ky) {
-            uint32_t u[4];
-            philox4x32_10(q, col_hop_id(ky), w, 0u, key0, key1, u);
-            const uint32_t thr = thresholds.thr[ky + 1];
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                pick_col[j] = (u[j] < thr) ? ky : pick_col[j];
-        }
-        // Row chain of the surviving row.  On a ring all four bits share the one row and one call
-        // per hop serves them; on a torus the rows differ per bit.
-        uint32_t row_of[4], pick_row[4] = {0, 0, 0, 0};
+        // (2) gather: the picked workers' elements (ordinary loads, so the lines stay in L2 for
+        // the sweep), and behind them the first batch of the sweep and the model
+        float pg[4] = {0.0f, 0.0f, 0.0f, 0.0f}, pc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            const uint32_t y = b + pick_col[j];
-            row_of[j] = (y >= Y) ? y - Y : y;
-        }
-        if (Y == 1) {
-            for (uint32_t kx = 1; kx < X; ++kx) {
-                uint32_t u[4];
-                philox4x32_10(q, row_hop_id(0, kx), w, 0u, key0, key1, u);
-                const uint32_t thr = thresholds.thr[kx + 1];
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    pick_row[j] = (u[j] < thr) ? kx : pick_row[j];
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                for (uint32_t kx = 1; kx < X; ++kx) {
-                    uint32_t u[4];
-                    philox4x32_10(q, row_hop_id(row_of[j], kx), w, 0u, key0, key1, u);
-                    pick_row[j] = (u[j] < thresholds.thr[kx + 1]) ? kx : pick_row[j];
-                }
+            if (static_cast<uint32_t>(j) < n_valid) {
+                const size_t at = static_cast<size_t>(worker[j]) * ld + e + static_cast<uint32_t>(j);
+                pg[j] = g[at];
+                pc[j] = c[at];
             }
         }
+        f32x4 gv[kSweepBatch], cv[kSweepBatch];
+#pragma unroll
+        for (int i = 0; i < kSweepBatch; ++i) {
+            if (static_cast<uint32_t>(i) < M) {
+                const size_t off = static_cast<size_t>(i) * ld + e;
+                gv[i] = load4(g + off, vec, n_valid);
+                cv[i] = load4(c + off, vec, n_valid);
+            }
+        }
+        f32x4 xv = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (x_model != nullptr)
+            xv = load4(x_model + e, vec, n_valid);
+        __builtin_amdgcn_sched_barrier(0);
 
+        // global update: +scale where the picked sign bit is clear, -scale where it is set
         f32x4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             if (static_cast<uint32_t>(j) < n_valid) {
-                uint32_t x = a + pick_row[j];
-                x = (x >= X) ? x - X : x;
-                const uint32_t sign = picked_sign<STAGED>(stage, g, c, row_of[j] * X + x, ld, e, j);
-                upd[j] = __uint_as_float(scale_bits ^ sign);          // global update
+                const uint32_t sign = f32_bits(pg[j] + pc[j]) & 0x80000000u;   // compensated gradient's sign
+                upd[j] = __uint_as_float(scale_bits ^ sign);
                 nib |= (sign == 0u) ? (1u << j) : 0u;
             }
         }
         if (update != nullptr)
             store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
-        if (x_model != nullptr) {
-            // Algorithm 2, model update in the same pass
-            const f32x4 xv = load4(x_model + e, vec, n_valid);
+        if (x_model != nullptr)       // Algorithm 2, model update in the same pass
             store4<MARSIT_STREAMING_STORES>(x_model + e, xv - upd, vec, n_valid);
-        }
 
-        if (STAGED)
-            compensate_from_stage(c, stage, upd, M, ld, e, vec, n_valid);
-        else
-            compensate_from_memory(g, c, upd, M, ld, e, vec, n_valid);
-    }
-
-    const uint32_t half = gather_half_word(nib, q);
-    if (bits32 != nullptr && (q & 7u) == 0u && static_cast<uint64_t>(w) * 64u < d)
-        bits32[2u * static_cast<size_t>(w) + (q >> 3)] = half;
-}
-
-// -------------------------------------------------------------------------------------------------
-// Fused pass over a torus whose last row is short (M is not a multiple of the X columns): rows of
-// X workers, the last one of X_last; the row chains run over the row's own length and the column
-// merges are weighted by the workers each side stands for.  Same structure as the generic kernel:
-// s staged in LDS, chains evaluated on the draws alone (column chain first, then the chain of the
-// row it names), one sign looked up per bit.  parts.bound[0..X] holds the X row-parts; the Y
-// sub-parts of a row-part follow the same floor rule and are found arithmetically.
-// -------------------------------------------------------------------------------------------------
-template <bool STAGED>
-__global__ void __launch_bounds__(kSyncBlock)
-sync_step_ragged_kernel(const float *__restrict__ g, float *__restrict__ c,
-                        float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
-                        uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1, uint32_t M,
-                        uint32_t X, uint32_t Y, uint32_t X_last, PartTable parts,
-                        ThresholdTable thresholds, float *__restrict__ x_model)
-{
-    const uint64_t n_cols = (d + 3) >> 2;
-    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
-    const uint32_t w = static_cast<uint32_t>(col >> 4);
-    const uint32_t q = static_cast<uint32_t>(col) & 15u;
-    uint32_t nib = 0;
-
-    if (col < n_cols) {
-        const uint64_t e = col << 2;
-        const bool full = e + 4 <= d;
-        const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
-        const bool vec = full;
-
-        // split step: row-part a, then sub-part b of it
-        uint32_t a = 0;
-        for (uint32_t k = 1; k < X; ++k)
-            a += (w >= parts.bound[k]) ? 1u : 0u;
-        const uint32_t lo = parts.bound[a];
-        const uint64_t n_part = parts.bound[a + 1] - lo;
-        uint32_t b = 0;
-        for (uint32_t k = 1; k < Y; ++k)
-            b += (w >= lo + static_cast<uint32_t>((k * n_part) / Y)) ? 1u : 0u;
-
-        f32x4 *stage = reinterpret_cast<f32x4 *>(marsit_dynamic_lds);
-        if (STAGED)
-            stage_sums(g, c, stage, M, ld, e, vec, n_valid);
-
-        // column chain: which row result survives, per bit (weighted draws)
-        uint32_t pick_col[4] = {0, 0, 0, 0};
-        uint32_t gathered = (b + 1u == Y) ? X_last : X;
-        for (uint32_t k = 1; k < Y; ++k) {
-            uint32_t y = b + k;
-            y = (y >= Y) ? y - Y : y;
-            const uint32_t w_local = (y + 1u == Y) ? X_last : X;
-            const uint32_t thr = weighted_threshold(gathered, w_local);
-            uint32_t u[4];
-            philox4x32_10(q, col_hop_id(k), w, 0u, key0, key1, u);
+        // (3) the sweep: compensation update c <- (g + c) - update for every worker
+#pragma unroll 1
+        for (uint32_t m0 = 0; m0 < M; m0 += kSweepBatch) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                pick_col[j] = (u[j] < thr) ? k : pick_col[j];
-            gathered += w_local;
-        }
-
-        f32x4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
-        for (uint32_t j = 0; j < n_valid; ++j) {
-            const uint32_t pc = (j == 0) ? pick_col[0] : (j == 1) ? pick_col[1] : (j == 2) ? pick_col[2] : pick_col[3];
-            uint32_t y = b + pc;
-            y = (y >= Y) ? y - Y : y;
-            const uint32_t Xy = (y + 1u == Y) ? X_last : X;
-            // the chain of row y over its own Xy workers, from column a mod Xy
-            uint32_t pick_row = 0;
-            for (uint32_t h = 1; h < Xy; ++h) {
-                uint32_t u[4];
-                philox4x32_10(q, row_hop_id(y, h), w, 0u, key0, key1, u);
-                const uint32_t uj = (j == 0) ? u[0] : (j == 1) ? u[1] : (j == 2) ? u[2] : u[3];
-                pick_row = (uj < thresholds.thr[h + 1]) ? h : pick_row;
+            for (int i = 0; i < kSweepBatch; ++i) {
+                if (m0 + i < M) {
+                    const size_t off = static_cast<size_t>(m0 + i) * ld + e;
+                    store4<MARSIT_STREAMING_STORES>(c + off, (gv[i] + cv[i]) - upd, vec, n_valid);
+                }
             }
-            const uint32_t column = (a % Xy + pick_row) % Xy;
-            const uint32_t sign = picked_sign<STAGED>(stage, g, c, y * X + column, ld, e, static_cast<int>(j));
-            const float uval = __uint_as_float(scale_bits ^ sign);
-            if (j == 0) upd.x = uval; else if (j == 1) upd.y = uval; else if (j == 2) upd.z = uval; else upd.w = uval;
-            nib |= (sign == 0u) ? (1u << j) : 0u;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < kSweepBatch; ++i) {
+                if (m0 + kSweepBatch + i < M) {
+                    const size_t off = static_cast<size_t>(m0 + kSweepBatch + i) * ld + e;
+                    gv[i] = load4(g + off, vec, n_valid);
+                    cv[i] = load4(c + off, vec, n_valid);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        if (update != nullptr)
-            store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
-        if (x_model != nullptr) {
-            const f32x4 xv = load4(x_model + e, vec, n_valid);
-            store4<MARSIT_STREAMING_STORES>(x_model + e, xv - upd, vec, n_valid);
-        }
-        if (STAGED)
-            compensate_from_stage(c, stage, upd, M, ld, e, vec, n_valid);
-        else
-            compensate_from_memory(g, c, upd, M, ld, e, vec, n_valid);
     }
 
     const uint32_t half = gather_half_word(nib, q);
@@ -559,81 +683,18 @@ tree_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
         bits32[2u * static_cast<size_t>(w) + (q >> 3)] = half;
 }
 
-// Any M, any alignment, ragged tails.  Only the merges on the way from the root to the chosen
-// leaf decide a bit (all draws are independent), so every bit walks down the tree with at most
-// ceil(log2 M) draws and looks up the sign of the one worker it ends at; s of every worker is
-// staged in LDS as in the generic ring kernel.
-template <bool STAGED>
-__global__ void __launch_bounds__(kSyncBlock)
-tree_step_generic_kernel(const float *__restrict__ g, float *__restrict__ c,
-                         float *__restrict__ update, uint32_t *__restrict__ bits32, uint64_t d,
-                         uint64_t ld, uint64_t col_begin, uint32_t scale_bits, uint32_t key0,
-                         uint32_t key1, uint32_t M, uint32_t top_level,
-                         float *__restrict__ x_model)
-{
-    const uint64_t n_cols = (d + 3) >> 2;
-    const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
-    const uint32_t w = static_cast<uint32_t>(col >> 4);
-    const uint32_t q = static_cast<uint32_t>(col) & 15u;
-    uint32_t nib = 0;
-
-    if (col < n_cols) {
-        const uint64_t e = col << 2;
-        const bool full = e + 4 <= d;
-        const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
-        const bool vec = full;
-
-        f32x4 *stage = reinterpret_cast<f32x4 *>(marsit_dynamic_lds);
-        if (STAGED)
-            stage_sums(g, c, stage, M, ld, e, vec, n_valid);
-
-        f32x4 upd = {0.0f, 0.0f, 0.0f, 0.0f};
-        for (uint32_t j = 0; j < n_valid; ++j) {
-            uint32_t k = 0;
-            for (uint32_t level = top_level; level-- > 0;) {
-                const uint32_t stride = 1u << level;
-                const uint32_t src = k + stride;
-                if (src >= M)
-                    continue;
-                const uint32_t w_recv = (M - src < stride) ? (M - src) : stride;
-                const uint32_t thr = (w_recv == stride) ? 0x80000000u : weighted_threshold(w_recv, stride);
-                uint32_t u[4];
-                philox4x32_10(q, tree_hop_id(level, k), w, 0u, key0, key1, u);
-                const uint32_t uj = (j == 0) ? u[0] : (j == 1) ? u[1] : (j == 2) ? u[2] : u[3];
-                k = (uj < thr) ? k : src;
-            }
-            const uint32_t sign = picked_sign<STAGED>(stage, g, c, k, ld, e, static_cast<int>(j));
-            const float uval = __uint_as_float(scale_bits ^ sign);
-            if (j == 0) upd.x = uval; else if (j == 1) upd.y = uval; else if (j == 2) upd.z = uval; else upd.w = uval;
-            nib |= (sign == 0u) ? (1u << j) : 0u;
-        }
-        if (update != nullptr)
-            store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
-        if (x_model != nullptr) {
-            const f32x4 xv = load4(x_model + e, vec, n_valid);
-            store4<MARSIT_STREAMING_STORES>(x_model + e, xv - upd, vec, n_valid);
-        }
-        if (STAGED)
-            compensate_from_stage(c, stage, upd, M, ld, e, vec, n_valid);
-        else
-            compensate_from_memory(g, c, upd, M, ld, e, vec, n_valid);
-    }
-
-    const uint32_t half = gather_half_word(nib, q);
-    if (bits32 != nullptr && (q & 7u) == 0u && static_cast<uint64_t>(w) * 64u < d)
-        bits32[2u * static_cast<size_t>(w) + (q >> 3)] = half;
-}
-
 // -------------------------------------------------------------------------------------------------
 // Full-precision round (Algorithm 1, branch mod(t,K) == 0) for M simulated workers.
 // -------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kBlock)
+// Any worker count, any alignment, ragged tails: one-wavefront workgroups, the workers taken
+// kSweepBatch at a time with the batch's loads issued back to back.
+__global__ void __launch_bounds__(kSyncBlock)
 full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
                  uint32_t M, uint64_t d, uint64_t ld, uint64_t col_begin,
                  float *__restrict__ x_model)
 {
     const uint64_t n_cols = (d + 3) >> 2;
-    const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
     if (col >= n_cols)
         return;
     const uint64_t e = col << 2;
@@ -645,14 +706,32 @@ full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
     // double, rounded once to fp32
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
     const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll 4
-    for (uint32_t m = 0; m < M; ++m) {
-        const size_t off = static_cast<size_t>(m) * ld + e;
-        const f32x4 sv = load4(g + off, vec, n_valid) + load4(c + off, vec, n_valid);
+    f32x4 xv = zero;
+    if (x_model != nullptr)
+        xv = load4(x_model + e, vec, n_valid);
+#pragma unroll 1
+    for (uint32_t m0 = 0; m0 < M; m0 += kSweepBatch) {
+        f32x4 gv[kSweepBatch], cv[kSweepBatch];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            acc[j] += static_cast<double>(sv[j]);
-        store4<MARSIT_STREAMING_STORES>(c + off, zero, vec, n_valid);
+        for (int i = 0; i < kSweepBatch; ++i) {
+            if (m0 + i < M) {
+                const size_t off = static_cast<size_t>(m0 + i) * ld + e;
+                gv[i] = load4(g + off, vec, n_valid);
+                cv[i] = load4(c + off, vec, n_valid);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < kSweepBatch; ++i) {
+            if (m0 + i < M) {
+                const f32x4 sv = gv[i] + cv[i];
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[j] += static_cast<double>(sv[j]);
+                store4<MARSIT_STREAMING_STORES>(c + static_cast<size_t>(m0 + i) * ld + e, zero, vec, n_valid);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
     const double dm = static_cast<double>(M);
     f32x4 mean;
@@ -661,10 +740,8 @@ full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
         mean[j] = static_cast<float>(acc[j] / dm);
     if (update != nullptr)
         store4<MARSIT_STREAMING_STORES>(update + e, mean, vec, n_valid);
-    if (x_model != nullptr) {
-        const f32x4 xv = load4(x_model + e, vec, n_valid);
+    if (x_model != nullptr)
         store4<MARSIT_STREAMING_STORES>(x_model + e, xv - mean, vec, n_valid);
-    }
 }
 
 // The same for a compile-time worker count, whole aligned columns only, launched like the fused
@@ -742,28 +819,93 @@ inline uint32_t throttle_lds_bytes(uint32_t waves)
     return ((lds_per_cu / waves) * 31u / 32u) & ~511u;
 }
 
-// Dynamic LDS of the generic kernels: the [M][64] staging area of 128-bit entries (M KB per
-// wavefront).  Above 40 workers it would leave fewer than four wavefronts per CU, and reading g
-// and c twice is faster (measured at M = 64: 62 % against 54 % of HBM peak).
-constexpr uint32_t kMaxStagedWorkers = 40;
-inline uint32_t generic_lds_bytes(uint32_t M)
+// The any-schedule kernels.  Up to kMaxStagedWorkers workers the [M][64] staging area of 128-bit
+// entries (M KB per one-wavefront workgroup) is the dynamic LDS request, never less than what
+// leaves room for staged_waves_per_cu() workgroups on a CU; above (fewer than three wavefronts
+// would fit on a CU, too few to hide the M - 1 draws of each) the gather-and-sweep kernel runs,
+// throttled like the compiled schedules by LDS it never touches.
+// Measured on MI355X at 25.6 M elements (fraction of the 8 TB/s HBM peak, best wavefront count and
+// batch per worker count): M = 5: 14 wavefronts, batch 4 (70 %); 7: 10, 4 (75 %); 9, 10: 8, 4
+// (74-75 %); 11-18: 5, 8 (73-75 %; short last row: 7); 24, 32: 4, 8 (73 %, 72 %); 40: 69 %; 41, 48: batch 16 (66 %,
+// 68 %); ring of 64 staged: 52 %, gather-and-sweep: 63 %.  A plain streaming kernel with the same
+// 2M read and M + 1 write streams (the full-precision round) reaches 80 % at M = 9, 74 % at 24,
+// 70 % at 32 and 66 % at 64: the fall with M is the memory system's, not these kernels'.
+constexpr uint32_t kMaxStagedWorkers = 48;
+
+inline uint32_t staged_batch(uint32_t M)
 {
-    // never less than 20 KB: at most 8 wavefronts per CU (measured best for M = 9, 10: 72 % of peak
-    // against 65 % with 17 wavefronts)
-    const uint32_t need = M * static_cast<uint32_t>(kSyncBlock) * 16u;
-    return need > 20u * 1024u ? need : 20u * 1024u;
+    return M <= 10 ? 4u : (M <= 40 ? 8u : 16u);
 }
 
-// The same for the short-last-row kernel, whose lanes spend more of their time on per-bit draws:
-// it wants more wavefronts at small M (measured at 12.8 M elements: M = 5: 8 KB per wavefront,
-// 71 % of HBM peak against 59 % with 20 KB; M = 7: 12 KB; M = 13: 20 KB).
-inline uint32_t ragged_lds_bytes(uint32_t M)
+inline uint32_t staged_waves_per_cu(uint32_t M, int sched)
+{
+    if (M > 20)
+        return 4;
+    if (M > 10)     // the short-last-row schedule spends more draws per lane and wants more wavefronts
+        return sched == kSweepRaggedTorus ? 7 : 5;
+    const uint32_t waves = 72u / M;
+    return waves < 8u ? 8u : (waves > 14u ? 14u : waves);
+}
+
+inline uint32_t staged_lds_bytes(uint32_t M, int sched)
 {
     const uint32_t need = M * static_cast<uint32_t>(kSyncBlock) * 16u;
-    uint32_t want = ((need * 8u / 5u) + 511u) & ~511u;
-    if (want > 20u * 1024u)
-        want = 20u * 1024u;
-    return need > want ? need : want;
+    const uint32_t throttle = throttle_lds_bytes(staged_waves_per_cu(M, sched));
+    return need > throttle ? need : throttle;
+}
+
+constexpr uint32_t kSweepWavesPerCu = 8;   // gather-and-sweep kernel; 6 to 16 measure the same
+
+// Any-M kernel of the full-precision round: 4 one-wavefront workgroups per CU up to 16 workers,
+// 3 above (measured: M = 9: 79 %, 24: 74 %, 32: 70 %, 64: 66 % of the HBM peak).
+inline uint32_t full_sync_waves_per_cu(uint32_t M)
+{
+    return M <= 16 ? 4u : 3u;
+}
+
+inline ThresholdTable keep_thresholds()
+{
+    ThresholdTable thresholds;
+    thresholds.thr[0] = 0;
+    thresholds.thr[1] = 0xFFFFFFFFu;
+    for (uint32_t m = 2; m <= MARSIT_MAX_WORKERS; ++m)
+        thresholds.thr[m] = keep_threshold(m);
+    return thresholds;
+}
+
+// Launches the any-schedule kernel over columns col_begin .. ceil(d/4) - 1.
+template <int SCHED>
+void launch_sweep(const float *g, float *c, float *update, uint32_t *bits32, uint64_t d, uint64_t ld,
+                  uint64_t col_begin, uint32_t scale_bits, uint32_t key0, uint32_t key1,
+                  const SweepShape &shape, const PartTable &parts, float *x_model, hipStream_t stream)
+{
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint32_t blocks = static_cast<uint32_t>((n_cols - col_begin + kSyncBlock - 1) / kSyncBlock);
+    const ThresholdTable thresholds = keep_thresholds();
+    if (shape.M > kMaxStagedWorkers) {
+        hipLaunchKernelGGL((sweep_step_kernel<SCHED>), dim3(blocks), dim3(kSyncBlock),
+                           throttle_lds_bytes(kSweepWavesPerCu), stream, g, c, update, bits32, d, ld, col_begin,
+                           scale_bits, key0, key1, shape, parts, thresholds, x_model);
+        return;
+    }
+    const uint32_t lds = staged_lds_bytes(shape.M, SCHED);
+    switch (staged_batch(shape.M)) {
+    case 4:
+        hipLaunchKernelGGL((staged_step_kernel<SCHED, 4>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,
+                           update, bits32, d, ld, col_begin, scale_bits, key0, key1, shape, parts, thresholds,
+                           x_model);
+        break;
+    case 8:
+        hipLaunchKernelGGL((staged_step_kernel<SCHED, 8>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,
+                           update, bits32, d, ld, col_begin, scale_bits, key0, key1, shape, parts, thresholds,
+                           x_model);
+        break;
+    default:
+        hipLaunchKernelGGL((staged_step_kernel<SCHED, 16>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,
+                           update, bits32, d, ld, col_begin, scale_bits, key0, key1, shape, parts, thresholds,
+                           x_model);
+        break;
+    }
 }
 
 template <int X, int Y>
@@ -790,7 +932,9 @@ SyncLauncher find_specialisation(uint32_t X, uint32_t Y)
 #define MARSIT_CASE(XX, YY) \
     if (X == XX && Y == YY) return &launch_sync_step<XX, YY>;
     MARSIT_CASE(1, 1) MARSIT_CASE(2, 1) MARSIT_CASE(3, 1) MARSIT_CASE(4, 1) MARSIT_CASE(5, 1)
-    MARSIT_CASE(6, 1) MARSIT_CASE(7, 1) MARSIT_CASE(8, 1) MARSIT_CASE(12, 1) MARSIT_CASE(16, 1)
+    MARSIT_CASE(6, 1) MARSIT_CASE(7, 1) MARSIT_CASE(8, 1) MARSIT_CASE(9, 1) MARSIT_CASE(10, 1)
+    MARSIT_CASE(11, 1) MARSIT_CASE(12, 1) MARSIT_CASE(13, 1) MARSIT_CASE(14, 1) MARSIT_CASE(15, 1)
+    MARSIT_CASE(16, 1)
     MARSIT_CASE(2, 2) MARSIT_CASE(3, 2) MARSIT_CASE(2, 3) MARSIT_CASE(4, 2) MARSIT_CASE(2, 4)
     MARSIT_CASE(3, 3) MARSIT_CASE(4, 4)
 #undef MARSIT_CASE
@@ -917,22 +1061,9 @@ static int ring_step_impl(const float *g, float *c, float *update_out, uint64_t 
     }
     const uint64_t n_cols = (d + 3) >> 2;
     if (generic_col_begin < n_cols) {
-        ThresholdTable thresholds;
-        thresholds.thr[0] = 0;
-        thresholds.thr[1] = 0xFFFFFFFFu;
-        for (uint32_t m = 2; m <= MARSIT_MAX_WORKERS; ++m)
-            thresholds.thr[m] = keep_threshold(m);
-        const uint32_t blocks =
-            static_cast<uint32_t>((n_cols - generic_col_begin + kSyncBlock - 1) / kSyncBlock);
-        if (M <= kMaxStagedWorkers)
-            hipLaunchKernelGGL(sync_step_generic_kernel<true>, dim3(blocks), dim3(kSyncBlock),
-                               generic_lds_bytes(M), s, g, c, update_out, bits32, d, ld,
-                               generic_col_begin, scale_bits, key0, key1, X, Y, parts, thresholds,
-                               x_model);
-        else
-            hipLaunchKernelGGL(sync_step_generic_kernel<false>, dim3(blocks), dim3(kSyncBlock), 0, s, g, c,
-                               update_out, bits32, d, ld, generic_col_begin, scale_bits, key0, key1, X, Y,
-                               parts, thresholds, x_model);
+        const SweepShape shape = {M, X, Y, X, 0u};
+        launch_sweep<kSweepTorus>(g, c, update_out, bits32, d, ld, generic_col_begin, scale_bits, key0, key1,
+                                  shape, parts, x_model, s);
         return finish_launch();
     }
     return MARSIT_OK;
@@ -964,26 +1095,12 @@ static int ragged_torus_impl(const float *g, float *c, float *update_out, uint64
     PartTable parts;
     for (uint32_t k = 0; k <= MARSIT_MAX_WORKERS; ++k)
         parts.bound[k] = static_cast<uint32_t>(k <= X ? row_bounds[k] : n_words);
-    ThresholdTable thresholds;
-    thresholds.thr[0] = 0;
-    thresholds.thr[1] = 0xFFFFFFFFu;
-    for (uint32_t m = 2; m <= MARSIT_MAX_WORKERS; ++m)
-        thresholds.thr[m] = keep_threshold(m);
-
     const uint32_t scale_bits = float_bits_host(scale);
     const uint32_t key0 = static_cast<uint32_t>(seed), key1 = static_cast<uint32_t>(seed >> 32);
-    uint32_t *bits32 = reinterpret_cast<uint32_t *>(bits_out);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const uint64_t n_cols = (d + 3) >> 2;
-    const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
-    if (M <= kMaxStagedWorkers)
-        hipLaunchKernelGGL(sync_step_ragged_kernel<true>, dim3(blocks), dim3(kSyncBlock),
-                           ragged_lds_bytes(M), s, g, c, update_out, bits32, d, ld, scale_bits, key0, key1,
-                           M, X, Y, X_last, parts, thresholds, x_model);
-    else
-        hipLaunchKernelGGL(sync_step_ragged_kernel<false>, dim3(blocks), dim3(kSyncBlock), 0, s, g, c,
-                           update_out, bits32, d, ld, scale_bits, key0, key1, M, X, Y, X_last,
-                           parts, thresholds, x_model);
+    const SweepShape shape = {M, X, Y, X_last, 0u};
+    launch_sweep<kSweepRaggedTorus>(g, c, update_out, reinterpret_cast<uint32_t *>(bits_out), d, ld, 0,
+                                    scale_bits, key0, key1, shape, parts, x_model,
+                                    static_cast<hipStream_t>(stream));
     return finish_launch();
 }
 
@@ -1010,8 +1127,10 @@ static int full_sync_impl(const float *g, float *c, float *update_out, float *x_
     }
     const uint64_t n_cols = (d + 3) >> 2;
     if (col_begin < n_cols) {
-        hipLaunchKernelGGL(full_sync_kernel, dim3(blocks_for(n_cols - col_begin)), dim3(kBlock), 0, s,
-                           g, c, update_out, M, d, ld, col_begin, x_model);
+        const uint32_t blocks = static_cast<uint32_t>((n_cols - col_begin + kSyncBlock - 1) / kSyncBlock);
+        hipLaunchKernelGGL(full_sync_kernel, dim3(blocks), dim3(kSyncBlock),
+                           throttle_lds_bytes(full_sync_waves_per_cu(M)), s, g, c, update_out, M, d, ld, col_begin,
+                           x_model);
         return finish_launch();
     }
     return MARSIT_OK;
@@ -1062,16 +1181,12 @@ static int tree_step_impl(const float *g, float *c, float *update_out, uint64_t 
         uint32_t top_level = 0;
         while ((1u << top_level) < M)
             ++top_level;
-        const uint32_t blocks =
-            static_cast<uint32_t>((n_cols - generic_col_begin + kSyncBlock - 1) / kSyncBlock);
-        if (M <= kMaxStagedWorkers)
-            hipLaunchKernelGGL(tree_step_generic_kernel<true>, dim3(blocks), dim3(kSyncBlock),
-                               generic_lds_bytes(M), s, g, c, update_out, bits32, d, ld,
-                               generic_col_begin, scale_bits, key0, key1, M, top_level, x_model);
-        else
-            hipLaunchKernelGGL(tree_step_generic_kernel<false>, dim3(blocks), dim3(kSyncBlock), 0, s, g, c,
-                               update_out, bits32, d, ld, generic_col_begin, scale_bits, key0, key1, M,
-                               top_level, x_model);
+        const SweepShape shape = {M, M, 1u, M, top_level};
+        PartTable no_parts;
+        for (uint32_t k = 0; k <= MARSIT_MAX_WORKERS; ++k)
+            no_parts.bound[k] = 0;                        // a tree folds whole vectors
+        launch_sweep<kSweepTree>(g, c, update_out, bits32, d, ld, generic_col_begin, scale_bits, key0, key1,
+                                 shape, no_parts, x_model, s);
         return finish_launch();
     }
     return MARSIT_OK;

@@ -54,7 +54,7 @@ def load_library(path: str | None = None):
     global _lib
     if _lib is not None and path is None:
         return _lib
-    path = path or LIB_PATH
+    path = path or os.environ.get("MARSIT_LIBRARY") or LIB_PATH     # MARSIT_LIBRARY: another build of the library
     if not os.path.exists(path):
         raise RuntimeError(
             f"{path} is missing: build the HIP library first (python -m paper_2204_06787_amd.build). "
@@ -143,7 +143,7 @@ def load_library(path: str | None = None):
     lib.marsit_apply_update.restype = ci
     lib.marsit_local_momentum.argtypes = [vp, vp, vp, u32, u64, u64, f32, f32, vp]
     lib.marsit_local_momentum.restype = ci
-    if path == LIB_PATH:
+    if path == (os.environ.get("MARSIT_LIBRARY") or LIB_PATH):
         _lib = lib
     return lib
 

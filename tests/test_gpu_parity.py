@@ -234,10 +234,19 @@ def test_fused_torus_shapes(X, Y, d):
     _check_fused(X * Y, d, grid_x=X, seed=0x2000 + X * 10 + Y)
 
 
-@pytest.mark.parametrize("M,grid_x", [(9, 0), (10, 5), (10, 2), (24, 6), (64, 0), (64, 8), (11, 0), (7, 1)])
+@pytest.mark.parametrize("M", [4, 6, 7, 9, 10, 11, 12, 13, 14, 15])
+@pytest.mark.parametrize("d", [64 * 7 + 5, 100_003])
+def test_fused_ring_every_compiled_worker_count(M, d):
+    _check_fused(M, d, grid_x=0, seed=0x1800 + M)
+
+
+@pytest.mark.parametrize("M,grid_x", [(10, 5), (10, 2), (24, 6), (64, 0), (64, 8), (7, 1), (17, 0), (20, 4), (21, 7),
+                                      (33, 0), (40, 0), (41, 0), (48, 6), (48, 0), (49, 0), (49, 7), (60, 5), (63, 0)])
 @pytest.mark.parametrize("d", [7, 640, 33_333])
 def test_fused_generic_schedule(M, grid_x, d):
-    """Schedules without a compiled specialisation run the generic kernel."""
+    """Schedules without a compiled specialisation run the any-schedule kernels: staged in LDS in
+    batches of 4, 8 or 16 workers up to 48 workers, gather-and-sweep above; tori of up to four rows
+    share the row draws among a lane's bits, taller ones draw per bit."""
     _check_fused(M, d, grid_x=grid_x, seed=0x3000 + M)
 
 
@@ -574,7 +583,7 @@ def test_nan_elements_leave_their_neighbours_bit_exact(M, grid_x, d):
     c_h = c.copy()
     with np.errstate(invalid="ignore"):
         if ragged:
-            want_u, want_b, _ = orc.ragged_torus_step(g, c_h, scale, seed, grid_x)
+            want_u, want_b = orc.ragged_torus_step(g, c_h, scale, seed, grid_x)
         else:
             want_u, want_b, _ = oracle_step(g, c_h, scale, seed, grid_x=grid_x)
     g_d, c_d = dev(g), dev(c)

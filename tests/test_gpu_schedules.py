@@ -57,7 +57,7 @@ def test_tree_step_compiled_schedules(M, d):
     _check_tree(M, d)
 
 
-@pytest.mark.parametrize("M", [9, 10, 11, 13, 24, 33, 64])
+@pytest.mark.parametrize("M", [9, 10, 11, 13, 24, 33, 41, 48, 49, 64])
 @pytest.mark.parametrize("d", [7, 4100, 50_001])
 def test_tree_step_generic(M, d):
     _check_tree(M, d)
@@ -91,11 +91,11 @@ def test_tree_step_full_size_headline_shape():
 # ------------------------------------------------------------------------------------------------
 
 @pytest.mark.parametrize("M,grid_x", [(3, 2), (5, 2), (5, 3), (7, 3), (5, 4), (11, 4), (13, 5), (23, 6), (41, 7),
-                                      (64, 9), (63, 8), (6, 3), (8, 8), (4, 1)])
+                                      (64, 9), (63, 8), (6, 3), (8, 8), (4, 1), (9, 2), (23, 4), (47, 5), (50, 7), (50, 12)])
 @pytest.mark.parametrize("d,ld,offset", [(7, 7, 0), (64 * 40, 64 * 40, 0), (33_333, 33_336, 0), (5001, 5003, 1)])
 def test_ragged_torus_step(M, grid_x, d, ld, offset):
-    """Short last row, weighted column merges; staged (M <= 40) and re-reading (M > 40) kernels,
-    ragged sizes, padded and misaligned rows, two steps with the compensation carried over; the
+    """Short last row, weighted column merges; staged (M <= 48) and gather-and-sweep (M > 48)
+    kernels, up to four rows (row draws shared by a lane's bits) and more (drawn per bit), ragged sizes, padded and misaligned rows, two steps with the compensation carried over; the
     dividing shapes take the plain torus kernels and must agree with the same oracle routine."""
     rng = np.random.default_rng(M * 100 + grid_x + d)
     c_h = np.zeros((M, ld), dtype=np.float32)

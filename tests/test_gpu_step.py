@@ -179,9 +179,9 @@ def test_round_with_schedule_selector(schedule, M, grid_x, d, ld, with_model):
             want_u = orc.full_sync(g_h, c_h, d=d)
         else:
             if schedule == "tree":
-                want_u, want_b, _ = orc.tree_step(g_h, c_h, scale, seed0 + t, d=d)
+                want_u, want_b = orc.tree_step(g_h, c_h, scale, seed0 + t, d=d)
             elif schedule == "torus":
-                want_u, want_b, _ = orc.ragged_torus_step(g_h, c_h, scale, seed0 + t, grid_x, d=d)
+                want_u, want_b = orc.ragged_torus_step(g_h, c_h, scale, seed0 + t, grid_x, d=d)
             else:
                 want_u, want_b, _ = orc.sync_step(g_h, c_h, scale, seed0 + t, d=d)
             assert np.array_equal(host_bits(bits), want_b), t
