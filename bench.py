@@ -76,7 +76,7 @@ def measured_traffic(key: str):
     summary covers this run or the summary was made from other kernel sources than the ones here."""
     from paper_2204_06787_amd import build as hip_build
     digest = hip_build.fused_sources_digest()
-    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*hbm_traffic*.txt"))):
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
         text = open(path).read()
         if not re.search(r"^key: " + re.escape(key) + r"\s*$", text, flags=re.M):
             continue
