@@ -809,16 +809,6 @@ inline uint32_t fused_waves_per_cu(uint32_t X, uint32_t Y)
     return waves;
 }
 
-// Dynamic LDS bytes per workgroup that leave room for exactly `waves` one-wavefront workgroups on
-// a CU: the kernels never touch it, it only limits how many of them are resident.
-inline uint32_t throttle_lds_bytes(uint32_t waves)
-{
-    constexpr uint32_t lds_per_cu = 160u * 1024u;   // gfx950; the runtime attribute reports 64 KB
-    // a few per cent below an even share: with an exact share one workgroup fewer fits.  At least
-    // 3 workgroups per CU keeps the request under the 64 KB a launch may ask for without opting in.
-    return ((lds_per_cu / waves) * 31u / 32u) & ~511u;
-}
-
 // The any-schedule kernels.  Up to kMaxStagedWorkers workers the [M][64] staging area of 128-bit
 // entries (M KB per one-wavefront workgroup) is the dynamic LDS request, never less than what
 // leaves room for staged_waves_per_cu() workgroups on a CU; above (fewer than three wavefronts
@@ -908,6 +898,15 @@ void launch_sweep(const float *g, float *c, float *update, uint32_t *bits32, uin
     }
 }
 
+// The tree kernel does a little less work between issuing its loads and using them and wants one
+// wavefront more (measured: M = 4: 6-7 wavefronts 79 %, 5: 78 %; M = 8: 4 wavefronts 77.7 %, 3: 75 %;
+// M = 16: 3 wavefronts 75 %, 4: 73 %).
+inline uint32_t tree_waves_per_cu(uint32_t M)
+{
+    const uint32_t waves = (28u + M / 2u) / M;
+    return waves < 3u ? 3u : waves;
+}
+
 template <int X, int Y>
 void launch_sync_step(const float *g, float *c, float *update, uint32_t *bits32, uint64_t n_cols,
                       uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1,
@@ -960,7 +959,7 @@ void launch_tree_step(const float *g, float *c, float *update, uint32_t *bits32,
                       uint64_t ld, uint32_t scale_bits, uint32_t key0, uint32_t key1, float *x_model,
                       hipStream_t stream)
 {
-    const uint32_t lds = throttle_lds_bytes(fused_waves_per_cu(M, 1));
+    const uint32_t lds = throttle_lds_bytes(tree_waves_per_cu(M));
     const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
     if (x_model == nullptr)
         hipLaunchKernelGGL((tree_step_kernel<M, false>), dim3(blocks), dim3(kSyncBlock), lds, stream, g, c,

@@ -53,6 +53,16 @@ inline uint32_t float_bits_host(float x)
     return u;
 }
 
+// Dynamic LDS bytes per workgroup that leave room for exactly `waves` one-wavefront workgroups on
+// a CU: the kernels never touch it, it only limits how many of them are resident.
+inline uint32_t throttle_lds_bytes(uint32_t waves)
+{
+    constexpr uint32_t lds_per_cu = 160u * 1024u;   // gfx950; the runtime attribute reports 64 KB
+    // a few per cent below an even share: with an exact share one workgroup fewer fits.  At least
+    // 3 workgroups per CU keeps the request under the 64 KB a launch may ask for without opting in.
+    return ((lds_per_cu / waves) * 31u / 32u) & ~511u;
+}
+
 // Fine part bounds of the schedule (see marsit_split_bounds in marsit.h).
 int split_bounds_host(uint64_t n_words, uint32_t M, uint32_t grid_x, uint64_t *bounds);
 

@@ -65,41 +65,6 @@ int split_bounds_host(uint64_t n_words, uint32_t M, uint32_t grid_x, uint64_t *b
 }
 
 // -------------------------------------------------------------------------------------------------
-// marsit_compress: a wavefront takes 64 consecutive elements per packed word, one per lane, and
-// the 64-lane ballot of "sign bit clear" IS the word.  Four words per wavefront per trip keep
-// eight independent 256-byte loads in flight.
-// -------------------------------------------------------------------------------------------------
-constexpr int kWordsPerWave = 4;
-
-__global__ void __launch_bounds__(kBlock)
-compress_kernel(const float *__restrict__ g, const float *__restrict__ c,
-                uint64_t *__restrict__ bits, uint64_t d, uint64_t n_words)
-{
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint64_t wave = (static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x) >> 6;
-    const uint64_t w0 = wave * kWordsPerWave;
-    if (w0 >= n_words)
-        return;   // uniform over the wavefront
-
-    float s[kWordsPerWave];
-    bool valid[kWordsPerWave];
-#pragma unroll
-    for (int i = 0; i < kWordsPerWave; ++i) {
-        const uint64_t e = (w0 + i) * 64u + lane;
-        valid[i] = e < d;
-        const float gv = valid[i] ? __builtin_nontemporal_load(g + e) : 0.0f;
-        const float cv = (valid[i] && c != nullptr) ? __builtin_nontemporal_load(c + e) : 0.0f;
-        s[i] = gv + cv;
-    }
-#pragma unroll
-    for (int i = 0; i < kWordsPerWave; ++i) {
-        const uint64_t word = __ballot(valid[i] && (f32_bits(s[i]) >> 31) == 0u);
-        if (lane == 0 && w0 + i < n_words)
-            bits[w0 + i] = word;
-    }
-}
-
-// -------------------------------------------------------------------------------------------------
 // marsit_hop_merge: lane = (packed word i, nibble q); one Philox call per lane.
 // -------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kBlock)
@@ -140,51 +105,92 @@ hop_merge_kernel(const uint32_t *recv32, const uint32_t *local32, uint32_t *out3
 }
 
 // -------------------------------------------------------------------------------------------------
-// marsit_compress_hop_merge: the sign step and one merge in one pass.  lane = one column of 4
-// elements = nibble q of packed word i: the local nibble comes from the sign bits of g + c instead
-// of a stored bitmap, the rest is hop_merge_kernel.
+// marsit_compress_hop_merge and marsit_compress: the sign step and one merge in one pass.  lane =
+// one column of 4 elements = nibble q of packed word i: the local nibble comes from the sign bits
+// of g + c instead of a stored bitmap, the rest is hop_merge_kernel; the nibbles of a word are
+// OR-gathered over the half rows with DPP moves.  With fold count 1 (marsit_compress, or the first
+// holder of a part) nothing is received and nothing is drawn.
 // -------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kBlock)
+// Launch shape of the kernels that stream one worker's vectors: one-wavefront workgroups, every lane
+// takes COLS columns 64 apart (so each access of the wavefront is one contiguous KB), all of a
+// lane's loads are issued before the first use, non-temporal accesses.  With two to five streams
+// these kernels want every wavefront the CU can hold (measured at 25.6 M elements: one column per
+// lane 80-82 % of the HBM peak for decode, model update and momentum, 74-77 % with four; two
+// columns per lane for the sign step, 79 % against 76 %).
+constexpr int kCompressCols = 2;                      // sign step (with or without a merge)
+constexpr int kStreamCols = 1;                        // decode, model update, momentum
+
+inline uint32_t stream_blocks(uint64_t n_cols, int cols_per_lane)
+{
+    const uint64_t per_block = static_cast<uint64_t>(kSyncBlock) * static_cast<uint64_t>(cols_per_lane);
+    return static_cast<uint32_t>((n_cols + per_block - 1) / per_block);
+}
+
+template <int COLS>
+__global__ void __launch_bounds__(kSyncBlock)
 compress_hop_merge_kernel(const uint32_t *recv32, const float *__restrict__ g,
                           const float *__restrict__ c, uint32_t *out32, uint64_t word_begin,
                           uint64_t n, uint32_t threshold, bool always_local, uint32_t hop_id,
                           uint32_t key0, uint32_t key1)
 {
     const uint64_t n_cols = (n + 3) >> 2;
-    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    const uint64_t i = col >> 4;
-    const uint32_t q = static_cast<uint32_t>(col) & 15u;
-    const size_t half_index = 2u * static_cast<size_t>(i) + (q >> 3);
-    const uint32_t shift = (q & 7u) * 4u;
     const uint64_t n_words = (n + 63) >> 6;
-    uint32_t nib = 0;
+    const uint64_t col0 = static_cast<uint64_t>(blockIdx.x) * (kSyncBlock * COLS) + threadIdx.x;
+    const uint32_t q = threadIdx.x & 15u;
+    const uint32_t shift = (q & 7u) * 4u;
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
 
-    if (col < n_cols) {
-        const uint64_t e = col << 2;
-        const bool full = e + 4 <= n;
-        const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(n - e);
-        const bool vec = full;
-        const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-        const f32x4 sv = load4<true>(g + e, vec, n_valid) + ((c != nullptr) ? load4<true>(c + e, vec, n_valid) : zero);
-        uint32_t l = 0;
+    f32x4 gv[COLS], cv[COLS];
+    uint32_t rv[COLS];
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            l |= (static_cast<uint32_t>(j) < n_valid && (f32_bits(sv[j]) >> 31) == 0u) ? (1u << j) : 0u;
-        const uint32_t r = always_local ? 0u : (recv32[half_index] >> shift) & 0xFu;
-        const uint64_t w = word_begin + i;
-        uint32_t u[4];
-        philox4x32_10(q, hop_id, static_cast<uint32_t>(w), static_cast<uint32_t>(w >> 32), key0,
-                      key1, u);
-        uint32_t t = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            t |= (always_local || u[j] < threshold) ? (1u << j) : 0u;
-        nib = (r ^ ((r ^ l) & t)) & ((1u << n_valid) - 1u);   // t ? l : r; bits past the end stay 0
+    for (int k = 0; k < COLS; ++k) {
+        const uint64_t col = col0 + static_cast<uint64_t>(k) * kSyncBlock;
+        gv[k] = zero;
+        cv[k] = zero;
+        rv[k] = 0;
+        if (col < n_cols) {
+            const uint64_t e = col << 2;
+            const bool full = e + 4 <= n;
+            const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(n - e);
+            gv[k] = load4<true>(g + e, full, n_valid);
+            if (c != nullptr)
+                cv[k] = load4<true>(c + e, full, n_valid);
+            if (!always_local)
+                rv[k] = recv32[2u * static_cast<size_t>(col >> 4) + (q >> 3)];
+        }
     }
-
-    const uint32_t half = half_row_or(nib << shift);
-    if (i < n_words && (q & 7u) == 0u)
-        out32[half_index] = half;
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < COLS; ++k) {
+        const uint64_t col = col0 + static_cast<uint64_t>(k) * kSyncBlock;
+        const uint64_t i = col >> 4;
+        uint32_t nib = 0;
+        if (col < n_cols) {
+            const uint64_t e = col << 2;
+            const uint32_t n_valid = (e + 4 <= n) ? 4u : static_cast<uint32_t>(n - e);
+            const f32x4 sv = gv[k] + cv[k];
+            uint32_t l = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                l |= (static_cast<uint32_t>(j) < n_valid && (f32_bits(sv[j]) >> 31) == 0u) ? (1u << j) : 0u;
+            const uint32_t r = (rv[k] >> shift) & 0xFu;
+            uint32_t t = 0xFu;                                    // fold 1: the local signs as they are
+            if (!always_local) {
+                const uint64_t w = word_begin + i;
+                uint32_t u[4];
+                philox4x32_10(q, hop_id, static_cast<uint32_t>(w), static_cast<uint32_t>(w >> 32), key0,
+                              key1, u);
+                t = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    t |= (u[j] < threshold) ? (1u << j) : 0u;
+            }
+            nib = (r ^ ((r ^ l) & t)) & ((1u << n_valid) - 1u);   // t ? l : r; bits past the end stay 0
+        }
+        const uint32_t half = half_row_or(nib << shift);           // every lane takes part
+        if (i < n_words && (q & 7u) == 0u)
+            out32[2u * static_cast<size_t>(i) + (q >> 3)] = half;
+    }
 }
 
 // -------------------------------------------------------------------------------------------------
@@ -241,76 +247,135 @@ fold_segments_kernel(const uint32_t *__restrict__ maps32, uint64_t stride_halves
 // -------------------------------------------------------------------------------------------------
 // marsit_decode_compensate: lane = one column of 4 elements.
 // -------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kBlock)
+template <int COLS>
+__global__ void __launch_bounds__(kSyncBlock)
 decode_compensate_kernel(const uint32_t *__restrict__ bits32, const float *__restrict__ g,
                          const float *c, float *__restrict__ update, float *c_out, uint64_t d,
                          uint32_t scale_bits, float *__restrict__ x_model)
 {
     const uint64_t n_cols = (d + 3) >> 2;
-    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    if (col >= n_cols)
-        return;
-    const uint64_t e = col << 2;
-    const bool full = e + 4 <= d;
-    const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
-    const bool vec = full;
-
-    const uint32_t nib = (bits32[col >> 3] >> ((static_cast<uint32_t>(col) & 7u) * 4u)) & 0xFu;
+    const uint64_t col0 = static_cast<uint64_t>(blockIdx.x) * (kSyncBlock * COLS) + threadIdx.x;
     const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-    const f32x4 sv = load4(g + e, vec, n_valid) + ((c != nullptr) ? load4(c + e, vec, n_valid) : zero);
-    f32x4 upd;
+
+    f32x4 gv[COLS], cv[COLS], xv[COLS];
+    uint32_t bv[COLS];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-        upd[j] = __uint_as_float(scale_bits ^ (((nib >> j) & 1u) ? 0u : 0x80000000u));
-    if (update != nullptr)
-        store4<MARSIT_STREAMING_STORES>(update + e, upd, vec, n_valid);
-    if (x_model != nullptr) {
-        // Algorithm 2, model update in the same pass
-        const f32x4 xv = load4(x_model + e, vec, n_valid);
-        store4<MARSIT_STREAMING_STORES>(x_model + e, xv - upd, vec, n_valid);
+    for (int k = 0; k < COLS; ++k) {
+        const uint64_t col = col0 + static_cast<uint64_t>(k) * kSyncBlock;
+        gv[k] = zero;
+        cv[k] = zero;
+        xv[k] = zero;
+        bv[k] = 0;
+        if (col < n_cols) {
+            const uint64_t e = col << 2;
+            const bool full = e + 4 <= d;
+            const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+            gv[k] = load4(g + e, full, n_valid);
+            if (c != nullptr)
+                cv[k] = load4(c + e, full, n_valid);
+            if (x_model != nullptr)
+                xv[k] = load4(x_model + e, full, n_valid);
+            bv[k] = bits32[col >> 3];
+        }
     }
-    store4<MARSIT_STREAMING_STORES>(c_out + e, sv - upd, vec, n_valid);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < COLS; ++k) {
+        const uint64_t col = col0 + static_cast<uint64_t>(k) * kSyncBlock;
+        if (col < n_cols) {
+            const uint64_t e = col << 2;
+            const bool full = e + 4 <= d;
+            const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+            const uint32_t nib = (bv[k] >> ((static_cast<uint32_t>(col) & 7u) * 4u)) & 0xFu;
+            const f32x4 sv = gv[k] + cv[k];
+            f32x4 upd;
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                upd[j] = __uint_as_float(scale_bits ^ (((nib >> j) & 1u) ? 0u : 0x80000000u));
+            if (update != nullptr)
+                store4<MARSIT_STREAMING_STORES>(update + e, upd, full, n_valid);
+            if (x_model != nullptr)      // Algorithm 2, model update in the same pass
+                store4<MARSIT_STREAMING_STORES>(x_model + e, xv[k] - upd, full, n_valid);
+            store4<MARSIT_STREAMING_STORES>(c_out + e, sv - upd, full, n_valid);
+        }
+    }
 }
 
-__global__ void __launch_bounds__(kBlock)
+template <int COLS>
+__global__ void __launch_bounds__(kSyncBlock)
 apply_update_kernel(float *__restrict__ x, const float *__restrict__ update, uint64_t d)
 {
     const uint64_t n_cols = (d + 3) >> 2;
-    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    if (col >= n_cols)
-        return;
-    const uint64_t e = col << 2;
-    const bool full = e + 4 <= d;
-    const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
-    const bool vec = full;
-    const f32x4 xv = load4<false>(x + e, vec, n_valid);
-    const f32x4 uv = load4<true>(update + e, vec, n_valid);
-    store4<false>(x + e, xv - uv, vec, n_valid);
+    const uint64_t col0 = static_cast<uint64_t>(blockIdx.x) * (kSyncBlock * COLS) + threadIdx.x;
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    f32x4 xv[COLS], uv[COLS];
+#pragma unroll
+    for (int k = 0; k < COLS; ++k) {
+        const uint64_t col = col0 + static_cast<uint64_t>(k) * kSyncBlock;
+        xv[k] = zero;
+        uv[k] = zero;
+        if (col < n_cols) {
+            const uint64_t e = col << 2;
+            const bool full = e + 4 <= d;
+            const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+            xv[k] = load4<true>(x + e, full, n_valid);
+            uv[k] = load4<true>(update + e, full, n_valid);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < COLS; ++k) {
+        const uint64_t col = col0 + static_cast<uint64_t>(k) * kSyncBlock;
+        if (col < n_cols) {
+            const uint64_t e = col << 2;
+            const bool full = e + 4 <= d;
+            const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+            store4<MARSIT_STREAMING_STORES>(x + e, xv[k] - uv[k], full, n_valid);
+        }
+    }
 }
 
 // Local heavy-ball momentum for all workers in one launch (blockIdx.y = worker):
 // buf <- beta * buf + grad; g <- eta_l * buf.  Three separately rounded fp32 operations (the library
-// is built without contraction).  g may be the same array as grad: a lane reads its four elements
+// is built without contraction).  g may be the same array as grad: a lane reads its elements
 // before it writes them.
-__global__ void __launch_bounds__(kBlock)
+template <int COLS>
+__global__ void __launch_bounds__(kSyncBlock)
 local_momentum_kernel(float *__restrict__ buf, const float *grad, float *g_out, uint64_t d,
                       uint64_t ld, float beta, float eta_l)
 {
     const uint64_t n_cols = (d + 3) >> 2;
-    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kBlock + threadIdx.x;
-    if (col >= n_cols)
-        return;
-    const uint64_t e = col << 2;
-    const size_t at = static_cast<size_t>(blockIdx.y) * ld + e;
-    const bool full = e + 4 <= d;
-    const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
-    const bool vec = full;
-    const f32x4 bv = load4<true>(buf + at, vec, n_valid);
-    const f32x4 gv = load4<true>(grad + at, vec, n_valid);
-    const f32x4 carried = bv * beta;
-    const f32x4 v = carried + gv;
-    store4<true>(buf + at, v, vec, n_valid);
-    store4<true>(g_out + at, v * eta_l, vec, n_valid);
+    const uint64_t col0 = static_cast<uint64_t>(blockIdx.x) * (kSyncBlock * COLS) + threadIdx.x;
+    const size_t row = static_cast<size_t>(blockIdx.y) * ld;
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    f32x4 bv[COLS], gv[COLS];
+#pragma unroll
+    for (int k = 0; k < COLS; ++k) {
+        const uint64_t col = col0 + static_cast<uint64_t>(k) * kSyncBlock;
+        bv[k] = zero;
+        gv[k] = zero;
+        if (col < n_cols) {
+            const uint64_t e = col << 2;
+            const bool full = e + 4 <= d;
+            const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+            bv[k] = load4<true>(buf + row + e, full, n_valid);
+            gv[k] = load4<true>(grad + row + e, full, n_valid);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < COLS; ++k) {
+        const uint64_t col = col0 + static_cast<uint64_t>(k) * kSyncBlock;
+        if (col < n_cols) {
+            const uint64_t e = col << 2;
+            const bool full = e + 4 <= d;
+            const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+            const f32x4 carried = bv[k] * beta;
+            const f32x4 v = carried + gv[k];
+            store4<true>(buf + row + e, v, full, n_valid);
+            store4<true>(g_out + row + e, v * eta_l, full, n_valid);
+        }
+    }
 }
 
 }   // namespace marsit
@@ -360,10 +425,11 @@ int marsit_compress(const float *g, const float *c, uint64_t *bits_out, uint64_t
         return MARSIT_EALIGN;
     if (d == 0)
         return MARSIT_OK;
+    // the sign step alone is the sign-and-merge kernel with fold count 1: nothing received, no draw
     const uint64_t n_words = (d + 63) / 64;
-    const uint64_t n_waves = (n_words + kWordsPerWave - 1) / kWordsPerWave;
-    hipLaunchKernelGGL(compress_kernel, dim3(blocks_for(n_waves * 64)), dim3(kBlock), 0,
-                       static_cast<hipStream_t>(stream), g, c, bits_out, d, n_words);
+    hipLaunchKernelGGL(compress_hop_merge_kernel<kCompressCols>, dim3(stream_blocks(n_words * 16, kCompressCols)),
+                       dim3(kSyncBlock), 0, static_cast<hipStream_t>(stream), static_cast<const uint32_t *>(nullptr),
+                       g, c, reinterpret_cast<uint32_t *>(bits_out), 0, d, 0xFFFFFFFFu, true, 0u, 0u, 0u);
     return finish_launch();
 }
 
@@ -403,7 +469,7 @@ int marsit_compress_hop_merge(const uint64_t *recv, const float *g, const float 
     const bool always_local = (fold == 1);
     const uint32_t threshold = always_local ? 0xFFFFFFFFu : keep_threshold(fold);
     const uint64_t n_words = (n + 63) / 64;
-    hipLaunchKernelGGL(compress_hop_merge_kernel, dim3(blocks_for(n_words * 16)), dim3(kBlock), 0,
+    hipLaunchKernelGGL(compress_hop_merge_kernel<kCompressCols>, dim3(stream_blocks(n_words * 16, kCompressCols)), dim3(kSyncBlock), 0,
                        static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(recv), g, c,
                        reinterpret_cast<uint32_t *>(out), word_begin, n, threshold, always_local, hop_id,
                        static_cast<uint32_t>(seed), static_cast<uint32_t>(seed >> 32));
@@ -462,7 +528,7 @@ static int decode_impl(const uint64_t *bits, const float *g, const float *c, flo
         return MARSIT_EALIGN;
     if (d == 0)
         return MARSIT_OK;
-    hipLaunchKernelGGL(decode_compensate_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock), 0,
+    hipLaunchKernelGGL(decode_compensate_kernel<kStreamCols>, dim3(stream_blocks((d + 3) >> 2, kStreamCols)), dim3(kSyncBlock), 0,
                        static_cast<hipStream_t>(stream), reinterpret_cast<const uint32_t *>(bits), g,
                        c, update_out, c_out, d, float_bits_host(scale), x_model);
     return finish_launch();
@@ -706,7 +772,7 @@ int marsit_apply_update(float *x, const float *update, uint64_t d, void *stream)
         return MARSIT_EALIGN;
     if (d == 0)
         return MARSIT_OK;
-    hipLaunchKernelGGL(apply_update_kernel, dim3(blocks_for((d + 3) >> 2)), dim3(kBlock), 0,
+    hipLaunchKernelGGL(apply_update_kernel<kStreamCols>, dim3(stream_blocks((d + 3) >> 2, kStreamCols)), dim3(kSyncBlock), 0,
                        static_cast<hipStream_t>(stream), x, update, d);
     return finish_launch();
 }
@@ -722,7 +788,8 @@ int marsit_local_momentum(float *buf, const float *grad, float *g_out, uint32_t 
         return MARSIT_EALIGN;
     if (d == 0)
         return MARSIT_OK;
-    hipLaunchKernelGGL(local_momentum_kernel, dim3(blocks_for((d + 3) >> 2), M), dim3(kBlock), 0,
+    hipLaunchKernelGGL(local_momentum_kernel<kStreamCols>, dim3(stream_blocks((d + 3) >> 2, kStreamCols), M), dim3(kSyncBlock),
+                       throttle_lds_bytes(16),
                        static_cast<hipStream_t>(stream), buf, grad, g_out, d, ld, beta, eta_l);
     return finish_launch();
 }
