@@ -318,3 +318,34 @@ def test_bench_refuses_more_than_one_gpu():
     assert proc.returncode != 0
     assert "ONE GPU" in proc.stderr and "--gpus must be 1" in proc.stderr
     assert proc.stdout.strip() == ""
+
+
+def test_bench_byte_model_and_traffic_lookup(tmp_path, monkeypatch):
+    """bench.py's algorithmic bytes are the stated per-element figures, and roofline.traffic is
+    taken from a counter summary only when that summary was made from this tree's kernel sources."""
+    import importlib
+    import sys
+    if ROOT not in sys.path:
+        sys.path.insert(0, ROOT)
+    bench = importlib.import_module("bench")
+    M, d = 8, 25_600_000
+    assert bench.algorithmic_bytes("ring_step_sim", M, d) == 12 * M * d + 4 * d + d // 8 == 2_563_200_000
+    assert bench.algorithmic_bytes("tree_step_sim", M, d) == 2_563_200_000
+    assert bench.algorithmic_bytes("full_sync", M, d) == 12 * M * d + 4 * d
+    assert bench.algorithmic_bytes("step_apply", M, d) == 12 * M * d + 8 * d + d // 8
+    assert bench.algorithmic_bytes("ring_step_sim", 3, 65) == 12 * 3 * 65 + 4 * 65 + 16     # ragged: 2 words
+
+    from paper_2204_06787_amd import build
+    digest = build.fused_sources_digest()
+    assert len(digest) == 16 and int(digest, 16) >= 0
+    prof = tmp_path / "profiles"
+    prof.mkdir()
+    monkeypatch.setattr(bench, "ROOT", str(tmp_path))
+    key = "entry=ring_step_sim M=8 d=25600000 grid_x=0 ld_pad=0"
+    assert bench.measured_traffic(key)[0] is None                                   # nothing there
+    (prof / "a.txt").write_text(f"x\nkey: {key}\ntraffic_bytes_per_launch: 123456\nfused_sources_sha16: {digest}\n")
+    assert bench.measured_traffic(key) == (123456, os.path.join("profiles", "a.txt"))
+    assert bench.measured_traffic(key.replace("M=8", "M=9"))[0] is None             # another shape
+    (prof / "a.txt").write_text(f"key: {key}\ntraffic_bytes_per_launch: 123456\nfused_sources_sha16: {'0' * 16}\n")
+    value, why = bench.measured_traffic(key)
+    assert value is None and "other kernel sources" in why                          # stale summary
