@@ -204,11 +204,6 @@ struct SweepShape {
     uint32_t top_level;   // tree: ceil(log2 M)
 };
 
-__device__ __forceinline__ uint32_t pick4(const uint32_t v[4], uint32_t j)
-{
-    return (j == 0) ? v[0] : (j == 1) ? v[1] : (j == 2) ? v[2] : v[3];
-}
-
 // Ring or torus whose rows are all X long: worker picked by each of the lane's four bits.
 // Column chain first (which row result survives, per bit), then the chain of that row.  With up
 // to four rows every row's chain is evaluated once and serves all four bits (Y*(X-1) calls);
