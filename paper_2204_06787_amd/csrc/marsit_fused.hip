@@ -682,12 +682,18 @@ tree_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
 // Full-precision round (Algorithm 1, branch mod(t,K) == 0) for M simulated workers.
 // -------------------------------------------------------------------------------------------------
 // Any worker count, any alignment, ragged tails: one-wavefront workgroups, the workers taken
-// kSweepBatch at a time with the batch's loads issued back to back.
+// kSweepBatch at a time with the batch's loads issued back to back.  TWO_IN_FLIGHT (more than 24
+// workers): the next batch is requested before the current one is consumed, at two wavefronts per
+// CU (measured: M = 32: 73 % against 70 % of the HBM peak, M = 64: 68-69 % against 66 %; up to 24
+// workers the single-batch form with three or four wavefronts is the faster one: M = 9: 79 %
+// against 72 %, M = 24: 74 % against 73 %).
+template <bool TWO_IN_FLIGHT>
 __global__ void __launch_bounds__(kSyncBlock)
 full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
                  uint32_t M, uint64_t d, uint64_t ld, uint64_t col_begin,
                  float *__restrict__ x_model)
 {
+    constexpr int B = kSweepBatch;
     const uint64_t n_cols = (d + 3) >> 2;
     const uint64_t col = col_begin + static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
     if (col >= n_cols)
@@ -704,20 +710,19 @@ full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
     f32x4 xv = zero;
     if (x_model != nullptr)
         xv = load4(x_model + e, vec, n_valid);
-#pragma unroll 1
-    for (uint32_t m0 = 0; m0 < M; m0 += kSweepBatch) {
-        f32x4 gv[kSweepBatch], cv[kSweepBatch];
+    auto fetch = [&](f32x4 *gv, f32x4 *cv, uint32_t m0) {
 #pragma unroll
-        for (int i = 0; i < kSweepBatch; ++i) {
+        for (int i = 0; i < B; ++i) {
             if (m0 + i < M) {
                 const size_t off = static_cast<size_t>(m0 + i) * ld + e;
                 gv[i] = load4(g + off, vec, n_valid);
                 cv[i] = load4(c + off, vec, n_valid);
             }
         }
-        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto consume = [&](const f32x4 *gv, const f32x4 *cv, uint32_t m0) {
 #pragma unroll
-        for (int i = 0; i < kSweepBatch; ++i) {
+        for (int i = 0; i < B; ++i) {
             if (m0 + i < M) {
                 const f32x4 sv = gv[i] + cv[i];
 #pragma unroll
@@ -726,7 +731,33 @@ full_sync_kernel(const float *__restrict__ g, float *__restrict__ c, float *__re
                 store4<MARSIT_STREAMING_STORES>(c + static_cast<size_t>(m0 + i) * ld + e, zero, vec, n_valid);
             }
         }
-        __builtin_amdgcn_sched_barrier(0);
+    };
+    f32x4 ga[B], ca[B];
+    if (TWO_IN_FLIGHT) {
+        f32x4 gb[B], cb[B];
+        fetch(ga, ca, 0);
+#pragma unroll 1
+        for (uint32_t m0 = 0; m0 < M; m0 += 2 * B) {
+            if (m0 + B < M)
+                fetch(gb, cb, m0 + B);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(ga, ca, m0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (m0 + 2 * B < M)
+                fetch(ga, ca, m0 + 2 * B);
+            __builtin_amdgcn_sched_barrier(0);
+            if (m0 + B < M)
+                consume(gb, cb, m0 + B);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+#pragma unroll 1
+        for (uint32_t m0 = 0; m0 < M; m0 += B) {
+            fetch(ga, ca, m0);
+            __builtin_amdgcn_sched_barrier(0);
+            consume(ga, ca, m0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
     const double dm = static_cast<double>(M);
     f32x4 mean;
@@ -813,8 +844,9 @@ inline uint32_t fused_waves_per_cu(uint32_t X, uint32_t Y)
 // batch per worker count): M = 5: 14 wavefronts, batch 4 (70 %); 7: 10, 4 (75 %); 9, 10: 8, 4
 // (74-75 %); 11-18: 5, 8 (73-75 %; short last row: 7); 24, 32: 4, 8 (73 %, 72 %); 40: 69 %; 41, 48: batch 16 (66 %,
 // 68 %); ring of 64 staged: 52 %, gather-and-sweep: 63 %.  A plain streaming kernel with the same
-// 2M read and M + 1 write streams (the full-precision round) reaches 80 % at M = 9, 74 % at 24,
-// 70 % at 32 and 66 % at 64: the fall with M is the memory system's, not these kernels'.
+// 2M read and M + 1 write streams (the full-precision round) reaches 80 % at M = 9, 75 % at 24,
+// 73 % at 32 and 69 % at 64: the fall with M is the memory system's, not these kernels'.  Keeping
+// two batches of loads in flight, which helps that streaming kernel, does nothing here (measured).
 constexpr uint32_t kMaxStagedWorkers = 48;
 
 inline uint32_t staged_batch(uint32_t M)
@@ -840,13 +872,6 @@ inline uint32_t staged_lds_bytes(uint32_t M, int sched)
 }
 
 constexpr uint32_t kSweepWavesPerCu = 8;   // gather-and-sweep kernel; 6 to 16 measure the same
-
-// Any-M kernel of the full-precision round: 4 one-wavefront workgroups per CU up to 16 workers,
-// 3 above (measured: M = 9: 79 %, 24: 74 %, 32: 70 %, 64: 66 % of the HBM peak).
-inline uint32_t full_sync_waves_per_cu(uint32_t M)
-{
-    return M <= 16 ? 4u : 3u;
-}
 
 inline ThresholdTable keep_thresholds()
 {
@@ -1124,9 +1149,12 @@ static int full_sync_impl(const float *g, float *c, float *update_out, float *x_
     const uint64_t n_cols = (d + 3) >> 2;
     if (col_begin < n_cols) {
         const uint32_t blocks = static_cast<uint32_t>((n_cols - col_begin + kSyncBlock - 1) / kSyncBlock);
-        hipLaunchKernelGGL(full_sync_kernel, dim3(blocks), dim3(kSyncBlock),
-                           throttle_lds_bytes(full_sync_waves_per_cu(M)), s, g, c, update_out, M, d, ld, col_begin,
-                           x_model);
+        if (M > 24)
+            hipLaunchKernelGGL(full_sync_kernel<true>, dim3(blocks), dim3(kSyncBlock), throttle_lds_bytes(2), s, g, c,
+                               update_out, M, d, ld, col_begin, x_model);
+        else
+            hipLaunchKernelGGL(full_sync_kernel<false>, dim3(blocks), dim3(kSyncBlock),
+                               throttle_lds_bytes(M <= 16 ? 4 : 3), s, g, c, update_out, M, d, ld, col_begin, x_model);
         return finish_launch();
     }
     return MARSIT_OK;

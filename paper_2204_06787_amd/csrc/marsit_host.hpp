@@ -58,8 +58,8 @@ inline uint32_t float_bits_host(float x)
 inline uint32_t throttle_lds_bytes(uint32_t waves)
 {
     constexpr uint32_t lds_per_cu = 160u * 1024u;   // gfx950; the runtime attribute reports 64 KB
-    // a few per cent below an even share: with an exact share one workgroup fewer fits.  At least
-    // 3 workgroups per CU keeps the request under the 64 KB a launch may ask for without opting in.
+    // a few per cent below an even share: with an exact share one workgroup fewer fits.  (gfx950
+    // takes dynamic requests up to the whole 160 KB; two workgroups per CU ask for 77.5 KB.)
     return ((lds_per_cu / waves) * 31u / 32u) & ~511u;
 }
 
