@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--d", type=int, default=0, help="override the workload's elements per gradient")
     ap.add_argument("--grid-x", type=int, default=-1, help="override the workload's torus columns (0: ring)")
     ap.add_argument("--ld-pad", type=int, default=0, help="row stride = d + this many elements")
+    ap.add_argument("--fused-waves", type=int, default=0,
+                    help="force this many one-wavefront workgroups per CU for the compiled fused kernels "
+                         "(tuning hook marsit_set_fused_waves_per_cu; 0: the library's choice)")
     ap.add_argument("--seed", type=int, default=2022)
     ap.add_argument("--pool", type=int, default=10,
                     help="distinct gradient sets kept in HBM and cycled through (0: one per step)")
@@ -141,6 +144,8 @@ def main():
         sys.exit(1)
     marsit.load_library()          # raises if the HIP library has not been built
     torch.cuda.set_device(0)
+    if args.fused_waves:
+        marsit.marsit_set_fused_waves_per_cu(args.fused_waves)
     wl = workloads.WORKLOADS[args.workload]
     custom = {}
     if args.M > 0:
@@ -155,7 +160,7 @@ def main():
     if entry == "tree_step_sim" and wl.grid_x:
         wl = dataclasses.replace(wl, grid_x=0)
     M, d, ld = wl.M, wl.d, wl.d + args.ld_pad
-    headline = entry == "ring_step_sim" and not custom and args.ld_pad == 0
+    headline = entry == "ring_step_sim" and not custom and args.ld_pad == 0 and not args.fused_waves
     K, Wm = args.steps, args.warmup
     total = K + Wm
     pool = args.pool if args.pool > 0 else total
@@ -210,7 +215,8 @@ def main():
     achieved = nbytes / (avg_kernel_ms * 1e-3) / 1e9
     schedule = "tree" if entry == "tree_step_sim" else ("ring" if not wl.grid_x or wl.grid_x == M else
                                                         f"torus {wl.grid_x} columns x {-(-M // wl.grid_x)} rows")
-    key = f"entry={entry} M={M} d={d} grid_x={wl.grid_x} ld_pad={args.ld_pad}"
+    key = f"entry={entry} M={M} d={d} grid_x={wl.grid_x} ld_pad={args.ld_pad}" + (
+        f" fused_waves={args.fused_waves}" if args.fused_waves else "")
     traffic, traffic_source = measured_traffic(key)
 
     out = {
@@ -221,7 +227,8 @@ def main():
         "config": {"workload": f"{wl.name}: M={M} simulated workers, d={d} fp32, {schedule}, "
                                f"{wl.dist} gradients, compensation carried over steps, one seed per step",
                    "entry_point": "marsit_" + entry, "M": M, "d": d, "ld": ld, "grid_x": wl.grid_x,
-                   "scale": wl.scale, "gradient_sets_in_hbm": pool},
+                   "scale": wl.scale, "gradient_sets_in_hbm": pool,
+                   **({"fused_waves_per_cu": args.fused_waves} if args.fused_waves else {})},
         "worker_elements_per_s": M * d / (ms_per_step * 1e-3),
         "elements_per_s": d / (ms_per_step * 1e-3),
         "algorithmic_bytes_per_step": nbytes,

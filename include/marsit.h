@@ -176,6 +176,16 @@ int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *
                          uint32_t grid_x, void *stream);
 
 /*
+ * Tuning hook, host-side, process-wide.  The compiled kernels of marsit_ring_step_sim (and of the
+ * entry points built on them) limit how many of their one-wavefront workgroups share a compute unit
+ * -- about 21 / M, never fewer than 3 -- because HBM delivers most when the window of addresses in
+ * flight is compact.  waves = 2..32 forces that count for every compiled ring and torus schedule,
+ * 0 restores the built-in choice; anything else is MARSIT_EINVAL.  Results do not depend on it.
+ * bench.py --fused-waves uses it to reproduce the occupancy sweep behind the built-in choice.
+ */
+int marsit_set_fused_waves_per_cu(uint32_t waves);
+
+/*
  * Other multi-hop schedules (Section 5 names tree all-reduce and others as easy extensions, without
  * detail).  Reading taken: when the two operands of a merge stand for different numbers of workers,
  * Eq. 2 is used with the local share in place of 1/m, i.e. the local sign is kept with probability

@@ -14,6 +14,8 @@
 #include "marsit_device.hpp"
 #include "marsit_host.hpp"
 
+#include <atomic>
+
 namespace marsit {
 
 // Bounds of the M parts of the packed words (word indices), passed by value in the kernel
@@ -824,8 +826,14 @@ full_sync_fast_kernel(const float *__restrict__ g, float *__restrict__ c,
 // tori 2x2: 5, 3x2 and 2x3: 4, 4x2, 3x3, 4x4: 3 -- about 21/M, i.e. 40-50 KB of loads in flight
 // per CU, never fewer than 3.  The 2x4 torus keeps only two rows of two workers in flight and
 // takes one more (4: 79 % of HBM peak, 3: 73.5 %).
+// Tuning hook (marsit_set_fused_waves_per_cu): 0 = the table above.
+static std::atomic<uint32_t> fused_waves_override{0};
+
 inline uint32_t fused_waves_per_cu(uint32_t X, uint32_t Y)
 {
+    const uint32_t forced = fused_waves_override.load(std::memory_order_relaxed);
+    if (forced != 0)
+        return forced;
     const uint32_t M = X * Y;
     uint32_t waves = (21u + M / 2u) / M;
     if (waves < 3u)
@@ -1161,6 +1169,14 @@ static int full_sync_impl(const float *g, float *c, float *update_out, float *x_
 }
 
 extern "C" {
+
+int marsit_set_fused_waves_per_cu(uint32_t waves)
+{
+    if (waves != 0 && (waves < 2 || waves > 32))
+        return MARSIT_EINVAL;
+    fused_waves_override.store(waves, std::memory_order_relaxed);
+    return MARSIT_OK;
+}
 
 int marsit_ring_step_sim(const float *g, float *c, float *update_out, uint64_t *bits_out,
                          uint32_t M, uint64_t d, uint64_t ld, float scale, uint64_t seed,

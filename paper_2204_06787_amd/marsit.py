@@ -34,7 +34,7 @@ EXPORTS = (
     "marsit_ragged_torus_step_sim", "marsit_ragged_torus_step_apply",
     "marsit_ssdm_cascade_hop", "marsit_cascade_ring_step_sim",
     "marsit_hop_merge_device_seed", "marsit_set_device_seed",
-    "marsit_exchange_step_sim_static", "marsit_grid_work_items", "marsit_round",
+    "marsit_exchange_step_sim_static", "marsit_grid_work_items", "marsit_round", "marsit_set_fused_waves_per_cu",
 )
 
 _lib = None
@@ -137,6 +137,8 @@ def load_library(path: str | None = None):
     lib.marsit_ragged_torus_step_apply.restype = ci
     lib.marsit_step_apply.argtypes = [u64, u64, vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, u32, vp]
     lib.marsit_step_apply.restype = ci
+    lib.marsit_set_fused_waves_per_cu.argtypes = [u32]
+    lib.marsit_set_fused_waves_per_cu.restype = ci
     lib.marsit_round.argtypes = [u64, u64, ci, u32, vp, vp, vp, vp, vp, u32, u64, u64, f32, u64, vp]
     lib.marsit_round.restype = ci
     lib.marsit_apply_update.argtypes = [vp, vp, u64, vp]
@@ -315,6 +317,11 @@ def marsit_ring_step_sim(g, c, update_out, bits_out, scale: float, seed: int, gr
         _bits_ptr(bits_out, "bits_out", True, need=n_words(d)), M, d, ld, scale, seed & 0xFFFFFFFFFFFFFFFF, grid_x,
         _stream(stream)))
     return update_out, bits_out
+
+
+def marsit_set_fused_waves_per_cu(waves: int):
+    """Tuning hook: wavefronts per CU of the compiled fused kernels (0: built-in choice)."""
+    _check("marsit_set_fused_waves_per_cu", load_library().marsit_set_fused_waves_per_cu(waves))
 
 
 def marsit_chain_workspace_words(M: int, d: int, grid_x: int = 0) -> int:

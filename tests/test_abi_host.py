@@ -153,6 +153,14 @@ def test_size_limit_is_what_one_launch_can_cover(lib):
         assert lib.marsit_pipeline_workspace_words(1, d, 0) == 0
 
 
+def test_fused_waves_hook_validation(lib):
+    assert lib.marsit_set_fused_waves_per_cu(1) == marsit.EINVAL
+    assert lib.marsit_set_fused_waves_per_cu(33) == marsit.EINVAL
+    assert lib.marsit_set_fused_waves_per_cu(2) == marsit.OK
+    assert lib.marsit_set_fused_waves_per_cu(32) == marsit.OK
+    assert lib.marsit_set_fused_waves_per_cu(0) == marsit.OK          # back to the built-in choice
+
+
 def test_other_entry_points_argument_validation(lib):
     assert lib.marsit_compress(None, None, FAKE, 64, None) == marsit.EINVAL
     assert lib.marsit_compress(FAKE, None, None, 64, None) == marsit.EINVAL

@@ -250,6 +250,17 @@ def test_fused_generic_schedule(M, grid_x, d):
     _check_fused(M, d, grid_x=grid_x, seed=0x3000 + M)
 
 
+@pytest.mark.parametrize("M,grid_x", [(8, 0), (16, 4), (3, 0)])
+def test_fused_results_do_not_depend_on_the_occupancy_hook(M, grid_x):
+    """marsit_set_fused_waves_per_cu only changes how many workgroups share a CU."""
+    try:
+        for waves in (2, 3, 5, 8, 32):
+            marsit.marsit_set_fused_waves_per_cu(waves)
+            _check_fused(M, 64 * 300 + 9, grid_x=grid_x, seed=0x7000 + M)
+    finally:
+        marsit.marsit_set_fused_waves_per_cu(0)
+
+
 @pytest.mark.parametrize("M,grid_x", [(3, 0), (8, 0), (16, 4), (9, 3)])
 @pytest.mark.parametrize("d,ld", [(1000, 1001), (4099, 4102), (64, 67), (20_000, 20_004)])
 def test_fused_row_stride_and_misaligned_base(M, grid_x, d, ld):
