@@ -50,6 +50,10 @@ def parse_args():
     ap.add_argument("--fused-waves", type=int, default=0,
                     help="force this many one-wavefront workgroups per CU for the compiled fused kernels "
                          "(tuning hook marsit_set_fused_waves_per_cu; 0: the library's choice)")
+    ap.add_argument("--per-launch-events", action="store_true",
+                    help="record a HIP event after every timed step (per-launch min / median / max in the JSON) "
+                         "instead of only before the first and after the last one; the extra records cost "
+                         "1-2 % of the step time, so they are off by default")
     ap.add_argument("--seed", type=int, default=2022)
     ap.add_argument("--pool", type=int, default=10,
                     help="distinct gradient sets kept in HBM and cycled through (0: one per step)")
@@ -198,17 +202,21 @@ def main():
         step(t)
     torch.cuda.synchronize()
 
-    events = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+    # HIP events on the stream the kernels are launched on: one before the first timed step and one
+    # after the last (or one after every step with --per-launch-events)
+    every = 1 if args.per_launch_events else K
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(K // every + 1)]
     t0 = time.perf_counter()
     events[0].record(stream)
     for i in range(K):
         step(Wm + i)
-        events[i + 1].record(stream)
+        if (i + 1) % every == 0:
+            events[(i + 1) // every].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
-    per_launch_ms = [events[i].elapsed_time(events[i + 1]) for i in range(K)]
-    avg_kernel_ms = sum(per_launch_ms) / K
+    per_launch_ms = [events[i].elapsed_time(events[i + 1]) / every for i in range(K // every)]
+    avg_kernel_ms = sum(per_launch_ms) / len(per_launch_ms)
     ms_per_step = wall * 1e3 / K
     nbytes = algorithmic_bytes(entry, M, d)
     value = nbytes / (ms_per_step * 1e-3) / 1e9
@@ -236,10 +244,12 @@ def main():
                      "frac": achieved / HBM_PEAK_GBPS,
                      "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": "sync_step_kernel" if headline else f"the kernel marsit_{entry} launches for this shape",
-                     "avg_launch_ms": avg_kernel_ms,
-                     "median_launch_ms": sorted(per_launch_ms)[K // 2],
-                     "min_launch_ms": min(per_launch_ms), "max_launch_ms": max(per_launch_ms)},
+                     "avg_launch_ms": avg_kernel_ms, "launches_timed": K,
+                     "events": "one per launch" if args.per_launch_events else "first and last"},
     }
+    if args.per_launch_events:
+        out["roofline"].update(median_launch_ms=sorted(per_launch_ms)[K // 2], min_launch_ms=min(per_launch_ms),
+                               max_launch_ms=max(per_launch_ms))
 
     if not args.no_unfused and entry == "ring_step_sim":
         # what the fusion buys: the same pass hop by hop (M compress, M(M-1) hop merges, M decodes)
