@@ -14,9 +14,10 @@
  *     first); bit 1 means +1, i.e. the IEEE sign bit is clear (+0 -> +1, -0 -> -1); bits at
  *     positions >= d of the last word are written as 0.  Bitmap pointers must be 8-byte aligned,
  *     fp32 pointers 4-byte aligned (MARSIT_EALIGN otherwise).  That is all the 128-bit accesses of
- *     the kernels need; rows that start on 16-byte boundaries (16-byte aligned bases, row stride a
- *     multiple of 4) are faster because no access straddles a cache line (about 80 % against
- *     65-70 % of the HBM peak for the fused pass).
+ *     the kernels need; but rows that start on 128-byte boundaries (128-byte aligned bases, row
+ *     stride ld a multiple of 32 elements) are faster, because a wavefront's 1 KB access then
+ *     covers 8 whole cache lines instead of straddling 9 (78-80 % against 70-74 % of the HBM peak
+ *     for the fused pass): a caller that owns the layout should pad ld to a multiple of 32.
  *   - Random merge masks: counter-based Philox4x32-10.  The 32-bit word that decides bit j of
  *     packed word w at hop id h is output (j mod 4) of Philox with key = (seed low, seed high) and
  *     counter = (j / 4, h, w low, w high).  With fold count m the local sign is taken where that

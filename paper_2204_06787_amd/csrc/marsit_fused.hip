@@ -22,6 +22,7 @@ namespace marsit {
 // arguments so that a compile-time index becomes a scalar load.
 struct PartTable {
     uint32_t bound[MARSIT_MAX_WORKERS + 1];
+    uint32_t xcd_group;     // compiled schedules, rows off the 128-byte lines: tiles per XCD run
 };
 
 // Keep thresholds floor(2^32 / fold) for the kernels whose fold counts are run-time values.
@@ -49,14 +50,29 @@ struct ThresholdTable {
 //
 // APPLY: the model update of Algorithm 2 in the same pass, x <- x - update (x is one more read and
 // one more write stream); `update` may then be NULL.  Without APPLY the kernel never looks at x.
-template <int X, int Y, bool APPLY>
+template <int X, int Y, bool APPLY, bool GROUPED>
 __global__ void __launch_bounds__(kSyncBlock)
 sync_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__restrict__ update,
                  uint32_t *__restrict__ bits32, uint64_t n_cols, uint64_t ld, uint32_t scale_bits,
                  uint32_t key0, uint32_t key1, PartTable parts, float *__restrict__ x_model)
 {
     constexpr int M = X * Y;
-    const uint64_t col = static_cast<uint64_t>(blockIdx.x) * kSyncBlock + threadIdx.x;
+    // Consecutive workgroup ids go to consecutive XCDs, each with its own L2.  When the rows do not
+    // start on 128-byte lines a tile shares its first and last line with its neighbours; GROUPED
+    // gives each XCD runs of parts.xcd_group consecutive tiles, so that the second request for such
+    // a line hits that L2.  (A separate instantiation: the plain one is sensitive to every
+    // instruction added before its loads.)
+    uint32_t tile = blockIdx.x;
+    if (GROUPED) {
+        const uint32_t xcd_group = parts.xcd_group;
+        const uint32_t span = 8u * xcd_group;
+        const uint32_t full = (gridDim.x / span) * span;
+        if (tile < full) {
+            const uint32_t xcd = tile % 8u, j = tile / 8u;
+            tile = ((j / xcd_group) * 8u + xcd) * xcd_group + (j % xcd_group);
+        }
+    }
+    const uint64_t col = static_cast<uint64_t>(tile) * kSyncBlock + threadIdx.x;
     const uint32_t w = static_cast<uint32_t>(col >> 4);
     const uint32_t q = static_cast<uint32_t>(col) & 15u;
     uint32_t nib = 0;
@@ -944,12 +960,28 @@ void launch_sync_step(const float *g, float *c, float *update, uint32_t *bits32,
 {
     const uint32_t lds = throttle_lds_bytes(fused_waves_per_cu(X, Y));
     const uint32_t blocks = static_cast<uint32_t>((n_cols + kSyncBlock - 1) / kSyncBlock);
+    // rows on 128-byte lines: plain round-robin of tiles over the XCDs is best (M = 8: 80 % of the
+    // HBM peak against 77 % with runs of 8); otherwise runs of 8 tiles per XCD up to 8 workers, of 2
+    // above (M = 8, ld = d + 1: 71 % against 67 %; ld = d + 8: 72.5 % against 69.5 %; M = 16,
+    // ld = d + 8: 66-67 % against 63 %)
+    const bool on_lines = aligned_to(g, 128) && aligned_to(c, 128) && (ld % 32u) == 0;
+    if (on_lines) {
+        if (x_model == nullptr)
+            hipLaunchKernelGGL((sync_step_kernel<X, Y, false, false>), dim3(blocks), dim3(kSyncBlock), lds, stream,
+                               g, c, update, bits32, n_cols, ld, scale_bits, key0, key1, parts, x_model);
+        else
+            hipLaunchKernelGGL((sync_step_kernel<X, Y, true, false>), dim3(blocks), dim3(kSyncBlock), lds, stream,
+                               g, c, update, bits32, n_cols, ld, scale_bits, key0, key1, parts, x_model);
+        return;
+    }
+    PartTable grouped = parts;
+    grouped.xcd_group = (X * Y <= 8) ? 8u : 2u;
     if (x_model == nullptr)
-        hipLaunchKernelGGL((sync_step_kernel<X, Y, false>), dim3(blocks), dim3(kSyncBlock), lds, stream,
-                           g, c, update, bits32, n_cols, ld, scale_bits, key0, key1, parts, x_model);
+        hipLaunchKernelGGL((sync_step_kernel<X, Y, false, true>), dim3(blocks), dim3(kSyncBlock), lds, stream,
+                           g, c, update, bits32, n_cols, ld, scale_bits, key0, key1, grouped, x_model);
     else
-        hipLaunchKernelGGL((sync_step_kernel<X, Y, true>), dim3(blocks), dim3(kSyncBlock), lds, stream,
-                           g, c, update, bits32, n_cols, ld, scale_bits, key0, key1, parts, x_model);
+        hipLaunchKernelGGL((sync_step_kernel<X, Y, true, true>), dim3(blocks), dim3(kSyncBlock), lds, stream,
+                           g, c, update, bits32, n_cols, ld, scale_bits, key0, key1, grouped, x_model);
 }
 
 using SyncLauncher = void (*)(const float *, float *, float *, uint32_t *, uint64_t, uint64_t,
@@ -1065,6 +1097,7 @@ static int ring_step_impl(const float *g, float *c, float *update_out, uint64_t 
     uint64_t bounds[MARSIT_MAX_WORKERS + 1];
     split_bounds_host(n_words, M, grid_x, bounds);
     PartTable parts;
+    parts.xcd_group = 1;
     for (uint32_t k = 0; k <= MARSIT_MAX_WORKERS; ++k)
         parts.bound[k] = static_cast<uint32_t>(k <= M ? bounds[k] : n_words);
 
@@ -1122,6 +1155,7 @@ static int ragged_torus_impl(const float *g, float *c, float *update_out, uint64
     uint64_t row_bounds[MARSIT_MAX_WORKERS + 1];
     split_bounds_host(n_words, X, 0, row_bounds);          // the X row-parts (a ring split in X)
     PartTable parts;
+    parts.xcd_group = 1;
     for (uint32_t k = 0; k <= MARSIT_MAX_WORKERS; ++k)
         parts.bound[k] = static_cast<uint32_t>(k <= X ? row_bounds[k] : n_words);
     const uint32_t scale_bits = float_bits_host(scale);
@@ -1223,6 +1257,7 @@ static int tree_step_impl(const float *g, float *c, float *update_out, uint64_t 
             ++top_level;
         const SweepShape shape = {M, M, 1u, M, top_level};
         PartTable no_parts;
+        no_parts.xcd_group = 1;
         for (uint32_t k = 0; k <= MARSIT_MAX_WORKERS; ++k)
             no_parts.bound[k] = 0;                        // a tree folds whole vectors
         launch_sweep<kSweepTree>(g, c, update_out, bits32, d, ld, generic_col_begin, scale_bits, key0, key1,

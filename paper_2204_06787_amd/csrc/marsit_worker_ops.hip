@@ -384,7 +384,7 @@ using namespace marsit;
 
 extern "C" {
 
-int marsit_version(void) { return 100; }
+int marsit_version(void) { return 200; }
 
 int marsit_last_hip_error(void) { return tls_last_hip_error; }
 
