@@ -8,6 +8,8 @@
  *   - Pointers named g, c, x, update*, bits*, recv, local, out are DEVICE pointers owned by the
  *     caller.  The library never allocates, frees or synchronises; work is enqueued on `stream`
  *     (a hipStream_t passed as void*; NULL is the default stream) and the call returns at once.
+ *     Apart from the marsit_pipeline_* calls an entry point only launches kernels on `stream`, so
+ *     it may be recorded into a HIP graph; scalar arguments (seed, t, scale) are then fixed in it.
  *   - fp32 vectors are plain arrays of IEEE-754 binary32.  Arithmetic is fp32 with one
  *     round-to-nearest-even operation per step of Algorithm 1; denormals are kept.
  *   - Sign bitmaps: 64-bit words; element e sits in word e/64 at bit e%64 (least significant
