@@ -148,6 +148,14 @@ def main():
         sys.exit(1)
     marsit.load_library()          # raises if the HIP library has not been built
     torch.cuda.set_device(0)
+    # One 256-element call now, so that the runtime loads the library's code object for this device
+    # here and not at the first warm-up step: that load takes milliseconds, the GPU would sit idle
+    # between the input generation and the steps, and the device's clock transient after an idle
+    # period would then fall into the timed region of a short run.
+    probe = torch.zeros(256, dtype=torch.float32, device="cuda")
+    marsit.marsit_apply_update(probe, probe.clone())
+    torch.cuda.synchronize()
+    del probe
     if args.fused_waves:
         marsit.marsit_set_fused_waves_per_cu(args.fused_waves)
     wl = workloads.WORKLOADS[args.workload]

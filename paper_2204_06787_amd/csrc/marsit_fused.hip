@@ -426,12 +426,10 @@ staged_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__
         f32x4 gv[BATCH], cv[BATCH];
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
-            {
-                const uint32_t mm = (static_cast<uint32_t>(i) < M) ? static_cast<uint32_t>(i) : M - 1u;
-                const size_t off = static_cast<size_t>(mm) * ld + e;
-                gv[i] = load4(g + off, vec, n_valid);
-                cv[i] = load4(c + off, vec, n_valid);
-            }
+            const uint32_t mm = (static_cast<uint32_t>(i) < M) ? static_cast<uint32_t>(i) : M - 1u;
+            const size_t off = static_cast<size_t>(mm) * ld + e;
+            gv[i] = load4(g + off, vec, n_valid);
+            cv[i] = load4(c + off, vec, n_valid);
         }
         f32x4 xv = {0.0f, 0.0f, 0.0f, 0.0f};
         if (x_model != nullptr)
@@ -449,29 +447,25 @@ staged_step_kernel(const float *__restrict__ g, float *__restrict__ c, float *__
 
         // compensated gradient of every worker into LDS (Algorithm 1, first step)
 #pragma unroll
-        for (int i = 0; i < BATCH; ++i)
-            {
-                const uint32_t mm = (static_cast<uint32_t>(i) < M) ? static_cast<uint32_t>(i) : M - 1u;
-                stage[static_cast<size_t>(mm) * kSyncBlock] = gv[i] + cv[i];
-            }
+        for (int i = 0; i < BATCH; ++i) {
+            const uint32_t mm = (static_cast<uint32_t>(i) < M) ? static_cast<uint32_t>(i) : M - 1u;
+            stage[static_cast<size_t>(mm) * kSyncBlock] = gv[i] + cv[i];
+        }
 #pragma unroll 1
         for (uint32_t m0 = BATCH; m0 < M; m0 += BATCH) {
 #pragma unroll
             for (int i = 0; i < BATCH; ++i) {
-                {
-                    const uint32_t mm = (m0 + i < M) ? m0 + i : M - 1u;
-                    const size_t off = static_cast<size_t>(mm) * ld + e;
-                    gv[i] = load4(g + off, vec, n_valid);
-                    cv[i] = load4(c + off, vec, n_valid);
-                }
+                const uint32_t mm = (m0 + i < M) ? m0 + i : M - 1u;
+                const size_t off = static_cast<size_t>(mm) * ld + e;
+                gv[i] = load4(g + off, vec, n_valid);
+                cv[i] = load4(c + off, vec, n_valid);
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < BATCH; ++i)
-                {
-                    const uint32_t mm = (m0 + i < M) ? m0 + i : M - 1u;
-                    stage[static_cast<size_t>(mm) * kSyncBlock] = gv[i] + cv[i];
-                }
+            for (int i = 0; i < BATCH; ++i) {
+                const uint32_t mm = (m0 + i < M) ? m0 + i : M - 1u;
+                stage[static_cast<size_t>(mm) * kSyncBlock] = gv[i] + cv[i];
+            }
         }
 
         // global update from the picked workers' signs
