@@ -97,7 +97,7 @@ def test_round_replays():
 def test_multi_kernel_entry_points_replay():
     def exchange_static(g, s, stream):
         marsit.marsit_exchange_step_sim_static(g, s["c"], s["update"], s["bits"], SCALE, 82, stream=stream)
-    _record_and_replay("one exchange step on the static workspace (17 launches)", 8, 40_003, exchange_static,
+    _record_and_replay("one exchange step on the static workspace (24 launches)", 8, 40_003, exchange_static,
                        seed=7)
 
     M, d = 4, 20_000
