@@ -382,6 +382,50 @@ int oracle_local_momentum(float *buf, const float *grad, float *g_out, uint32_t 
     return 0;
 }
 
+/*
+ * Local Adam of a worker (Section 5, "Optimizers and hyper-parameters": the sentiment-analysis runs
+ * use Adam; the paper prints no formula, so the optimizer's published form with bias correction is
+ * taken).  Per worker m and element e < d, with first moment p, second moment q and gradient a:
+ *     p <- beta1 * p + (1 - beta1) * a
+ *     q <- beta2 * q + (1 - beta2) * (a * a)
+ *     g <- eta_l * ( (p / bias1) / (sqrt(q / bias2) + eps) )
+ * bias1 = 1 - beta1^t and bias2 = 1 - beta2^t are the caller's (they depend on the round only).
+ * Every operation is one fp32 rounding, in the order written: 1 - beta is rounded once; each
+ * moment is product, product, sum; the step is quotient, quotient, root, sum, quotient, product.
+ * g is what Algorithm 2 hands to Marsit as its (already scaled) gradient.
+ */
+int oracle_local_adam(float *mom1, float *mom2, const float *grad, float *g_out, uint32_t M,
+                      uint64_t d, uint64_t ld, float beta1, float beta2, float eps, float eta_l,
+                      float bias1, float bias2)
+{
+    if (ld < d)
+        return -1;
+    const float rest1 = 1.0f - beta1;
+    const float rest2 = 1.0f - beta2;
+    for (uint32_t m = 0; m < M; ++m) {
+        for (uint64_t e = 0; e < d; ++e) {
+            const size_t i = (size_t)m * ld + e;
+            const float a = grad[i];
+            const float p_old = beta1 * mom1[i];
+            const float p_new = rest1 * a;
+            const float p = p_old + p_new;
+            const float a2 = a * a;
+            const float q_old = beta2 * mom2[i];
+            const float q_new = rest2 * a2;
+            const float q = q_old + q_new;
+            mom1[i] = p;
+            mom2[i] = q;
+            const float p_hat = p / bias1;
+            const float q_hat = q / bias2;
+            const float root = sqrtf(q_hat);
+            const float denom = root + eps;
+            const float dir = p_hat / denom;
+            g_out[i] = eta_l * dir;
+        }
+    }
+    return 0;
+}
+
 /* ------------------------------------------------------------------------------------------
  * Diagnostics of Section 3.2.2 / Fig. 2(b): the "matching rate" of a sign vector is the share of
  * elements whose sign equals the sign of the non-compressed aggregate sum_m (g^(m) + c^(m)).

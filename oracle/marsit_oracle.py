@@ -79,6 +79,8 @@ def _load():
     lib.oracle_apply_update.restype = None
     lib.oracle_local_momentum.argtypes = [vp, vp, vp, u32, u64, u64, f32, f32]
     lib.oracle_local_momentum.restype = ctypes.c_int
+    lib.oracle_local_adam.argtypes = [vp, vp, vp, vp, u32, u64, u64, f32, f32, f32, f32, f32, f32]
+    lib.oracle_local_adam.restype = ctypes.c_int
     lib.oracle_aggregate_sign.argtypes = [vp, vp, vp, u32, u64, u64]
     lib.oracle_aggregate_sign.restype = None
     lib.oracle_majority_vote.argtypes = [vp, vp, vp, u32, u64, u64]
@@ -297,6 +299,22 @@ def local_momentum(buf, grad, beta, eta_l, d=None):
     g = np.full_like(grad, 12345.0)
     rc = _load().oracle_local_momentum(_ptr(buf), _ptr(grad), _ptr(g), M, d, ld,
                                        beta, eta_l)
+    assert rc == 0
+    return g
+
+
+def local_adam(mom1, mom2, grad, beta1, beta2, eps, eta_l, bias1, bias2, d=None):
+    """Adam moments updated in place (float32 [M, ld]); returns g = eta_l * corrected step.
+    bias1 = 1 - beta1**t, bias2 = 1 - beta2**t for the round t >= 1 being taken."""
+    mom1 = _f32(mom1, "mom1")
+    mom2 = _f32(mom2, "mom2")
+    grad = _f32(grad, "grad")
+    assert mom1.ndim == 2 and mom1.shape == grad.shape == mom2.shape
+    M, ld = mom1.shape
+    d = ld if d is None else int(d)
+    g = np.full_like(grad, 12345.0)
+    rc = _load().oracle_local_adam(_ptr(mom1), _ptr(mom2), _ptr(grad), _ptr(g), M, d, ld, beta1, beta2, eps, eta_l,
+                                   bias1, bias2)
     assert rc == 0
     return g
 

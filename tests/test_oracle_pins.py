@@ -553,6 +553,86 @@ def test_local_momentum_matches_torch_sgd_buffer():
         assert np.allclose(p.detach().numpy(), x, rtol=0, atol=2e-6 * (t + 1))
 
 
+def test_local_adam_sign_like_special_case():
+    """beta1 = beta2 = 0, no bias left to correct, eps = 0: the moments are the gradient and its
+    square, sqrt(a*a) = |a| exactly whenever a*a neither overflows nor goes denormal, a/|a| = +-1,
+    so the step is exactly +-eta_l; a zero gradient gives 0/0 = NaN, which Adam's eps is there for."""
+    rng = np.random.default_rng(90)
+    grad = rng.standard_normal((2, 300)).astype(np.float32)
+    grad[grad == 0] = 1.0
+    p = rng.standard_normal((2, 300)).astype(np.float32)
+    q = np.abs(rng.standard_normal((2, 300))).astype(np.float32)
+    g = orc.local_adam(p, q, grad, 0.0, 0.0, 0.0, 0.125, 1.0, 1.0)
+    assert np.array_equal(p, grad) and np.array_equal(q, grad * grad)
+    assert np.array_equal(g, np.where(grad > 0, np.float32(0.125), np.float32(-0.125)))
+    # eps is added to the root, not under it: a = 3, eps = 1 -> 3 / (3 + 1)
+    one = np.full((1, 4), 3.0, dtype=np.float32)
+    g = orc.local_adam(np.zeros_like(one), np.zeros_like(one), one, 0.0, 0.0, 1.0, 1.0, 1.0, 1.0)
+    assert np.all(g == np.float32(0.75))
+
+
+def test_local_adam_constant_gradient_closed_form():
+    """Constant gradient a from zero moments: p_t = (1 - beta1^t) a and q_t = (1 - beta2^t) a^2, so the
+    corrected moments are a and a^2 at every round and the step is eta_l * a / (|a| + eps) -- the
+    property the bias correction exists for.  Columns >= d are neither read nor written."""
+    b1, b2, eps, eta = 0.9, 0.999, 1e-8, 0.01
+    a = np.array([[0.5, -2.0, 1e-3, -7.0, 777.0], [3.0, -0.25, 40.0, 1e-2, 777.0]], dtype=np.float32)
+    p = np.zeros_like(a)
+    q = np.zeros_like(a)
+    for t in range(1, 40):
+        g = orc.local_adam(p, q, a, b1, b2, eps, eta, 1.0 - b1 ** t, 1.0 - b2 ** t, d=4)
+        want_p = (1.0 - b1 ** t) * a[:, :4].astype(np.float64)
+        want_q = (1.0 - b2 ** t) * a[:, :4].astype(np.float64) ** 2
+        assert np.allclose(p[:, :4], want_p, rtol=2e-5, atol=0) and np.allclose(q[:, :4], want_q, rtol=2e-5, atol=0)
+        want = eta * a[:, :4] / (np.abs(a[:, :4]) + eps)
+        assert np.allclose(g[:, :4], want, rtol=5e-5, atol=0), t
+        assert np.all(p[:, 4] == 0.0) and np.all(q[:, 4] == 0.0) and np.all(g[:, 4] == 12345.0)
+
+
+def test_local_adam_matches_torch_adam():
+    """torch.optim.Adam (CPU, fp32, no weight decay, no amsgrad) moves the parameter by -g every step
+    when lr = eta_l.  torch orders the arithmetic differently (lerp for the first moment, the bias
+    correction folded into the step size), so agreement is to accumulated fp32 rounding."""
+    import torch
+    rng = np.random.default_rng(91)
+    b1, b2, eps, eta = 0.9, 0.98, 1e-6, 0.02
+    x0 = rng.standard_normal(400).astype(np.float32)
+    par = torch.nn.Parameter(torch.from_numpy(x0.copy()))
+    opt = torch.optim.Adam([par], lr=eta, betas=(b1, b2), eps=eps)
+    p = np.zeros((1, 400), dtype=np.float32)
+    q = np.zeros((1, 400), dtype=np.float32)
+    x = x0.astype(np.float64)
+    for t in range(1, 9):
+        grad = (rng.standard_normal((1, 400)) * 10.0 ** rng.uniform(-3, 1)).astype(np.float32)
+        par.grad = torch.from_numpy(grad[0].copy())
+        opt.step()
+        g = orc.local_adam(p, q, grad, b1, b2, eps, eta, 1.0 - b1 ** t, 1.0 - b2 ** t)
+        x = x - g[0].astype(np.float64)
+        assert np.allclose(par.detach().numpy(), x, rtol=0, atol=3e-6 * t), t
+        state = opt.state[par]
+        assert np.allclose(state["exp_avg"].numpy(), p[0], rtol=1e-5, atol=1e-6 * np.abs(p).max())
+        assert np.allclose(state["exp_avg_sq"].numpy(), q[0], rtol=1e-5, atol=1e-6 * q.max())
+
+
+def test_local_adam_single_roundings():
+    """Each operation is rounded once in fp32, in the stated order: an element-by-element replay
+    with numpy float32 scalars (which round after every operation) gives the same bits."""
+    rng = np.random.default_rng(92)
+    f = np.float32
+    b1, b2, eps, eta, bias1, bias2 = f(0.9), f(0.999), f(1e-8), f(0.003), f(1 - 0.9 ** 3), f(1 - 0.999 ** 3)
+    grad = rng.standard_normal((1, 64)).astype(np.float32)
+    p = rng.standard_normal((1, 64)).astype(np.float32)
+    q = np.abs(rng.standard_normal((1, 64))).astype(np.float32)
+    p0, q0 = p.copy(), q.copy()
+    g = orc.local_adam(p, q, grad, b1, b2, eps, eta, bias1, bias2)
+    for i in range(64):
+        a = grad[0, i]
+        pp = b1 * p0[0, i] + (f(1) - b1) * a
+        qq = b2 * q0[0, i] + (f(1) - b2) * (a * a)
+        step = eta * ((pp / bias1) / (np.sqrt(qq / bias2) + eps))
+        assert pp == p[0, i] and qq == q[0, i] and step == g[0, i], i
+
+
 # ---------------------------------------------------------------------------------------------
 # Matching-rate diagnostics (Section 3.2.2, Fig. 2b)
 # ---------------------------------------------------------------------------------------------
