@@ -11,7 +11,7 @@ Inputs are resident in HBM before the timed region starts.  Prints ONE JSON line
 The default run is the headline: marsit_ring_step_sim on the resnet50 workload (M = 8,
 d = 25.6 M, ring).  The switches --entry, --M, --d, --grid-x and --ld-pad time the other
 whole-pass entry points, other worker counts and schedules (those without a compiled
-specialisation run the any-schedule kernel) and rows that do not start on 16-byte boundaries;
+specialisation run the any-schedule kernel) and rows that do not start on 128-byte lines;
 they exist so that every figure quoted for those kernels comes from this file.
 """
 
@@ -356,6 +356,12 @@ def other_entry_points(torch, marsit, workloads, wl, grads, update, bits, stream
     scaled = torch.empty_like(c3)
     aux["marsit_local_momentum"] = entry(timed(lambda i: marsit.marsit_local_momentum(
         c3, grads[i % pool], scaled, 0.5, 0.1, stream=stream)), 16 * M * d)
+    c3.zero_()
+    mom2 = torch.zeros_like(c3)
+    aux["marsit_local_adam"] = entry(timed(lambda i: marsit.marsit_local_adam(
+        c3, mom2, grads[i % pool], scaled, 0.9, 0.999, 1e-8, 0.1, 1.0 - 0.9 ** (i + 1), 1.0 - 0.999 ** (i + 1),
+        stream=stream)), 24 * M * d)
+    del mom2
     c3.zero_()
 
     # ---- per-worker kernels, operands rotated so that none is cache resident ----

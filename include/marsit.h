@@ -450,6 +450,23 @@ int marsit_cascade_ring_step_sim(const float *g, const float *c, float *update_o
 int marsit_local_momentum(float *buf, const float *grad, float *g_out, uint32_t M, uint64_t d,
                           uint64_t ld, float beta, float eta_l, void *stream);
 
+/*
+ * Local Adam of the M workers before a synchronisation (Section 5, optimizers: the sentiment-analysis
+ * runs use Adam; the paper prints no formula, the optimizer's published form with bias correction is
+ * taken).  With first moment p = mom1, second moment q = mom2 and gradient a = grad:
+ *     p <- beta1 * p + (1 - beta1) * a;     q <- beta2 * q + (1 - beta2) * (a * a);
+ *     g_out <- eta_l * ((p / bias1) / (sqrt(q / bias2) + eps)),
+ * each operation rounded once in fp32 in the order written (1 - beta is rounded once).  bias1 and
+ * bias2 are the caller's 1 - beta1^t and 1 - beta2^t for the round t >= 1 being taken (they depend
+ * on t only); both must be finite and non-zero.  g_out is what Algorithm 2 passes to the
+ * synchronisation as the scaled gradient.  All four arrays are [M][ld] device memory, columns >= d
+ * untouched; g_out may be the same array as grad, the moments may alias nothing.  A zero second
+ * moment with eps = 0 gives 0/0 = NaN, as the formula says.
+ */
+int marsit_local_adam(float *mom1, float *mom2, const float *grad, float *g_out, uint32_t M, uint64_t d,
+                      uint64_t ld, float beta1, float beta2, float eps, float eta_l, float bias1,
+                      float bias2, void *stream);
+
 /* Algorithm 2, the model update:  x[e] <- x[e] - update[e]. */
 int marsit_apply_update(float *x, const float *update, uint64_t d, void *stream);
 

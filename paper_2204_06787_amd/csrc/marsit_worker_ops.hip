@@ -378,13 +378,78 @@ local_momentum_kernel(float *__restrict__ buf, const float *grad, float *g_out, 
     }
 }
 
+// Local Adam for all workers in one launch (blockIdx.y = worker), the published form with bias
+// correction (Section 5 of the paper names the optimizer only):
+//   p <- beta1 * p + (1 - beta1) * a;   q <- beta2 * q + (1 - beta2) * (a * a);
+//   g <- eta_l * ((p / bias1) / (sqrt(q / bias2) + eps)).
+// One fp32 rounding per operation in this order (the library is built without contraction, and
+// hipcc's fp32 division and square root are correctly rounded).  rest1 = 1 - beta1 and
+// rest2 = 1 - beta2 are rounded once on the host.  g may be the same array as the gradient: a lane
+// reads its elements before it writes them.
+template <int COLS>
+__global__ void __launch_bounds__(kSyncBlock)
+local_adam_kernel(float *__restrict__ mom1, float *__restrict__ mom2, const float *grad, float *g_out,
+                  uint64_t d, uint64_t ld, float beta1, float rest1, float beta2, float rest2, float eps,
+                  float eta_l, float bias1, float bias2)
+{
+    const uint64_t n_cols = (d + 3) >> 2;
+    const uint64_t col0 = static_cast<uint64_t>(blockIdx.x) * (kSyncBlock * COLS) + threadIdx.x;
+    const size_t row = static_cast<size_t>(blockIdx.y) * ld;
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    f32x4 pv[COLS], qv[COLS], av[COLS];
+#pragma unroll
+    for (int k = 0; k < COLS; ++k) {
+        const uint64_t col = col0 + static_cast<uint64_t>(k) * kSyncBlock;
+        pv[k] = zero;
+        qv[k] = zero;
+        av[k] = zero;
+        if (col < n_cols) {
+            const uint64_t e = col << 2;
+            const bool full = e + 4 <= d;
+            const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+            pv[k] = load4<true>(mom1 + row + e, full, n_valid);
+            qv[k] = load4<true>(mom2 + row + e, full, n_valid);
+            av[k] = load4<true>(grad + row + e, full, n_valid);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int k = 0; k < COLS; ++k) {
+        const uint64_t col = col0 + static_cast<uint64_t>(k) * kSyncBlock;
+        if (col < n_cols) {
+            const uint64_t e = col << 2;
+            const bool full = e + 4 <= d;
+            const uint32_t n_valid = full ? 4u : static_cast<uint32_t>(d - e);
+            const f32x4 p_old = pv[k] * beta1;
+            const f32x4 p_new = av[k] * rest1;
+            const f32x4 p = p_old + p_new;
+            const f32x4 a2 = av[k] * av[k];
+            const f32x4 q_old = qv[k] * beta2;
+            const f32x4 q_new = a2 * rest2;
+            const f32x4 q = q_old + q_new;
+            f32x4 step;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float p_hat = p[j] / bias1;
+                const float q_hat = q[j] / bias2;
+                const float denom = sqrtf(q_hat) + eps;
+                const float dir = p_hat / denom;
+                step[j] = eta_l * dir;
+            }
+            store4<true>(mom1 + row + e, p, full, n_valid);
+            store4<true>(mom2 + row + e, q, full, n_valid);
+            store4<true>(g_out + row + e, step, full, n_valid);
+        }
+    }
+}
+
 }   // namespace marsit
 
 using namespace marsit;
 
 extern "C" {
 
-int marsit_version(void) { return 200; }
+int marsit_version(void) { return 210; }
 
 int marsit_last_hip_error(void) { return tls_last_hip_error; }
 
@@ -791,6 +856,28 @@ int marsit_local_momentum(float *buf, const float *grad, float *g_out, uint32_t 
     hipLaunchKernelGGL(local_momentum_kernel<kStreamCols>, dim3(stream_blocks((d + 3) >> 2, kStreamCols), M), dim3(kSyncBlock),
                        throttle_lds_bytes(16),
                        static_cast<hipStream_t>(stream), buf, grad, g_out, d, ld, beta, eta_l);
+    return finish_launch();
+}
+
+int marsit_local_adam(float *mom1, float *mom2, const float *grad, float *g_out, uint32_t M, uint64_t d,
+                      uint64_t ld, float beta1, float beta2, float eps, float eta_l, float bias1,
+                      float bias2, void *stream)
+{
+    if (mom1 == nullptr || mom2 == nullptr || grad == nullptr || g_out == nullptr || M == 0 ||
+        M > MARSIT_MAX_WORKERS || ld < d || d > kMaxElements || !std::isfinite(beta1) ||
+        !std::isfinite(beta2) || !std::isfinite(eps) || !std::isfinite(eta_l) || !std::isfinite(bias1) ||
+        !std::isfinite(bias2) || bias1 == 0.0f || bias2 == 0.0f || mom1 == mom2 || mom1 == grad ||
+        mom2 == grad || mom1 == g_out || mom2 == g_out)
+        return MARSIT_EINVAL;
+    if (!aligned_to(mom1, 4) || !aligned_to(mom2, 4) || !aligned_to(grad, 4) || !aligned_to(g_out, 4))
+        return MARSIT_EALIGN;
+    if (d == 0)
+        return MARSIT_OK;
+    const float rest1 = 1.0f - beta1;
+    const float rest2 = 1.0f - beta2;
+    hipLaunchKernelGGL(local_adam_kernel<kStreamCols>, dim3(stream_blocks((d + 3) >> 2, kStreamCols), M),
+                       dim3(kSyncBlock), throttle_lds_bytes(16), static_cast<hipStream_t>(stream), mom1, mom2, grad,
+                       g_out, d, ld, beta1, rest1, beta2, rest2, eps, eta_l, bias1, bias2);
     return finish_launch();
 }
 

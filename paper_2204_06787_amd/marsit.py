@@ -26,6 +26,7 @@ EXPORTS = (
     "marsit_split_bounds", "marsit_compress", "marsit_hop_merge", "marsit_decode_compensate",
     "marsit_ring_step_sim", "marsit_chain_step_sim", "marsit_chain_workspace_words",
     "marsit_full_sync", "marsit_step", "marsit_step_apply", "marsit_apply_update", "marsit_local_momentum",
+    "marsit_local_adam",
     "marsit_pipeline_create", "marsit_pipeline_destroy", "marsit_pipeline_workspace_words",
     "marsit_compress_hop_merge", "marsit_decode_compensate_apply", "marsit_fold_segments",
     "marsit_exchange_step_sim", "marsit_pipeline_step", "marsit_pipeline_ring_step", "marsit_pipeline_last_hip_error",
@@ -145,6 +146,8 @@ def load_library(path: str | None = None):
     lib.marsit_apply_update.restype = ci
     lib.marsit_local_momentum.argtypes = [vp, vp, vp, u32, u64, u64, f32, f32, vp]
     lib.marsit_local_momentum.restype = ci
+    lib.marsit_local_adam.argtypes = [vp, vp, vp, vp, u32, u64, u64, f32, f32, f32, f32, f32, f32, vp]
+    lib.marsit_local_adam.restype = ci
     if path == (os.environ.get("MARSIT_LIBRARY") or LIB_PATH):
         _lib = lib
     return lib
@@ -498,6 +501,18 @@ def marsit_local_momentum(buf, grad, g_out, beta: float, eta_l: float, d: int | 
     _check("marsit_local_momentum", load_library().marsit_local_momentum(
         _f32_ptr(buf, "buf"), _f32_ptr(grad, "grad"), _f32_ptr(g_out, "g_out"), M, d, ld, beta, eta_l,
         _stream(stream)))
+    return g_out
+
+
+def marsit_local_adam(mom1, mom2, grad, g_out, beta1: float, beta2: float, eps: float, eta_l: float,
+                      bias1: float, bias2: float, d: int | None = None, stream=None):
+    """Local Adam of the M workers; ``bias1 = 1 - beta1**t``, ``bias2 = 1 - beta2**t`` for round t >= 1."""
+    M, ld, d = _matrix_args(mom1, grad, d, names=("mom1", "grad"))
+    if _rows(mom2, "mom2", d) != (M, ld) or _rows(g_out, "g_out", d) != (M, ld):
+        raise TypeError("mom1, mom2, grad and g_out must have the same shape and row stride")
+    _check("marsit_local_adam", load_library().marsit_local_adam(
+        _f32_ptr(mom1, "mom1"), _f32_ptr(mom2, "mom2"), _f32_ptr(grad, "grad"), _f32_ptr(g_out, "g_out"), M, d, ld,
+        beta1, beta2, eps, eta_l, bias1, bias2, _stream(stream)))
     return g_out
 
 

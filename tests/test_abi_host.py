@@ -141,6 +141,7 @@ def test_size_limit_is_what_one_launch_can_cover(lib):
         assert lib.marsit_fold_segments(FAKE, d, 2, 0, FAKE, 0, d // 64 + 1, 0, 5, None) == E
         assert lib.marsit_apply_update(FAKE, FAKE, d, None) == E
         assert lib.marsit_local_momentum(FAKE, FAKE + 64, FAKE + 64, 1, d, d, 0.5, 0.1, None) == E
+        assert lib.marsit_local_adam(FAKE, FAKE + 64, FAKE + 128, FAKE + 128, 1, d, d, 0.9, 0.99, 1e-8, 0.1, 0.1, 0.01, None) == E
         assert lib.marsit_chain_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, 1, d, d, 1.0, 1, 0, None) == E
         assert lib.marsit_exchange_step_sim(FAKE, FAKE, FAKE, FAKE, FAKE, 1, d, d, 1.0, 1, 0, None) == E
         assert lib.marsit_exchange_step_sim_static(FAKE, FAKE, FAKE, FAKE, 1, d, d, 1.0, 1, 0, None) == E
@@ -283,6 +284,17 @@ def test_other_entry_points_argument_validation(lib):
     assert lib.marsit_local_momentum(FAKE, FAKE + 64, FAKE + 64, 2, 64, 64, float("nan"), 0.1, None) == marsit.EINVAL
     assert lib.marsit_local_momentum(FAKE, FAKE + 62, FAKE + 64, 2, 64, 64, 0.9, 0.1, None) == marsit.EALIGN
     assert lib.marsit_local_momentum(FAKE, FAKE + 64, FAKE + 64, 2, 0, 64, 0.9, 0.1, None) == marsit.OK
+    adam = lib.marsit_local_adam
+    ok_args = (2, 64, 64, 0.9, 0.999, 1e-8, 0.1, 0.1, 0.001, None)
+    assert adam(FAKE, FAKE + 1024, FAKE + 2048, None, *ok_args) == marsit.EINVAL
+    assert adam(FAKE, FAKE, FAKE + 2048, FAKE + 2048, *ok_args) == marsit.EINVAL                 # moments alias
+    assert adam(FAKE, FAKE + 1024, FAKE, FAKE + 2048, *ok_args) == marsit.EINVAL                 # moment aliases grad
+    assert adam(FAKE, FAKE + 1024, FAKE + 2048, FAKE + 1024, *ok_args) == marsit.EINVAL          # moment aliases output
+    assert adam(FAKE, FAKE + 1024, FAKE + 2048, FAKE + 2048, 2, 64, 32, 0.9, 0.999, 1e-8, 0.1, 0.1, 0.001, None) == marsit.EINVAL
+    assert adam(FAKE, FAKE + 1024, FAKE + 2048, FAKE + 2048, 2, 64, 64, 0.9, 0.999, 1e-8, 0.1, 0.0, 0.001, None) == marsit.EINVAL   # bias1 = 0
+    assert adam(FAKE, FAKE + 1024, FAKE + 2048, FAKE + 2048, 2, 64, 64, 0.9, float("inf"), 1e-8, 0.1, 0.1, 0.001, None) == marsit.EINVAL
+    assert adam(FAKE, FAKE + 1022, FAKE + 2048, FAKE + 2048, *ok_args) == marsit.EALIGN
+    assert adam(FAKE, FAKE + 1024, FAKE + 2048, FAKE + 2048, 2, 0, 64, 0.9, 0.999, 1e-8, 0.1, 0.1, 0.001, None) == marsit.OK
 
 
 def test_missing_library_fails_loudly(tmp_path):

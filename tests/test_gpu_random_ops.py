@@ -11,7 +11,7 @@ from paper_2204_06787_amd import marsit
 pytestmark = pytest.mark.gpu
 
 OPS = ["compress", "hop_merge", "weighted", "compress_hop_merge", "fold", "decode", "decode_apply", "momentum",
-       "votes", "cascade_ring"]
+       "adam", "votes", "cascade_ring"]
 
 
 def _vec(a: np.ndarray, off: int) -> torch.Tensor:
@@ -122,6 +122,25 @@ def test_random_ops(chunk):
             marsit.marsit_local_momentum(buf_d, grad_d, grad_d, beta, eta, d=d)
             torch.cuda.synchronize()
             assert np.array_equal(buf_d.cpu().numpy().view(np.uint32), buf_h.view(np.uint32)), case
+            assert np.array_equal(grad_d.cpu().numpy()[:, :d].view(np.uint32), want_g[:, :d].view(np.uint32)), case
+            assert np.array_equal(grad_d.cpu().numpy()[:, d:], grad_h[:, d:]), case
+        elif op == "adam":
+            M = int(rng.integers(1, 9))
+            d = max(1, n // M)
+            ld = d + int(rng.choice([0, 1, 4]))
+            p_h = (0.1 * rng.standard_normal((M, ld))).astype(np.float32)
+            q_h = (0.01 * rng.standard_normal((M, ld)) ** 2).astype(np.float32)
+            grad_h = (rng.standard_normal((M, ld)) * 10.0 ** rng.uniform(-6, 3, size=(M, ld))).astype(np.float32)
+            b1, b2 = float(rng.choice([0.0, 0.5, 0.9])), float(rng.choice([0.0, 0.9, 0.999]))
+            eps, eta = float(rng.choice([1e-8, 1e-3, 1.0])), float(rng.choice([1.0, 0.1, 3e-4]))
+            t = int(rng.integers(1, 2000))
+            bias1, bias2 = 1.0 - b1 ** t, 1.0 - b2 ** t
+            p_d, q_d, grad_d = torch.from_numpy(p_h).cuda(), torch.from_numpy(q_h).cuda(), torch.from_numpy(grad_h).cuda()
+            want_g = orc.local_adam(p_h, q_h, grad_h, b1, b2, eps, eta, bias1, bias2, d=d)
+            marsit.marsit_local_adam(p_d, q_d, grad_d, grad_d, b1, b2, eps, eta, bias1, bias2, d=d)
+            torch.cuda.synchronize()
+            assert np.array_equal(p_d.cpu().numpy().view(np.uint32), p_h.view(np.uint32)), case
+            assert np.array_equal(q_d.cpu().numpy().view(np.uint32), q_h.view(np.uint32)), case
             assert np.array_equal(grad_d.cpu().numpy()[:, :d].view(np.uint32), want_g[:, :d].view(np.uint32)), case
             assert np.array_equal(grad_d.cpu().numpy()[:, d:], grad_h[:, d:]), case
         elif op == "votes":

@@ -87,6 +87,91 @@ def test_local_momentum(M, d, ld, offset):
         assert_f32_parity(host_f32(out_d), want_g, f"scaled gradient, step {t}")
 
 
+@pytest.mark.parametrize("M,d,ld,offset", [(1, 1, 1, 0), (3, 5, 7, 0), (8, 4096, 4096, 0), (4, 100_003, 100_003, 0),
+                                           (5, 1000, 1004, 0), (2, 777, 780, 1), (64, 130, 132, 0)])
+def test_local_adam(M, d, ld, offset):
+    """Four rounds of the workers' Adam moments (bias corrections of rounds 1..4), in place over the
+    gradient and into a separate output, from unaligned bases and padded rows, gradients over
+    fourteen orders of magnitude with exact zeros among them.  Quotients and the square root are
+    correctly rounded on both sides, so the comparison is bit for bit."""
+    rng = np.random.default_rng(M * 1000 + d + 5)
+    b1, b2, eps, eta = 0.9, 0.999, 1e-8, 0.003
+    p_h = (0.1 * rng.standard_normal((M, ld))).astype(np.float32)
+    q_h = (0.01 * rng.standard_normal((M, ld)) ** 2).astype(np.float32)
+    if offset:
+        p_d, q_d = unaligned_rows(M, ld, offset), unaligned_rows(M, ld, offset)
+        p_d.copy_(dev(p_h))
+        q_d.copy_(dev(q_h))
+    else:
+        p_d, q_d = dev(p_h), dev(q_h)
+    for t in range(1, 5):
+        grad_h = (rng.standard_normal((M, ld)) * 10.0 ** rng.uniform(-10, 4, size=(M, ld))).astype(np.float32)
+        grad_h[rng.random((M, ld)) < 0.05] = 0.0
+        bias1, bias2 = 1.0 - b1 ** t, 1.0 - b2 ** t
+        want_g = orc.local_adam(p_h, q_h, grad_h, b1, b2, eps, eta, bias1, bias2, d=d)
+        grad_d = dev(grad_h)
+        if t % 2 == 0:
+            out_d = torch.full((M, ld), 12345.0, dtype=torch.float32, device="cuda")
+            marsit.marsit_local_adam(p_d, q_d, grad_d, out_d, b1, b2, eps, eta, bias1, bias2, d=d)
+        else:
+            out_d = marsit.marsit_local_adam(p_d, q_d, grad_d, grad_d, b1, b2, eps, eta, bias1, bias2, d=d)
+            want_g[:, d:] = grad_h[:, d:]                      # in place: the padding keeps the gradient's values
+        torch.cuda.synchronize()
+        assert_f32_parity(host_f32(p_d), p_h, f"first moment, round {t}")
+        assert_f32_parity(host_f32(q_d), q_h, f"second moment, round {t}")
+        assert_f32_parity(host_f32(out_d), want_g, f"scaled step, round {t}")
+
+
+def test_local_adam_extreme_values():
+    """Denormal and huge second moments, eps = 0 with a zero moment (0/0 = NaN on both sides), beta = 0."""
+    f = np.float32
+    grad_h = np.array([[0.0, 1e-30, -1e-25, 3e18, -1e19, 1e-45, 5.0, -0.0]], dtype=np.float32)
+    for b1, b2, eps in ((0.9, 0.999, 1e-8), (0.0, 0.0, 0.0), (0.5, 0.25, 1.0)):
+        p_h = np.zeros_like(grad_h)
+        q_h = np.zeros_like(grad_h)
+        p_d, q_d = dev(p_h), dev(q_h)
+        for t in range(1, 4):
+            bias1 = 1.0 - b1 ** t
+            bias2 = 1.0 - b2 ** t
+            want = orc.local_adam(p_h, q_h, grad_h, b1, b2, eps, 0.01, bias1, bias2)
+            out_d = torch.empty_like(p_d)
+            marsit.marsit_local_adam(p_d, q_d, dev(grad_h), out_d, b1, b2, eps, 0.01, bias1, bias2)
+            torch.cuda.synchronize()
+            got = host_f32(out_d)
+            assert np.array_equal(np.isnan(got), np.isnan(want)), (b1, b2, eps, t)
+            ok = ~np.isnan(want)
+            assert np.array_equal(got[ok].view(np.uint32), want[ok].view(np.uint32)), (b1, b2, eps, t, got, want)
+            assert np.array_equal(host_f32(p_d).view(np.uint32), p_h.view(np.uint32))
+            assert np.array_equal(host_f32(q_d).view(np.uint32), q_h.view(np.uint32))
+
+
+def test_sgd_driver_with_local_adam():
+    """MarsitSGD with optimizer="adam" against the oracle's Adam + synchronisation + update."""
+    from paper_2204_06787_amd.sgd import MarsitSGD
+    M, d, K = 4, 50_001, 4
+    rng = np.random.default_rng(98)
+    x_h = rng.standard_normal(d).astype(np.float32)
+    c_h = np.zeros((M, d), dtype=np.float32)
+    p_h = np.zeros((M, d), dtype=np.float32)
+    q_h = np.zeros((M, d), dtype=np.float32)
+    opt = MarsitSGD(dev(x_h), M=M, K=K, eta_s=2e-3, seed=41, optimizer="adam", betas=(0.9, 0.98), eps=1e-6)
+    for t in range(6):
+        grad_h = rng.standard_normal((M, d)).astype(np.float32)
+        opt.step_from_raw_gradients(dev(grad_h), eta_l=0.01)
+        g_h = orc.local_adam(p_h, q_h, grad_h, 0.9, 0.98, 1e-6, 0.01, 1.0 - 0.9 ** (t + 1), 1.0 - 0.98 ** (t + 1))
+        if t % K == 0:
+            u_h = orc.full_sync(g_h, c_h)
+        else:
+            u_h, _, _ = orc.sync_step(g_h, c_h, 2e-3, 41 + t)
+        x_h = orc.apply_update(x_h, u_h)
+        torch.cuda.synchronize()
+        assert_f32_parity(host_f32(opt.buf), p_h, f"first moments, round {t}")
+        assert_f32_parity(host_f32(opt.buf2), q_h, f"second moments, round {t}")
+        assert_f32_parity(host_f32(opt.c), c_h, f"compensation, round {t}")
+        assert_f32_parity(host_f32(opt.update), u_h, f"update, round {t}")
+        assert_f32_parity(host_f32(opt.x), x_h, f"model, round {t}")
+
+
 def test_sgd_driver_with_local_momentum():
     """MarsitSGD.step_from_raw_gradients against the oracle's momentum + synchronisation + update."""
     from paper_2204_06787_amd.sgd import MarsitSGD
