@@ -14,7 +14,7 @@ thread_local int tls_last_hip_error = 0;
 // Workspace of marsit_exchange_step_sim_static.  Every GPU the library runs on holds its own copy
 // of this array, at its own address, until the process ends.  In host code the name is only a
 // handle for hipGetSymbolAddress; kernels get the address that call returns.
-__device__ __align__(256) uint64_t scratch[MARSIT_STATIC_SCRATCH_WORDS];
+static __device__ __align__(256) uint64_t scratch[MARSIT_STATIC_SCRATCH_WORDS];
 
 constexpr int kMaxDevices = 64;
 static std::atomic<uint64_t *> scratch_address[kMaxDevices];
