@@ -38,89 +38,88 @@ def test_random_shapes(chunk):
 
 def run_case(rng, label, worker_counts):
     """One random case through one whole-pass entry point, compared with the oracle in full."""
-    if True:
-        M = int(rng.choice(worker_counts))
-        grid_x = int(rng.choice([0] + [x for x in range(1, M + 1) if M % x == 0]))
-        kind = str(rng.choice(KINDS))
-        if kind == "pipe" and M > 16:
-            kind = "ring"
-        d = int(rng.choice([rng.integers(1, 300), rng.integers(300, 70_000), 64 * int(rng.integers(1, 400)),
-                            256 * int(rng.integers(1, 200))]))
-        if M > 32:
-            d = min(d, 20_000)
-        ld = d + int(rng.choice([0, 0, 1, 3, 4, 8]))
-        off = int(rng.choice([0, 0, 0, 1, 2]))
-        scale = float(rng.choice([1e-3, 0.5, -2.0, 1e-30]))
-        seed = int(rng.integers(0, 2**63))
-        case = f"{label} kind={kind} M={M} grid_x={grid_x} d={d} ld={ld} off={off} scale={scale} seed={seed}"
-        print(case, flush=True)
+    M = int(rng.choice(worker_counts))
+    grid_x = int(rng.choice([0] + [x for x in range(1, M + 1) if M % x == 0]))
+    kind = str(rng.choice(KINDS))
+    if kind == "pipe" and M > 16:
+        kind = "ring"
+    d = int(rng.choice([rng.integers(1, 300), rng.integers(300, 70_000), 64 * int(rng.integers(1, 400)),
+                        256 * int(rng.integers(1, 200))]))
+    if M > 32:
+        d = min(d, 20_000)
+    ld = d + int(rng.choice([0, 0, 1, 3, 4, 8]))
+    off = int(rng.choice([0, 0, 0, 1, 2]))
+    scale = float(rng.choice([1e-3, 0.5, -2.0, 1e-30]))
+    seed = int(rng.integers(0, 2**63))
+    case = f"{label} kind={kind} M={M} grid_x={grid_x} d={d} ld={ld} off={off} scale={scale} seed={seed}"
+    print(case, flush=True)
 
-        g_h = rng.standard_normal((M, ld)).astype(np.float32)
-        c_h = (0.3 * rng.standard_normal((M, ld))).astype(np.float32)
-        if rng.random() < 0.2:
-            k = min(d, SPECIAL.size)
-            g_h[:, :k] = SPECIAL[:k]
-            c_h[:, :k] = 0.0
-        x_h = rng.standard_normal(d).astype(np.float32)
-        g_d, c_d = _place(g_h, off), _place(c_h, off)
-        u_d = torch.full((d + 8,), 7.0, dtype=torch.float32, device="cuda")[off:off + d]
-        b_d = marsit.new_bitmap(d).fill_(-1)
-        x_d = _place(x_h, off)
+    g_h = rng.standard_normal((M, ld)).astype(np.float32)
+    c_h = (0.3 * rng.standard_normal((M, ld))).astype(np.float32)
+    if rng.random() < 0.2:
+        k = min(d, SPECIAL.size)
+        g_h[:, :k] = SPECIAL[:k]
+        c_h[:, :k] = 0.0
+    x_h = rng.standard_normal(d).astype(np.float32)
+    g_d, c_d = _place(g_h, off), _place(c_h, off)
+    u_d = torch.full((d + 8,), 7.0, dtype=torch.float32, device="cuda")[off:off + d]
+    b_d = marsit.new_bitmap(d).fill_(-1)
+    x_d = _place(x_h, off)
 
-        c_ref = c_h.copy()
-        if kind in ("full", "apply_full"):
-            # the full-precision round: mean of the compensated gradients, compensation cleared
-            want_u = orc.full_sync(g_h, c_ref, d=d)
-            if kind == "full":
-                marsit.marsit_full_sync(g_d, c_d, u_d, d=d)
-            else:
-                marsit.marsit_step_apply(0, 3, g_d, c_d, x_d, u_d, b_d, scale, seed, grid_x=grid_x, d=d)
-            torch.cuda.synchronize()
-            assert np.array_equal(u_d.cpu().numpy().view(np.uint32), want_u.view(np.uint32)), case
-            got_c = c_d.cpu().numpy()
-            assert not got_c[:, :d].any() and np.array_equal(got_c[:, d:].view(np.uint32), c_h[:, d:].view(np.uint32)), case
-            assert bool((b_d == -1).all()), case                  # the bitmap is left alone
-            if kind == "apply_full":
-                want_x = orc.apply_update(x_h.copy(), want_u)
-                assert np.array_equal(x_d.cpu().numpy().view(np.uint32), want_x.view(np.uint32)), case
-            return
-        if kind in ("ragged", "ragged_apply"):
-            grid_x = int(rng.integers(1, M + 1))                       # any width, dividing or not
-            case += f" ragged_grid_x={grid_x}"
-            want_u, want_b = orc.ragged_torus_step(g_h, c_ref, scale, seed, grid_x, d=d, threads=8)
-            if kind == "ragged":
-                marsit.marsit_ragged_torus_step_sim(g_d, c_d, u_d, b_d, scale, seed, grid_x, d=d)
-            else:
-                marsit.marsit_ragged_torus_step_apply(g_d, c_d, x_d, u_d, b_d, scale, seed, grid_x, d=d)
-        elif kind in ("tree", "tree_apply"):
-            want_u, want_b = orc.tree_step(g_h, c_ref, scale, seed, d=d)
-            if kind == "tree":
-                marsit.marsit_tree_step_sim(g_d, c_d, u_d, b_d, scale, seed, d=d)
-            else:
-                marsit.marsit_tree_step_apply(g_d, c_d, x_d, u_d, b_d, scale, seed, d=d)
+    c_ref = c_h.copy()
+    if kind in ("full", "apply_full"):
+        # the full-precision round: mean of the compensated gradients, compensation cleared
+        want_u = orc.full_sync(g_h, c_ref, d=d)
+        if kind == "full":
+            marsit.marsit_full_sync(g_d, c_d, u_d, d=d)
         else:
-            want_u, want_b, _ = orc.sync_step(g_h, c_ref, scale, seed, grid_x=grid_x, d=d, threads=8)
-            if kind == "ring":
-                marsit.marsit_ring_step_sim(g_d, c_d, u_d, b_d, scale, seed, grid_x=grid_x, d=d)
-            elif kind == "apply":
-                marsit.marsit_step_apply(1, 2, g_d, c_d, x_d, u_d, b_d, scale, seed, grid_x=grid_x, d=d)
-            elif kind == "pipe":
-                with marsit.RingPipeline(M) as pipe:
-                    ws = torch.empty(max(1, pipe.workspace_words(d, grid_x)), dtype=torch.int64, device="cuda")
-                    pipe.step(g_d, c_d, u_d, b_d, ws, scale, seed, grid_x=grid_x, d=d)
-                    torch.cuda.synchronize()
-            else:
-                ws = torch.empty(max(1, marsit.marsit_chain_workspace_words(M, d, grid_x)), dtype=torch.int64,
-                                 device="cuda")
-                step = marsit.marsit_exchange_step_sim if kind == "exchange" else marsit.marsit_chain_step_sim
-                step(g_d, c_d, u_d, b_d, ws, scale, seed, grid_x=grid_x, d=d)
+            marsit.marsit_step_apply(0, 3, g_d, c_d, x_d, u_d, b_d, scale, seed, grid_x=grid_x, d=d)
         torch.cuda.synchronize()
-
-        assert np.array_equal(b_d.cpu().numpy().view(np.uint64), want_b), case
         assert np.array_equal(u_d.cpu().numpy().view(np.uint32), want_u.view(np.uint32)), case
         got_c = c_d.cpu().numpy()
-        assert np.array_equal(got_c[:, :d].view(np.uint32), c_ref[:, :d].view(np.uint32)), case
-        assert np.array_equal(got_c[:, d:].view(np.uint32), c_h[:, d:].view(np.uint32)), case     # padding untouched
-        if kind in ("apply", "tree_apply", "ragged_apply"):
+        assert not got_c[:, :d].any() and np.array_equal(got_c[:, d:].view(np.uint32), c_h[:, d:].view(np.uint32)), case
+        assert bool((b_d == -1).all()), case                  # the bitmap is left alone
+        if kind == "apply_full":
             want_x = orc.apply_update(x_h.copy(), want_u)
             assert np.array_equal(x_d.cpu().numpy().view(np.uint32), want_x.view(np.uint32)), case
+        return
+    if kind in ("ragged", "ragged_apply"):
+        grid_x = int(rng.integers(1, M + 1))                       # any width, dividing or not
+        case += f" ragged_grid_x={grid_x}"
+        want_u, want_b = orc.ragged_torus_step(g_h, c_ref, scale, seed, grid_x, d=d, threads=8)
+        if kind == "ragged":
+            marsit.marsit_ragged_torus_step_sim(g_d, c_d, u_d, b_d, scale, seed, grid_x, d=d)
+        else:
+            marsit.marsit_ragged_torus_step_apply(g_d, c_d, x_d, u_d, b_d, scale, seed, grid_x, d=d)
+    elif kind in ("tree", "tree_apply"):
+        want_u, want_b = orc.tree_step(g_h, c_ref, scale, seed, d=d)
+        if kind == "tree":
+            marsit.marsit_tree_step_sim(g_d, c_d, u_d, b_d, scale, seed, d=d)
+        else:
+            marsit.marsit_tree_step_apply(g_d, c_d, x_d, u_d, b_d, scale, seed, d=d)
+    else:
+        want_u, want_b, _ = orc.sync_step(g_h, c_ref, scale, seed, grid_x=grid_x, d=d, threads=8)
+        if kind == "ring":
+            marsit.marsit_ring_step_sim(g_d, c_d, u_d, b_d, scale, seed, grid_x=grid_x, d=d)
+        elif kind == "apply":
+            marsit.marsit_step_apply(1, 2, g_d, c_d, x_d, u_d, b_d, scale, seed, grid_x=grid_x, d=d)
+        elif kind == "pipe":
+            with marsit.RingPipeline(M) as pipe:
+                ws = torch.empty(max(1, pipe.workspace_words(d, grid_x)), dtype=torch.int64, device="cuda")
+                pipe.step(g_d, c_d, u_d, b_d, ws, scale, seed, grid_x=grid_x, d=d)
+                torch.cuda.synchronize()
+        else:
+            ws = torch.empty(max(1, marsit.marsit_chain_workspace_words(M, d, grid_x)), dtype=torch.int64,
+                             device="cuda")
+            step = marsit.marsit_exchange_step_sim if kind == "exchange" else marsit.marsit_chain_step_sim
+            step(g_d, c_d, u_d, b_d, ws, scale, seed, grid_x=grid_x, d=d)
+    torch.cuda.synchronize()
+
+    assert np.array_equal(b_d.cpu().numpy().view(np.uint64), want_b), case
+    assert np.array_equal(u_d.cpu().numpy().view(np.uint32), want_u.view(np.uint32)), case
+    got_c = c_d.cpu().numpy()
+    assert np.array_equal(got_c[:, :d].view(np.uint32), c_ref[:, :d].view(np.uint32)), case
+    assert np.array_equal(got_c[:, d:].view(np.uint32), c_h[:, d:].view(np.uint32)), case     # padding untouched
+    if kind in ("apply", "tree_apply", "ragged_apply"):
+        want_x = orc.apply_update(x_h.copy(), want_u)
+        assert np.array_equal(x_d.cpu().numpy().view(np.uint32), want_x.view(np.uint32)), case
