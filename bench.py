@@ -13,6 +13,7 @@ d = 25.6 M, ring).  The switches --entry, --M, --d, --grid-x and --ld-pad time t
 whole-pass entry points, other worker counts and schedules (those without a compiled
 specialisation run the any-schedule kernel) and rows that do not start on 128-byte lines;
 they exist so that every figure quoted for those kernels comes from this file.
+--split-workers is a probe of the memory system (the rows taken as separate synchronisations).
 """
 
 from __future__ import annotations
@@ -50,6 +51,11 @@ def parse_args():
     ap.add_argument("--fused-waves", type=int, default=0,
                     help="force this many one-wavefront workgroups per CU for the compiled fused kernels "
                          "(tuning hook marsit_set_fused_waves_per_cu; 0: the library's choice)")
+    ap.add_argument("--split-workers", type=int, default=1,
+                    help="memory-system probe: take the M workers as this many separate synchronisations of "
+                         "M / N workers each, one launch after the other over row blocks of the same arrays "
+                         "(NOT the result of one synchronisation of M workers; ring_step_sim and full_sync only). "
+                         "Shows what the pass would cost with only M / N workers' streams open at a time")
     ap.add_argument("--per-launch-events", action="store_true",
                     help="record a HIP event after every timed step (per-launch min / median / max in the JSON) "
                          "instead of only before the first and after the last one; the extra records cost "
@@ -172,7 +178,12 @@ def main():
     if entry == "tree_step_sim" and wl.grid_x:
         wl = dataclasses.replace(wl, grid_x=0)
     M, d, ld = wl.M, wl.d, wl.d + args.ld_pad
-    headline = entry == "ring_step_sim" and not custom and args.ld_pad == 0 and not args.fused_waves
+    headline = (entry == "ring_step_sim" and not custom and args.ld_pad == 0 and not args.fused_waves
+                and args.split_workers == 1)
+    split = args.split_workers
+    if split != 1 and (split < 1 or M % split or wl.grid_x or entry not in ("ring_step_sim", "full_sync")):
+        print("bench.py: --split-workers must divide M and goes with a ring or the full-precision round", file=sys.stderr)
+        sys.exit(2)
     K, Wm = args.steps, args.warmup
     total = K + Wm
     pool = args.pool if args.pool > 0 else total
@@ -188,7 +199,15 @@ def main():
 
     def step(t):
         g, seed = grads[t % pool], workloads.step_seed(args.seed, t)
-        if entry == "ring_step_sim":
+        if split > 1:
+            rows = M // split
+            for k in range(split):
+                gk, ck = g[k * rows:(k + 1) * rows], c[k * rows:(k + 1) * rows]
+                if entry == "ring_step_sim":
+                    marsit.marsit_ring_step_sim(gk, ck, update, bits, wl.scale, seed, d=d, stream=stream)
+                else:
+                    marsit.marsit_full_sync(gk, ck, update, d=d, stream=stream)
+        elif entry == "ring_step_sim":
             marsit.marsit_ring_step_sim(g, c, update, bits, wl.scale, seed, grid_x=wl.grid_x, d=d, stream=stream)
         elif entry == "tree_step_sim":
             marsit.marsit_tree_step_sim(g, c, update, bits, wl.scale, seed, d=d, stream=stream)
@@ -226,13 +245,14 @@ def main():
     per_launch_ms = [events[i].elapsed_time(events[i + 1]) / every for i in range(K // every)]
     avg_kernel_ms = sum(per_launch_ms) / len(per_launch_ms)
     ms_per_step = wall * 1e3 / K
-    nbytes = algorithmic_bytes(entry, M, d)
+    nbytes = algorithmic_bytes(entry, M, d) if split == 1 else split * algorithmic_bytes(entry, M // split, d)
     value = nbytes / (ms_per_step * 1e-3) / 1e9
     achieved = nbytes / (avg_kernel_ms * 1e-3) / 1e9
     schedule = "tree" if entry == "tree_step_sim" else ("ring" if not wl.grid_x or wl.grid_x == M else
                                                         f"torus {wl.grid_x} columns x {-(-M // wl.grid_x)} rows")
     key = f"entry={entry} M={M} d={d} grid_x={wl.grid_x} ld_pad={args.ld_pad}" + (
-        f" fused_waves={args.fused_waves}" if args.fused_waves else "")
+        f" fused_waves={args.fused_waves}" if args.fused_waves else "") + (
+        f" split_workers={split}" if split > 1 else "")
     traffic, traffic_source = measured_traffic(key)
 
     out = {
@@ -244,7 +264,9 @@ def main():
                                f"{wl.dist} gradients, compensation carried over steps, one seed per step",
                    "entry_point": "marsit_" + entry, "M": M, "d": d, "ld": ld, "grid_x": wl.grid_x,
                    "scale": wl.scale, "gradient_sets_in_hbm": pool,
-                   **({"fused_waves_per_cu": args.fused_waves} if args.fused_waves else {})},
+                   **({"fused_waves_per_cu": args.fused_waves} if args.fused_waves else {}),
+                   **({"split_workers": split, "note": "probe: separate synchronisations of M / split workers each, "
+                       "launches_timed counts steps of `split` launches"} if split > 1 else {})},
         "worker_elements_per_s": M * d / (ms_per_step * 1e-3),
         "elements_per_s": d / (ms_per_step * 1e-3),
         "algorithmic_bytes_per_step": nbytes,
