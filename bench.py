@@ -32,6 +32,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, vendor figure
+# Integer vector peak for the kernels that only draw: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz 32-bit
+# lane operations per second; one Philox4x32-10 call is at least 60 of them (per round the two
+# 32 x 32 -> 64-bit products are four multiply instructions, plus two three-input XORs).
+PHILOX_PEAK_CALLS_PER_S = 256 * 4 * 16 * 2.4e9 / 60
 
 ENTRIES = ("ring_step_sim", "tree_step_sim", "ragged_torus_step_sim", "full_sync", "step_apply")
 
@@ -455,11 +459,15 @@ def other_entry_points(torch, marsit, workloads, wl, grads, update, bits, stream
                                                  stream=stream), reps=20, warm=4)
     aux["marsit_hop_merge_whole_bitmap"] = entry(ms, 24 * W, bound="alu", philox_calls=16 * W,
                                                  philox_calls_per_s=16 * W / (ms * 1e-3),
+                                                 alu_peak_calls_per_s=PHILOX_PEAK_CALLS_PER_S,
+                                                 frac_of_alu_peak=16 * W / (ms * 1e-3) / PHILOX_PEAK_CALLS_PER_S,
                                                  note="operands are 3.2 MB bitmaps: cache resident by nature")
     ms = timed(lambda i: marsit.marsit_fold_segments(maps, M, i % M, whole, 0, W, 0, seed0 + i, stream=stream),
                reps=20, warm=4)
     aux["marsit_fold_segments_whole_bitmap"] = entry(ms, 8 * (M + 1) * W, bound="alu", philox_calls=16 * (M - 1) * W,
                                                      philox_calls_per_s=16 * (M - 1) * W / (ms * 1e-3),
+                                                     alu_peak_calls_per_s=PHILOX_PEAK_CALLS_PER_S,
+                                                     frac_of_alu_peak=16 * (M - 1) * W / (ms * 1e-3) / PHILOX_PEAK_CALLS_PER_S,
                                                      note=f"the {M - 1}-hop chain of all {W} words in one launch")
     del full_recv, recv, whole, upds, maps
 
