@@ -10,6 +10,11 @@
  *     (a hipStream_t passed as void*; NULL is the default stream) and the call returns at once.
  *     Apart from the marsit_pipeline_* calls an entry point only launches kernels on `stream`, so
  *     it may be recorded into a HIP graph; scalar arguments (seed, t, scale) are then fixed in it.
+ *   - Host threads: the library keeps no mutable state between calls (the error slots below are per
+ *     thread), so threads may call it at the same time on their own streams and buffers.  The
+ *     exceptions are stated where they apply: one marsit_pipeline object is used by one thread at
+ *     a time, marsit_exchange_step_sim_static shares one workspace per GPU, and
+ *     marsit_set_fused_waves_per_cu changes a process-wide setting.
  *   - fp32 vectors are plain arrays of IEEE-754 binary32.  Arithmetic is fp32 with one
  *     round-to-nearest-even operation per step of Algorithm 1; denormals are kept.
  *   - Sign bitmaps: 64-bit words; element e sits in word e/64 at bit e%64 (least significant

@@ -315,6 +315,49 @@ def test_runs_on_a_side_stream():
     assert np.array_equal(host_bits(b), want_b) and np.array_equal(host_f32(u), want_u)
 
 
+def test_host_threads_on_their_own_streams():
+    """Four host threads, each with its own stream and buffers, run carried steps of different
+    shapes at the same time (the library keeps no mutable state between calls; its error slot is per
+    thread).  Every thread's results equal the oracle's for its inputs."""
+    import threading
+    shapes = [(8, 0, 200_000), (16, 4, 90_001), (20, 0, 30_000), (5, 0, 123_457)]
+    steps = 6
+    work = []
+    for k, (M, grid_x, d) in enumerate(shapes):
+        g_h, c_h = _inputs(M, d, seed=100 + k)
+        work.append({"M": M, "grid_x": grid_x, "d": d, "g_h": g_h, "c_h": c_h, "g": dev(g_h), "c": dev(c_h),
+                     "u": [torch.empty(d, device="cuda") for _ in range(steps)],
+                     "b": [marsit.new_bitmap(d) for _ in range(steps)], "stream": torch.cuda.Stream(), "error": None})
+    torch.cuda.synchronize()
+    print("threads:", [(w["M"], w["grid_x"], w["d"]) for w in work], flush=True)
+
+    def run(w):
+        try:
+            for t in range(steps):
+                marsit.marsit_ring_step_sim(w["g"], w["c"], w["u"][t], w["b"][t], 1e-3, 500 + t, grid_x=w["grid_x"],
+                                            stream=w["stream"])
+            w["stream"].synchronize()
+        except Exception as exc:        # reported by the main thread
+            w["error"] = exc
+
+    threads = [threading.Thread(target=run, args=(w,)) for w in work]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join(timeout=100)
+        assert not th.is_alive(), "a worker thread did not finish"
+    torch.cuda.synchronize()
+    for w in work:
+        assert w["error"] is None, w["error"]
+        c_ref = w["c_h"].copy()
+        for t in range(steps):
+            want_u, want_b, _ = oracle_step(w["g_h"], c_ref, 1e-3, 500 + t, grid_x=w["grid_x"])
+            what = f"M={w['M']} grid_x={w['grid_x']} d={w['d']} step {t}"
+            assert np.array_equal(host_bits(w["b"][t]), want_b), what
+            assert np.array_equal(host_f32(w["u"][t]).view(np.uint32), want_u.view(np.uint32)), what
+        assert np.array_equal(host_f32(w["c"]).view(np.uint32), c_ref.view(np.uint32)), f"compensation, M={w['M']}"
+
+
 # ------------------------------------------------------------------------------------------------
 # fused pass == chain of the un-fused entry points (bit for bit), moderate sizes
 # ------------------------------------------------------------------------------------------------
