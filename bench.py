@@ -303,9 +303,27 @@ def main():
             chain(2 + t)
         torch.cuda.synchronize()
         chain_ms = (time.perf_counter() - t0) * 1e3 / n_chain
+
+        def replayed_ms(call):
+            """The step recorded once into a HIP graph; ms per replay (no host code between launches)."""
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                call(torch.cuda.current_stream())
+            for _ in range(2):
+                graph.replay()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(n_chain):
+                graph.replay()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / n_chain
+
         out["unfused_chain"] = {"ms_per_step": chain_ms, "value": nbytes / (chain_ms * 1e-3) / 1e9,
                                 "unit": "GB/s (same algorithmic bytes)", "steps": n_chain,
-                                "launches_per_step": 2 * M + M * (M - 1) + M}
+                                "launches_per_step": 2 * M + M * (M - 1) + M,
+                                "ms_per_step_in_a_graph": replayed_ms(lambda st: marsit.marsit_chain_step_sim(
+                                    grads[0], c2, update, bits, ws, wl.scale, workloads.step_seed(args.seed, 0),
+                                    grid_x=wl.grid_x, d=d, stream=st))}
 
         # the same pass as ONE exchange step: M compress, one fold per part, M decodes
         def exchange(t):
@@ -323,7 +341,10 @@ def main():
         out["unfused_exchange_step"] = {
             "ms_per_step": ex_ms, "value": nbytes / (ex_ms * 1e-3) / 1e9,
             "unit": "GB/s (same algorithmic bytes)", "steps": n_chain,
-            "launches_per_step": 2 * M + M + (M if M // Xb > 1 else 0)}
+            "launches_per_step": 2 * M + M + (M if M // Xb > 1 else 0),
+            "ms_per_step_in_a_graph": replayed_ms(lambda st: marsit.marsit_exchange_step_sim(
+                grads[0], c2, update, bits, ws, wl.scale, workloads.step_seed(args.seed, 0), grid_x=wl.grid_x, d=d,
+                stream=st))}
         del ws, c2
 
     if not args.no_aux and entry == "ring_step_sim" and args.ld_pad == 0:
@@ -357,6 +378,25 @@ def other_entry_points(torch, marsit, workloads, wl, grads, update, bits, stream
         ev1.record(stream)
         torch.cuda.synchronize()
         return ev0.elapsed_time(ev1) / reps
+
+    def graph_us_per_launch(fn, n=40, replays=10):
+        """fn(i, stream) recorded n times into one HIP graph; microseconds per launch over replays of it
+        (what a hop costs when no host code runs between the launches)."""
+        graph = torch.cuda.CUDAGraph()
+        fn(0, stream)                                   # first use outside the capture
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph):
+            for i in range(n):
+                fn(i, torch.cuda.current_stream())
+        for _ in range(3):
+            graph.replay()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record(stream)
+        for _ in range(replays):
+            graph.replay()
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        return ev0.elapsed_time(ev1) * 1e3 / (replays * n)
 
     def entry(ms, nb, **extra):
         e = {"ms": ms, "GB/s": nb / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
@@ -440,6 +480,13 @@ def other_entry_points(torch, marsit, workloads, wl, grads, update, bits, stream
     aux["marsit_compress_hop_merge"]["note"] = (
         f"one part of {n_part} elements ({8 * seg} B message) per launch: launch-bound at this size")
 
+    def g_chm(i, st):
+        g, m = row(i)
+        lo = (i % M) * n_part
+        marsit.marsit_compress_hop_merge(recv[m], g[lo:lo + n_part], c3[m][lo:lo + n_part], recv[m],
+                                         (i % M) * seg, 3, 2, seed0, stream=st)
+    aux["marsit_compress_hop_merge"]["us_per_launch_in_a_graph"] = graph_us_per_launch(g_chm)
+
     # the same kernel over a whole vector (fold of a whole bitmap), where HBM is the bound
     full_recv = torch.zeros((M, W), dtype=torch.int64, device="cuda")
 
@@ -452,6 +499,8 @@ def other_entry_points(torch, marsit, workloads, wl, grads, update, bits, stream
     aux["marsit_hop_merge"] = entry(timed(lambda i: marsit.marsit_hop_merge(
         recv[i % M], maps[i % M][:seg], recv[i % M], 0, seg, 3, 2, seed0, stream=stream)), 24 * seg)
     aux["marsit_hop_merge"].update(
+        us_per_launch_in_a_graph=graph_us_per_launch(lambda i, st: marsit.marsit_hop_merge(
+            recv[i % M], maps[i % M][:seg], recv[i % M], 0, seg, 3, 2, seed0, stream=st)),
         note=f"one part of {seg} packed words ({8 * seg} B message): launch-bound",
         bound="launch latency at this size; integer ALU (Philox) on large inputs, see the whole-bitmap rows")
     whole = torch.empty(W, dtype=torch.int64, device="cuda")
