@@ -534,6 +534,18 @@ def other_entry_points(torch, marsit, workloads, wl, grads, update, bits, stream
         "hop_steps": X + (Y - 1) + 1,
         "note": f"1 compress+send step, {X - 1} row hops (sign step fused into the merge), {Y - 1} column hops, 1 decode step; "
                 f"row segments of {8 * ((d // 64) // X)} B"}
+
+    # context, not product: PyTorch's own elementwise kernels on arrays of one gradient set's size
+    # (rows of the same tensors, so nothing new is allocated but the output)
+    if pool >= 2:
+        a_flat, b_flat = grads[0].view(-1), grads[1].view(-1)
+        out_flat = c3.view(-1)
+        n = out_flat.numel()
+        ms_add = timed(lambda i: torch.add(a_flat, b_flat, out=out_flat))
+        ms_copy = timed(lambda i: out_flat.copy_(a_flat if i % 2 else b_flat))
+        aux["context_torch_elementwise"] = {
+            "note": "PyTorch's library kernels on the same box, for scale; not part of the path",
+            "add_2_reads_1_write": entry(ms_add, 12 * n), "copy_1_read_1_write": entry(ms_copy, 8 * n)}
     return aux
 
 
