@@ -306,17 +306,20 @@ def main():
 
         def replayed_ms(call):
             """The step recorded once into a HIP graph; ms per replay (no host code between launches)."""
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph):
-                call(torch.cuda.current_stream())
-            for _ in range(2):
-                graph.replay()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(n_chain):
-                graph.replay()
-            torch.cuda.synchronize()
-            return (time.perf_counter() - t0) * 1e3 / n_chain
+            try:
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph):
+                    call(torch.cuda.current_stream())
+                for _ in range(2):
+                    graph.replay()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(n_chain):
+                    graph.replay()
+                torch.cuda.synchronize()
+                return (time.perf_counter() - t0) * 1e3 / n_chain
+            except Exception as exc:        # an extra figure must not cost the line
+                return f"not measured: {type(exc).__name__}: {exc}"[:200]
 
         out["unfused_chain"] = {"ms_per_step": chain_ms, "value": nbytes / (chain_ms * 1e-3) / 1e9,
                                 "unit": "GB/s (same algorithmic bytes)", "steps": n_chain,
@@ -348,8 +351,11 @@ def main():
         del ws, c2
 
     if not args.no_aux and entry == "ring_step_sim" and args.ld_pad == 0:
-        out["other_entry_points"] = other_entry_points(torch, marsit, workloads, wl, grads, update, bits,
-                                                       stream, args.seed, nbytes)
+        try:
+            out["other_entry_points"] = other_entry_points(torch, marsit, workloads, wl, grads, update, bits,
+                                                           stream, args.seed, nbytes)
+        except Exception as exc:            # the headline figures above stand on their own
+            out["other_entry_points"] = {"error": f"{type(exc).__name__}: {exc}"[:300]}
 
     if not args.no_cpu_baseline and entry == "ring_step_sim":
         threads = args.cpu_threads or min(16, os.cpu_count() or 1)
@@ -382,21 +388,24 @@ def other_entry_points(torch, marsit, workloads, wl, grads, update, bits, stream
     def graph_us_per_launch(fn, n=40, replays=10):
         """fn(i, stream) recorded n times into one HIP graph; microseconds per launch over replays of it
         (what a hop costs when no host code runs between the launches)."""
-        graph = torch.cuda.CUDAGraph()
-        fn(0, stream)                                   # first use outside the capture
-        torch.cuda.synchronize()
-        with torch.cuda.graph(graph):
-            for i in range(n):
-                fn(i, torch.cuda.current_stream())
-        for _ in range(3):
-            graph.replay()
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        ev0.record(stream)
-        for _ in range(replays):
-            graph.replay()
-        ev1.record(stream)
-        torch.cuda.synchronize()
-        return ev0.elapsed_time(ev1) * 1e3 / (replays * n)
+        try:
+            graph = torch.cuda.CUDAGraph()
+            fn(0, stream)                                   # first use outside the capture
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph):
+                for i in range(n):
+                    fn(i, torch.cuda.current_stream())
+            for _ in range(3):
+                graph.replay()
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record(stream)
+            for _ in range(replays):
+                graph.replay()
+            ev1.record(stream)
+            torch.cuda.synchronize()
+            return ev0.elapsed_time(ev1) * 1e3 / (replays * n)
+        except Exception as exc:            # an extra figure must not cost the line
+            return f"not measured: {type(exc).__name__}: {exc}"[:200]
 
     def entry(ms, nb, **extra):
         e = {"ms": ms, "GB/s": nb / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nb / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
