@@ -60,8 +60,42 @@ def run_case(M, d, grid_x, scale, seed, steps):
     return out
 
 
+# The other rounds and schedules: name, kind, M, d, parameter (ragged: columns of the torus), steps
+EXTRA = [
+    ("ragged_torus_M13_x4_d9001", "ragged", 13, 9_001, 4, 2),
+    ("ragged_torus_M7_x3_d640", "ragged", 7, 640, 3, 2),
+    ("full_precision_M5_d5003", "full", 5, 5_003, 0, 2),
+    ("local_adam_M3_d4099", "adam", 3, 4_099, 0, 3),
+    ("local_momentum_M3_d4099", "momentum", 3, 4_099, 0, 3),
+]
+
+
+def run_extra(kind, M, d, param, steps):
+    c = np.zeros((M, d), dtype=np.float32)
+    state1 = np.zeros((M, d), dtype=np.float32)
+    state2 = np.zeros((M, d), dtype=np.float32)
+    out = []
+    for t in range(steps):
+        g = inputs(M, d, t)
+        if kind == "ragged":
+            update, bits = orc.ragged_torus_step(g, c, 1e-3, 31 + t, param, d=d)
+            out.append({"bits": digest(bits), "update": digest(update), "c": digest(c)})
+        elif kind == "full":
+            c += inputs(M, d, 100 + t) * np.float32(0.25)              # a non-zero compensation to fold in
+            update = orc.full_sync(g, c, d=d)
+            out.append({"update": digest(update), "c": digest(c)})
+        elif kind == "adam":
+            step = orc.local_adam(state1, state2, g, 0.9, 0.999, 1e-8, 0.01, 1.0 - 0.9 ** (t + 1), 1.0 - 0.999 ** (t + 1))
+            out.append({"step": digest(step), "mom1": digest(state1), "mom2": digest(state2)})
+        else:
+            step = orc.local_momentum(state1, g, 0.9, 0.05)
+            out.append({"step": digest(step), "buf": digest(state1)})
+    return out
+
+
 def main():
     table = {name: run_case(M, d, gx, scale, seed, steps) for name, M, d, gx, scale, seed, steps in CASES}
+    table.update({name: run_extra(kind, M, d, param, steps) for name, kind, M, d, param, steps in EXTRA})
     path = os.path.join(HERE, "oracle_digests.json")
     with open(path, "w") as fh:
         json.dump(table, fh, indent=1, sort_keys=True)
