@@ -110,7 +110,7 @@ def cpu_baseline(wl, g_host, seed, threads):
     import numpy as np
     from oracle import marsit_oracle as orc
     c_host = np.zeros_like(g_host)
-    n_steps = max(1, min(wl.steps, 8))          # about 10 s on 16 cores at the headline size
+    n_steps = max(1, min(wl.steps, 10))         # about 12 s on 16 cores at the headline size
     t0 = time.perf_counter()
     for t in range(n_steps):                    # the same gradients again, compensation carried over
         orc.sync_step(g_host, c_host, wl.scale, seed + t, grid_x=wl.grid_x, threads=threads)
