@@ -23,7 +23,7 @@
  *     fp32 pointers 4-byte aligned (MARSIT_EALIGN otherwise).  That is all the 128-bit accesses of
  *     the kernels need; but rows that start on 128-byte boundaries (128-byte aligned bases, row
  *     stride ld a multiple of 32 elements) are faster, because a wavefront's 1 KB access then
- *     covers 8 whole cache lines instead of straddling 9 (78-80 % against 70-74 % of the HBM peak
+ *     covers 8 whole cache lines instead of straddling 9 (77-80 % against 69-74 % of the HBM peak
  *     for the fused pass): a caller that owns the layout should pad ld to a multiple of 32.
  *   - Random merge masks: counter-based Philox4x32-10.  The 32-bit word that decides bit j of
  *     packed word w at hop id h is output (j mod 4) of Philox with key = (seed low, seed high) and
